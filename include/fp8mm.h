@@ -1,0 +1,139 @@
+/*
+ * fp8mm.h -- C ABI of the MI355X (gfx950) scaled-FP8 matrix multiply library.
+ *
+ * The library implements, as hand-written HIP kernels, the per-tensor-scaled FP8
+ * path of "FP8 Formats for Deep Learning" (arXiv 2209.05433):
+ *
+ *     amax  ->  scale  ->  cast to E4M3 / E5M2  ->  FP8 x FP8 GEMM (fp32 accumulate)
+ *           ->  unscale epilogue to fp32 / bf16
+ *
+ * General rules for every entry point
+ *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns
+ *     every buffer; the library allocates no device memory and keeps no state
+ *     besides the thread-local error string.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it; no entry point synchronises the stream or the device.
+ *   - The return value is an fp8_status_t.  On anything but FP8_OK nothing was
+ *     launched and no output was written; fp8_last_error() describes the reason.
+ *   - Tensors are dense and contiguous.  Matrices are row-major.
+ *   - bfloat16 data is the upper 16 bits of an IEEE single (uint16_t storage).
+ */
+#ifndef FP8MM_H
+#define FP8MM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The two 8-bit encodings (Section 3, Table 1): sign.exponent.mantissa =
+ * 1.4.3 with bias 7, no infinities, one NaN pattern per sign, max 448 (E4M3);
+ * 1.5.2 with bias 15, IEEE-style inf/NaN, max 57344 (E5M2). */
+typedef enum { FP8_E4M3 = 0, FP8_E5M2 = 1 } fp8_format_t;
+
+/* The wider types FP8 tensors are produced from and GEMM results are written in
+ * (Section 2: FP8 tensors come from wider types; math on FP8 inputs yields
+ * higher-precision outputs). */
+typedef enum { FP8_F32 = 0, FP8_BF16 = 1 } fp8_dtype_t;
+
+typedef enum {
+    FP8_OK = 0,
+    FP8_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, negative size, misalignment */
+    FP8_ERR_UNSUPPORTED = 2,   /* valid request this build has no kernel for */
+    FP8_ERR_DEVICE = 3         /* the HIP runtime reported an error at launch */
+} fp8_status_t;
+
+/*
+ * fp8_amax -- largest magnitude of a tensor (Section 2: the scaling factor is chosen
+ * from the largest magnitude the tensor holds; Section 4.3: one factor per tensor).
+ *   x        n elements of in_dtype (fp8_dtype_t); 4-byte aligned for F32, 2-byte for BF16
+ *   amax_out one float, overwritten (not accumulated)
+ * Any NaN element makes the result NaN; +-inf gives +inf; n == 0 gives 0 (x may be
+ * NULL then).  Implemented with integer comparisons of the magnitude bits, which
+ * order like the values (Section 3.1).
+ */
+int fp8_amax(const void* x, size_t n, int in_dtype, float* amax_out, void* stream);
+
+/*
+ * fp8_scale_from_amax_host / fp8_scale_from_amax -- scale = fmt_max / amax in IEEE
+ * single precision, fmt_max = 448 (E4M3) or 57344 (E5M2) (Section 2: the maximum
+ * magnitude is moved close to the largest representable one; Table 1, Max normal;
+ * Section 3.2: the factor may be any real number, it is not rounded to a power of
+ * two).  If amax is 0, NaN or inf, or the quotient is not finite, the scale is 1.
+ * The device form reads amax[0] and writes scale_out[0] on `stream`.
+ */
+float fp8_scale_from_amax_host(float amax, int fmt);
+int fp8_scale_from_amax(const float* amax, int fmt, float* scale_out, void* stream);
+
+/*
+ * fp8_quantize -- q[i] = FP8(fl32(x[i] * scale)) (Section 2: multiply by the scaling
+ * factor, then cast; overflow saturates; Table 1 for the encodings).
+ *   x      n elements of in_dtype
+ *   fmt    fp8_format_t of the result
+ *   scale  by value (fp8_quantize) or read from device memory (fp8_quantize_dscale,
+ *          which lets amax -> scale -> cast run without a host round trip)
+ *   q_out  n bytes, same element order as x
+ * Rounding is to nearest, ties to the even code.  Finite values beyond the format's
+ * maximum become the maximum; NaN becomes NaN (0x7F | sign); +-inf becomes NaN for
+ * E4M3 and +-inf for E5M2 (Section 2, type conversion).  The sign of the input is
+ * kept, also on results that round to zero.  n == 0 is valid and launches nothing.
+ */
+int fp8_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
+                 uint8_t* q_out, void* stream);
+int fp8_quantize_dscale(const void* x, size_t n, int in_dtype, int fmt,
+                        const float* scale, uint8_t* q_out, void* stream);
+
+/*
+ * fp8_gemm -- C = (1 / (sA * sB)) * (A x B) with FP8 operands, fp32 accumulation
+ * and the unscale applied once per output (Section 2: matrix multiplies on FP8
+ * inputs produce single-precision results; unscaling is done once per dot product;
+ * Section 3: E4M3 for activations and weights, E5M2 for gradients -- all four
+ * operand format combinations are accepted).
+ *   A  M x K bytes, row-major, format fmtA, quantised with scale sA
+ *   B  K x N bytes, row-major, format fmtB, quantised with scale sB
+ *   C  M x N elements of out_dtype (fp32, or bf16 rounded to nearest even), row-major
+ * Every output satisfies |C - C_ref| <= 2^-20 * sum_k |a_ik b_kj| / (sA sB) + ulp/2,
+ * C_ref being the exact product of the decoded operands: the FP8 bytes are widened
+ * exactly to fp16 in registers and multiplied by the fp16 matrix-core instructions,
+ * whose accumulation is fp32-grade.  M, N or K equal to 0 is valid (K == 0 writes
+ * zeros).  Any shape is accepted; shapes with M and N multiples of 256, K a multiple
+ * of 128 and 16-byte aligned pointers take the tiled matrix-core kernel, the others a
+ * plain FMA kernel.  fp8_gemm_dscale reads the two scales from device memory instead.
+ */
+int fp8_gemm(const uint8_t* A, int fmtA, float sA,
+             const uint8_t* B, int fmtB, float sB,
+             void* C, int64_t M, int64_t N, int64_t K, int out_dtype, void* stream);
+int fp8_gemm_dscale(const uint8_t* A, int fmtA, const float* sA,
+                    const uint8_t* B, int fmtB, const float* sB,
+                    void* C, int64_t M, int64_t N, int64_t K, int out_dtype, void* stream);
+
+/*
+ * fp8_gemm_mfma8 -- the same product (same arguments, layouts and error behaviour)
+ * formed by the FP8 matrix-core instructions of gfx950, at twice the peak rate of
+ * fp8_gemm (Section 2 leaves the arithmetic of FP8-input instructions to the
+ * processor).  The hardware adds each run of 8 products after aligning them to the
+ * largest and dropping the bits more than 13 places below its leading bit, so the
+ * guarantee is weaker: |C - C_ref| <= 2^-10 * sum_k |a_ik b_kj| / (sA sB) + ulp/2 in the
+ * worst case, about 2^-17 of that sum for typical tensors.  Products whose runs of 8 span
+ * less than 7 binades are exact, as with fp8_gemm.  Shapes outside the tiled kernel's
+ * (see fp8_gemm) are computed exactly as fp8_gemm does.
+ */
+int fp8_gemm_mfma8(const uint8_t* A, int fmtA, float sA,
+                   const uint8_t* B, int fmtB, float sB,
+                   void* C, int64_t M, int64_t N, int64_t K, int out_dtype, void* stream);
+int fp8_gemm_mfma8_dscale(const uint8_t* A, int fmtA, const float* sA,
+                          const uint8_t* B, int fmtB, const float* sB,
+                          void* C, int64_t M, int64_t N, int64_t K, int out_dtype, void* stream);
+
+/* Text of the last error on the calling thread ("" if none).  Static storage. */
+const char* fp8_last_error(void);
+
+/* Library version string, static storage. */
+const char* fp8_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP8MM_H */

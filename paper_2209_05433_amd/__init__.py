@@ -1,0 +1,15 @@
+"""MI355X-native scaled-FP8 matrix multiply path (amax -> scale -> cast -> FP8 GEMM ->
+unscale) of arXiv 2209.05433, as hand-written HIP kernels behind a C ABI.
+
+The functions re-exported here have the names and argument order of include/fp8mm.h and
+only marshal arguments; the library is loaded on first use and its absence is an error.
+"""
+from .binding import (  # noqa: F401
+    FP8_E4M3, FP8_E5M2, FP8_F32, FP8_BF16,
+    FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE,
+    EXPORTS, LIB_PATH, Fp8Error, lib,
+    fp8_amax, fp8_scale_from_amax_host, fp8_scale_from_amax,
+    fp8_quantize, fp8_quantize_dscale, fp8_gemm, fp8_gemm_dscale,
+    fp8_gemm_mfma8, fp8_gemm_mfma8_dscale,
+    fp8_last_error, fp8_version,
+)

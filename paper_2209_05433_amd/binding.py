@@ -1,0 +1,157 @@
+"""ctypes binding of libfp8mm.so: same names as the C ABI (include/fp8mm.h), argument
+marshalling only.  Tensors are torch tensors used as device buffers; every computation
+happens in the HIP kernels.  There is no fallback: a missing library is an error."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+FP8_E4M3, FP8_E5M2 = 0, 1
+FP8_F32, FP8_BF16 = 0, 1
+FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
+
+EXPORTS = (
+    "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
+    "fp8_quantize_dscale", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
+    "fp8_gemm_mfma8_dscale", "fp8_last_error", "fp8_version",
+)
+
+_lib = None
+
+
+class Fp8Error(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("fp8mm status %d: %s" % (status, message))
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library (build it first: python -m paper_2209_05433_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build the HIP library with __graft_entry__.build() or "
+            "`python paper_2209_05433_amd/build.py`; there is no CPU fallback" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, sz, i, i64, f = c.c_void_p, c.c_size_t, c.c_int, c.c_int64, c.c_float
+    L.fp8_amax.argtypes, L.fp8_amax.restype = [vp, sz, i, vp, vp], i
+    L.fp8_scale_from_amax_host.argtypes, L.fp8_scale_from_amax_host.restype = [f, i], f
+    L.fp8_scale_from_amax.argtypes, L.fp8_scale_from_amax.restype = [vp, i, vp, vp], i
+    L.fp8_quantize.argtypes, L.fp8_quantize.restype = [vp, sz, i, i, f, vp, vp], i
+    L.fp8_quantize_dscale.argtypes, L.fp8_quantize_dscale.restype = [vp, sz, i, i, vp, vp, vp], i
+    L.fp8_gemm.argtypes, L.fp8_gemm.restype = [vp, i, f, vp, i, f, vp, i64, i64, i64, i, vp], i
+    L.fp8_gemm_dscale.argtypes, L.fp8_gemm_dscale.restype = [vp, i, vp, vp, i, vp, vp, i64, i64, i64, i, vp], i
+    L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
+    L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
+    L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
+    L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != FP8_OK:
+        raise Fp8Error(status, lib().fp8_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, what: str) -> int:
+    if not t.is_cuda:
+        raise ValueError("%s must live in device memory" % what)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % what)
+    return t.data_ptr()
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FP8_F32
+    if t.dtype == torch.bfloat16:
+        return FP8_BF16
+    raise TypeError("expected a float32 or bfloat16 tensor, got %s" % t.dtype)
+
+
+def fp8_last_error() -> str:
+    return lib().fp8_last_error().decode()
+
+
+def fp8_version() -> str:
+    return lib().fp8_version().decode()
+
+
+def fp8_amax(x: torch.Tensor, amax_out: torch.Tensor, stream=None) -> None:
+    _check(lib().fp8_amax(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x),
+                          _dev(amax_out, "amax_out"), _stream(stream)))
+
+
+def fp8_scale_from_amax_host(amax: float, fmt: int) -> float:
+    return float(lib().fp8_scale_from_amax_host(float(amax), fmt))
+
+
+def fp8_scale_from_amax(amax: torch.Tensor, fmt: int, scale_out: torch.Tensor, stream=None) -> None:
+    _check(lib().fp8_scale_from_amax(_dev(amax, "amax"), fmt, _dev(scale_out, "scale_out"),
+                                     _stream(stream)))
+
+
+def fp8_quantize(x: torch.Tensor, fmt: int, scale: float, q_out: torch.Tensor, stream=None) -> None:
+    if q_out.dtype != torch.uint8 or q_out.numel() != x.numel():
+        raise ValueError("q_out must be uint8 with as many elements as x")
+    _check(lib().fp8_quantize(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
+                              float(scale), _dev(q_out, "q_out") if x.numel() else None,
+                              _stream(stream)))
+
+
+def fp8_quantize_dscale(x: torch.Tensor, fmt: int, scale: torch.Tensor, q_out: torch.Tensor,
+                        stream=None) -> None:
+    if q_out.dtype != torch.uint8 or q_out.numel() != x.numel():
+        raise ValueError("q_out must be uint8 with as many elements as x")
+    _check(lib().fp8_quantize_dscale(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x),
+                                     fmt, _dev(scale, "scale"),
+                                     _dev(q_out, "q_out") if x.numel() else None, _stream(stream)))
+
+
+def _gemm_dims(A, B, C):
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8 or A.dim() != 2 or B.dim() != 2:
+        raise ValueError("A and B must be 2-D uint8 tensors of FP8 bytes")
+    M, K = A.shape
+    K2, N = B.shape
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not form C[M,N] = A[M,K] B[K,N]")
+    return M, N, K
+
+
+def _gemm(fn, A, fmtA, sA, B, fmtB, sB, C, stream):
+    M, N, K = _gemm_dims(A, B, C)
+    _check(fn(_dev(A, "A") if A.numel() else None, fmtA, sA,
+              _dev(B, "B") if B.numel() else None, fmtB, sB,
+              _dev(C, "C") if C.numel() else None, M, N, K, dtype_code(C), _stream(stream)))
+
+
+def fp8_gemm(A, fmtA: int, sA: float, B, fmtB: int, sB: float, C, stream=None) -> None:
+    _gemm(lib().fp8_gemm, A, fmtA, float(sA), B, fmtB, float(sB), C, stream)
+
+
+def fp8_gemm_dscale(A, fmtA: int, sA: torch.Tensor, B, fmtB: int, sB: torch.Tensor, C,
+                    stream=None) -> None:
+    _gemm(lib().fp8_gemm_dscale, A, fmtA, _dev(sA, "sA"), B, fmtB, _dev(sB, "sB"), C, stream)
+
+
+def fp8_gemm_mfma8(A, fmtA: int, sA: float, B, fmtB: int, sB: float, C, stream=None) -> None:
+    _gemm(lib().fp8_gemm_mfma8, A, fmtA, float(sA), B, fmtB, float(sB), C, stream)
+
+
+def fp8_gemm_mfma8_dscale(A, fmtA: int, sA: torch.Tensor, B, fmtB: int, sB: torch.Tensor, C,
+                          stream=None) -> None:
+    _gemm(lib().fp8_gemm_mfma8_dscale, A, fmtA, _dev(sA, "sA"), B, fmtB, _dev(sB, "sB"), C, stream)

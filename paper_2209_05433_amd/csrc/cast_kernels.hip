@@ -1,0 +1,382 @@
+// amax reduction, scale computation and the FP8 cast for gfx950 (MI355X).
+//
+// All three are HBM-streaming kernels: every lane moves 16-byte vectors, the arithmetic per
+// element is a handful of VALU instructions.  The paper's scheme (arXiv 2209.05433,
+// Section 2) is: find the largest magnitude of the tensor, pick scale = fmt_max / amax,
+// multiply every element by the scale and round it to E4M3 / E5M2 (Table 1) with
+// saturation.
+#include "common.hpp"
+
+namespace fp8mm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxBlocks = 256 * 8;       // 256 compute units, 8 workgroups of 4 waves each
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
+
+// ------------------------------------------------------------------------------------------
+// amax.  Magnitude bits of IEEE numbers order like unsigned integers (Section 3.1 relies on
+// the same property for FP8), NaN patterns sort above infinity, so an unsigned max of the
+// sign-stripped bits is the NaN-propagating amax.  bfloat16 pairs are reduced as packed
+// 16-bit integers.
+// ------------------------------------------------------------------------------------------
+template <int DT> struct Elem;
+template <> struct Elem<FP8_F32>  { static constexpr int size = 4; static constexpr int per_vec = 4; };
+template <> struct Elem<FP8_BF16> { static constexpr int size = 2; static constexpr int per_vec = 8; };
+
+template <int DT>
+__device__ __forceinline__ unsigned vec_mag_max(u32x4 v, unsigned run)
+{
+    if (DT == FP8_F32) {
+        unsigned m0 = v.x & 0x7fffffffu, m1 = v.y & 0x7fffffffu;
+        unsigned m2 = v.z & 0x7fffffffu, m3 = v.w & 0x7fffffffu;
+        m0 = m0 > m1 ? m0 : m1;
+        m2 = m2 > m3 ? m2 : m3;
+        m0 = m0 > m2 ? m0 : m2;
+        return run > m0 ? run : m0;
+    } else {
+        u16x2 r = __builtin_bit_cast(u16x2, run);
+        r = __builtin_elementwise_max(r, __builtin_bit_cast(u16x2, v.x & 0x7fff7fffu));
+        r = __builtin_elementwise_max(r, __builtin_bit_cast(u16x2, v.y & 0x7fff7fffu));
+        r = __builtin_elementwise_max(r, __builtin_bit_cast(u16x2, v.z & 0x7fff7fffu));
+        r = __builtin_elementwise_max(r, __builtin_bit_cast(u16x2, v.w & 0x7fff7fffu));
+        return __builtin_bit_cast(unsigned, r);
+    }
+}
+
+// Magnitude bits of one element, as the bits of an fp32 number.
+template <int DT>
+__device__ __forceinline__ unsigned scalar_mag(const void* x, size_t i)
+{
+    if (DT == FP8_F32) return ((const unsigned*)x)[i] & 0x7fffffffu;
+    return ((unsigned)(((const unsigned short*)x)[i] & 0x7fffu)) << 16;
+}
+
+__device__ __forceinline__ unsigned block_max_u32(unsigned v)
+{
+    __shared__ unsigned part[kThreads / 64];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        unsigned o = __shfl_xor(v, off, 64);
+        v = v > o ? v : o;
+    }
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) v = v > part[w] ? v : part[w];
+    }
+    return v;   // valid in thread 0
+}
+
+__global__ void store_u32_kernel(unsigned* p, unsigned v) { *p = v; }
+
+// Vector path: x is 16-byte aligned.  nvec full vectors, then n - nvec*per_vec tail elements.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restrict__ x, size_t n,
+                                                           unsigned* __restrict__ out_bits)
+{
+    constexpr int PV = Elem<DT>::per_vec;
+    const u32x4* xv = (const u32x4*)x;
+    const size_t nvec = n / PV;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    unsigned r0 = 0, r1 = 0, r2 = 0, r3 = 0;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        u32x4 a = xv[i], b = xv[i + stride], c = xv[i + 2 * stride], d = xv[i + 3 * stride];
+        r0 = vec_mag_max<DT>(a, r0);
+        r1 = vec_mag_max<DT>(b, r1);
+        r2 = vec_mag_max<DT>(c, r2);
+        r3 = vec_mag_max<DT>(d, r3);
+    }
+    for (; i < nvec; i += stride) r0 = vec_mag_max<DT>(xv[i], r0);
+    unsigned r;
+    if (DT == FP8_F32) {
+        r0 = r0 > r1 ? r0 : r1;
+        r2 = r2 > r3 ? r2 : r3;
+        r = r0 > r2 ? r0 : r2;
+    } else {
+        u16x2 p = __builtin_elementwise_max(
+            __builtin_elementwise_max(__builtin_bit_cast(u16x2, r0), __builtin_bit_cast(u16x2, r1)),
+            __builtin_elementwise_max(__builtin_bit_cast(u16x2, r2), __builtin_bit_cast(u16x2, r3)));
+        unsigned short m = p.x > p.y ? p.x : p.y;
+        r = (unsigned)m << 16;
+    }
+    // tail elements: first threads of block 0
+    if (blockIdx.x == 0) {
+        size_t t = nvec * PV + threadIdx.x;
+        if (t < n) {
+            unsigned m = scalar_mag<DT>(x, t);
+            r = r > m ? r : m;
+        }
+    }
+    r = block_max_u32(r);
+    if (threadIdx.x == 0) atomicMax(out_bits, r);
+}
+
+// Any alignment the element type allows: one element per lane per step.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void amax_scalar_kernel(const void* __restrict__ x, size_t n,
+                                                              unsigned* __restrict__ out_bits)
+{
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    unsigned r = 0;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        unsigned m = scalar_mag<DT>(x, i);
+        r = r > m ? r : m;
+    }
+    r = block_max_u32(r);
+    if (threadIdx.x == 0) atomicMax(out_bits, r);
+}
+
+// ------------------------------------------------------------------------------------------
+// scale = fmt_max / amax, one IEEE single division (Section 2; Table 1 "Max normal";
+// Section 3.2: any real value).  Degenerate amax (0, NaN, inf) or a quotient that is not
+// finite gives 1.
+// ------------------------------------------------------------------------------------------
+__host__ __device__ inline float scale_rule(float amax, int fmt)
+{
+    const float fmax = fmt == FP8_E4M3 ? 448.0f : 57344.0f;
+    if (!(amax > 0.0f) || amax > 3.4028234663852886e38f) return 1.0f;
+    const float s = fmax / amax;
+    if (!(s <= 3.4028234663852886e38f)) return 1.0f;
+    return s;
+}
+
+__global__ void scale_kernel(const float* __restrict__ amax, int fmt, float* __restrict__ out)
+{
+    *out = scale_rule(*amax, fmt);
+}
+
+// ------------------------------------------------------------------------------------------
+// The cast.  y = fl32(x * scale) is one IEEE multiply; then y is rounded to the nearest
+// FP8 value, ties to the even code (Table 1 encodings), finite overflow saturates to the
+// largest finite value (Section 2), NaN -> NaN, inf -> NaN (E4M3) or inf (E5M2).
+// ------------------------------------------------------------------------------------------
+
+// Rounding by integer arithmetic on the bits of y.
+//   normal results   : re-bias the exponent, add half of the dropped field (+ the tie bit),
+//                      shift the dropped mantissa bits out; a mantissa carry bumps the
+//                      exponent as it should.
+//   subnormal results: adding 2^(emin - mbits + 23) in fp32 leaves the multiple of the
+//                      subnormal step, rounded to nearest even by the adder, in the low bits.
+template <int FMT>
+__device__ __forceinline__ unsigned encode_bits(float y)
+{
+    constexpr int MB = FMT == FP8_E4M3 ? 3 : 2;                 // mantissa bits
+    constexpr int BIAS = FMT == FP8_E4M3 ? 7 : 15;
+    constexpr unsigned DROP = 23 - MB;                          // dropped fp32 mantissa bits
+    constexpr unsigned REBIAS = (unsigned)(127 - BIAS) << 23;
+    constexpr unsigned MIN_NORMAL = (unsigned)(127 + 1 - BIAS) << 23;
+    constexpr unsigned MAGIC = (unsigned)(127 + 1 - BIAS - MB + 23) << 23;
+    constexpr unsigned MAX_BITS = FMT == FP8_E4M3 ? 0x43E00000u : 0x47600000u;   // 448, 57344
+    constexpr unsigned MAX_CODE = FMT == FP8_E4M3 ? 0x7Eu : 0x7Bu;
+    constexpr unsigned INF_CODE = FMT == FP8_E4M3 ? 0x7Fu : 0x7Cu;
+
+    const unsigned u = as_u32(y);
+    const unsigned a = u & 0x7fffffffu;
+    const unsigned sign = (u >> 24) & 0x80u;
+
+    unsigned r = a - REBIAS;
+    r = (r + ((1u << (DROP - 1)) - 1u) + ((r >> DROP) & 1u)) >> DROP;
+    const unsigned sub = as_u32(as_f32(a) + as_f32(MAGIC)) - MAGIC;
+
+    unsigned code = a < MIN_NORMAL ? sub : r;
+    code = a >= MAX_BITS ? MAX_CODE : code;
+    code = a >= 0x7f800000u ? INF_CODE : code;
+    code = a > 0x7f800000u ? 0x7Fu : code;
+    return sign | code;
+}
+
+// Two values through the hardware converter.  The converter rounds to nearest even and
+// produces subnormals; the saturation rule is applied in front of it with a median-of-three
+// clamp.  NaN and inf inputs are not handled here (the caller routes them to encode_bits).
+template <int FMT, bool HI>
+__device__ __forceinline__ unsigned cvt_pair(float a, float b, unsigned old)
+{
+    constexpr float FMAX = FMT == FP8_E4M3 ? 448.0f : 57344.0f;
+    a = __builtin_amdgcn_fmed3f(a, FMAX, -FMAX);
+    b = __builtin_amdgcn_fmed3f(b, FMAX, -FMAX);
+    if (FMT == FP8_E4M3) return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, HI);
+    return (unsigned)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, HI);
+}
+
+__device__ __forceinline__ bool is_special(float y)      // NaN or +-inf
+{
+    return __builtin_amdgcn_class(y, 0x207);
+}
+
+// Four scaled values -> one dword of FP8 bytes (element 0 in the low byte).
+template <int FMT, int PATH>
+__device__ __forceinline__ unsigned encode4(float y0, float y1, float y2, float y3)
+{
+    if (PATH == kCastCvt) {
+        const bool special = is_special(y0) | is_special(y1) | is_special(y2) | is_special(y3);
+        if (!special) {
+            const unsigned w = cvt_pair<FMT, false>(y0, y1, 0u);
+            return cvt_pair<FMT, true>(y2, y3, w);
+        }
+    }
+    return encode_bits<FMT>(y0) | (encode_bits<FMT>(y1) << 8) | (encode_bits<FMT>(y2) << 16) |
+           (encode_bits<FMT>(y3) << 24);
+}
+
+template <int DT>
+__device__ __forceinline__ float load_scalar(const void* x, size_t i)
+{
+    if (DT == FP8_F32) return ((const float*)x)[i];
+    return as_f32((unsigned)((const unsigned short*)x)[i] << 16);
+}
+
+// One 16-byte vector of bfloat16 (8 elements) -> two dwords of FP8.
+template <int FMT, int PATH>
+__device__ __forceinline__ u32x2 cast_bf16x8(u32x4 v, float s)
+{
+    u32x2 o;
+    o.x = encode4<FMT, PATH>(as_f32(v.x << 16) * s, as_f32(v.x & 0xffff0000u) * s,
+                             as_f32(v.y << 16) * s, as_f32(v.y & 0xffff0000u) * s);
+    o.y = encode4<FMT, PATH>(as_f32(v.z << 16) * s, as_f32(v.z & 0xffff0000u) * s,
+                             as_f32(v.w << 16) * s, as_f32(v.w & 0xffff0000u) * s);
+    return o;
+}
+
+template <int FMT, int PATH>
+__device__ __forceinline__ unsigned cast_f32x4(u32x4 v, float s)
+{
+    return encode4<FMT, PATH>(as_f32(v.x) * s, as_f32(v.y) * s, as_f32(v.z) * s, as_f32(v.w) * s);
+}
+
+// Vector path: x and q are 16-byte aligned.  A work item is 16 consecutive elements:
+// 2 (bf16) or 4 (fp32) 16-byte loads and one 16-byte store per lane.
+template <int DT, int FMT, int PATH>
+__global__ __launch_bounds__(kThreads) void quantize_vec_kernel(const void* __restrict__ x, size_t n,
+                                                               float scale,
+                                                               const float* __restrict__ scale_dev,
+                                                               uint8_t* __restrict__ q)
+{
+    const float s = scale_dev ? *scale_dev : scale;
+    const u32x4* xv = (const u32x4*)x;
+    u32x4* qv = (u32x4*)q;
+    const size_t nitem = n / 16;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nitem; i += stride) {
+        u32x4 o;
+        if (DT == FP8_BF16) {
+            const u32x4 a = __builtin_nontemporal_load(&xv[2 * i]);
+            const u32x4 b = __builtin_nontemporal_load(&xv[2 * i + 1]);
+            const u32x2 lo = cast_bf16x8<FMT, PATH>(a, s), hi = cast_bf16x8<FMT, PATH>(b, s);
+            o.x = lo.x; o.y = lo.y; o.z = hi.x; o.w = hi.y;
+        } else {
+            const u32x4 a = __builtin_nontemporal_load(&xv[4 * i]);
+            const u32x4 b = __builtin_nontemporal_load(&xv[4 * i + 1]);
+            const u32x4 c = __builtin_nontemporal_load(&xv[4 * i + 2]);
+            const u32x4 d = __builtin_nontemporal_load(&xv[4 * i + 3]);
+            o.x = cast_f32x4<FMT, PATH>(a, s);
+            o.y = cast_f32x4<FMT, PATH>(b, s);
+            o.z = cast_f32x4<FMT, PATH>(c, s);
+            o.w = cast_f32x4<FMT, PATH>(d, s);
+        }
+        __builtin_nontemporal_store(o, &qv[i]);
+    }
+    if (blockIdx.x == 0) {                          // fewer than 16 tail elements
+        const size_t t = nitem * 16 + threadIdx.x;
+        if (t < n) q[t] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, t) * s);
+    }
+}
+
+// Any alignment: one element per lane per step, always the integer rounding.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_scalar_kernel(const void* __restrict__ x, size_t n,
+                                                                  float scale,
+                                                                  const float* __restrict__ scale_dev,
+                                                                  uint8_t* __restrict__ q)
+{
+    const float s = scale_dev ? *scale_dev : scale;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
+        q[i] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, i) * s);
+}
+
+inline int grid_for(size_t work_items)
+{
+    size_t b = (work_items + kThreads - 1) / kThreads;
+    if (b < 1) b = 1;
+    if (b > (size_t)kMaxBlocks) b = kMaxBlocks;
+    return (int)b;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream)
+{
+    unsigned* out = (unsigned*)amax_out;
+    hipLaunchKernelGGL(store_u32_kernel, dim3(1), dim3(1), 0, stream, out, 0u);
+    if (n == 0) return check_launch("amax init");
+    if (aligned16(x)) {
+        const size_t per_vec = in_dtype == FP8_F32 ? 4 : 8;
+        const int grid = grid_for((n / per_vec + 3) / 4);
+        if (in_dtype == FP8_F32)
+            hipLaunchKernelGGL(amax_vec_kernel<FP8_F32>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+        else
+            hipLaunchKernelGGL(amax_vec_kernel<FP8_BF16>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+    } else {
+        const int grid = grid_for(n);
+        if (in_dtype == FP8_F32)
+            hipLaunchKernelGGL(amax_scalar_kernel<FP8_F32>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+        else
+            hipLaunchKernelGGL(amax_scalar_kernel<FP8_BF16>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+    }
+    return check_launch("amax");
+}
+
+float scale_from_amax_host(float amax, int fmt) { return scale_rule(amax, fmt); }
+
+int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(scale_kernel, dim3(1), dim3(1), 0, stream, amax, fmt, scale_out);
+    return check_launch("scale_from_amax");
+}
+
+namespace {
+template <int DT, int FMT>
+void launch_quantize_typed(const void* x, size_t n, float scale, const float* scale_dev,
+                           uint8_t* q, hipStream_t stream)
+{
+    if (aligned16(x) && aligned16(q)) {
+        const int grid = grid_for(n / 16);
+        if (cast_path() == kCastCvt)
+            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastCvt>), dim3(grid), dim3(kThreads), 0,
+                               stream, x, n, scale, scale_dev, q);
+        else
+            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastBits>), dim3(grid), dim3(kThreads), 0,
+                               stream, x, n, scale, scale_dev, q);
+    } else {
+        hipLaunchKernelGGL((quantize_scalar_kernel<DT, FMT>), dim3(grid_for(n)), dim3(kThreads), 0, stream,
+                           x, n, scale, scale_dev, q);
+    }
+}
+}  // namespace
+
+int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
+                    const float* scale_dev, uint8_t* q_out, hipStream_t stream)
+{
+    if (n == 0) return FP8_OK;
+    if (in_dtype == FP8_F32) {
+        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_F32, FP8_E4M3>(x, n, scale, scale_dev, q_out, stream);
+        else                 launch_quantize_typed<FP8_F32, FP8_E5M2>(x, n, scale, scale_dev, q_out, stream);
+    } else {
+        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_BF16, FP8_E4M3>(x, n, scale, scale_dev, q_out, stream);
+        else                 launch_quantize_typed<FP8_BF16, FP8_E5M2>(x, n, scale, scale_dev, q_out, stream);
+    }
+    return check_launch("quantize");
+}
+
+}  // namespace fp8mm

@@ -1,0 +1,41 @@
+// Internal declarations shared by the translation units of libfp8mm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fp8mm.h"
+
+namespace fp8mm {
+
+// Records the message returned by fp8_last_error() on this thread and returns `code`.
+int fail(int code, const char* fmt, ...);
+void clear_error();
+
+// Turns the state of the HIP runtime after a launch into a status code.
+int check_launch(const char* what);
+
+inline bool valid_format(int f) { return f == FP8_E4M3 || f == FP8_E5M2; }
+inline bool valid_dtype(int d) { return d == FP8_F32 || d == FP8_BF16; }
+
+// Which implementation the cast kernel uses for the FP8 rounding step.
+//   kCastBits : integer bit manipulation written from the format definition
+//   kCastCvt  : the gfx950 v_cvt_pk_{fp8,bf8}_f32 instructions, with the saturation and
+//               special-value rules applied around them
+// Chosen per call from the environment variable FP8MM_CAST_PATH=bits|cvt.
+enum CastPath { kCastBits = 0, kCastCvt = 1 };
+CastPath cast_path();
+
+// ---- launchers (each enqueues on `stream` and returns a status) -------------------------
+int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream);
+float scale_from_amax_host(float amax, int fmt);
+int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream);
+int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
+                    const float* scale_dev, uint8_t* q_out, hipStream_t stream);
+int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
+                int64_t M, int64_t N, int64_t K, int out_dtype,
+                float sA, float sB, const float* sA_dev, const float* sB_dev,
+                bool fp8_accumulate, hipStream_t stream);
+
+}  // namespace fp8mm

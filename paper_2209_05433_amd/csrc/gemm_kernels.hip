@@ -1,0 +1,516 @@
+// FP8 x FP8 GEMM with fp32 accumulation and the fused unscale epilogue, for gfx950 (MI355X).
+//
+//   C[M x N] = alpha * A[M x K] * B[K x N],   alpha = 1 / (sA * sB)
+//
+// A and B hold E4M3 / E5M2 bytes (arXiv 2209.05433, Table 1), both row-major; the products
+// are accumulated in fp32 by the matrix cores and the reciprocal of the two per-tensor scales
+// is applied once per output (Section 2), then the result is written as fp32 or bf16.
+//
+// Fast kernel (M, N multiples of 256, K a multiple of 128, 16-byte aligned pointers):
+//   - one workgroup of 4 waves per 256 x 256 output tile, each wave owns 128 x 128 of it as
+//     4 x 4 blocks of v_mfma_f32_32x32x64_f8f6f4 (K = 64 per instruction, operand formats
+//     selected per operand, so the E5M2 x E4M3 mix costs nothing extra);
+//   - K is walked in stages of 64: a stage is a 256 x 64 slab of A and a 64 x 256 slab of B
+//     (32 KB), four stages live in LDS as a ring, filled by direct global->LDS loads issued
+//     three stages ahead of their use;
+//   - the MFMA wants, per lane, 32 consecutive-K bytes of one row (A) or one column (B).  A is
+//     K-contiguous in memory, so its fragments are plain 16-byte LDS reads.  B is N-contiguous;
+//     its fragments come from the transposing LDS read ds_read_b64_tr_b8, which hands each lane
+//     8 K-consecutive bytes of one column out of an 8 x 16 byte block;
+//   - both slabs are stored with an XOR swizzle of the 16-byte chunk index so that the
+//     fragment reads spread over the LDS banks; the swizzle is applied on the global side of
+//     the direct loads (LDS placement of a direct load is fixed: lane i writes 16 bytes at
+//     base + 16 i);
+//   - the instruction computes D[i][j] with operand 0 supplying i.  B fragments are operand 0,
+//     so every lane ends up with 4 consecutive N outputs of one row of C: 16-byte (fp32) or
+//     8-byte (bf16) stores;
+//   - workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile map
+//     gives every XCD one contiguous run of a column-sweeping order in bands of 8 tile rows,
+//     so the 32 tiles an XCD works on at a time share 8 row slabs of A and 4 column slabs of
+//     B in its L2.
+//
+//   - the products are formed either by the FP8 instruction above (ACC_FP8) or, after an exact
+//     widening of the bytes to fp16 in registers, by v_mfma_f32_32x32x16_f16 (ACC_F16, the
+//     default): see the note at the ACC_* constants for why both exist.
+//
+// Generic kernel (any shape, any alignment): decodes to fp32 in LDS and uses plain FMAs.
+#include "common.hpp"
+
+namespace fp8mm {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+__device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ unsigned bf16_bits(float f)
+{
+    const unsigned u = as_u32(f);
+    const unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r;
+}
+
+__device__ __forceinline__ double alpha_of(float sA, float sB, const float* sA_dev, const float* sB_dev)
+{
+    const double a = sA_dev ? (double)*sA_dev : (double)sA;
+    const double b = sB_dev ? (double)*sB_dev : (double)sB;
+    return 1.0 / (a * b);
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast kernel
+// ------------------------------------------------------------------------------------------
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int NSTAGE = 4;
+constexpr int A_STAGE = BM * BK;             // 16 KB
+constexpr int B_STAGE = BK * BN;             // 16 KB
+constexpr int STAGE = A_STAGE + B_STAGE;     // 32 KB
+constexpr int FAST_LDS = NSTAGE * STAGE;     // 128 KB of the 160 KB
+constexpr int FAST_THREADS = 256;
+constexpr int GROUP_M = 8;                   // tile rows per band of the tile order
+constexpr int NUM_XCD = 8;
+
+// Chunk swizzles.  A slab: rows of 64 B = 4 chunks; B slab: rows of 256 B = 16 chunks.
+__device__ __forceinline__ int swz_a(int row) { return ((row >> 1) ^ (row >> 3)) & 3; }
+__device__ __forceinline__ int swz_b(int krow) { return (krow & 7) | ((krow & 1) << 3); }
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
+// vmcnt = bits 3:0 and 15:14, expcnt = 6:4, lgkmcnt = 11:8).
+template <int VM>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt((VM & 15) | ((VM >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+struct TileMap { int tm, tn; };
+
+// Workgroup id -> output tile.  Ids go round-robin over the XCDs; XCD x gets ids x, x+8, ...
+// which are mapped to one contiguous run [start(x), start(x) + count(x)) of the order below.
+// Order: bands of GROUP_M tile rows; inside a band go down the rows first, then to the next
+// tile column.
+__device__ __forceinline__ TileMap map_tile(int bid, int tiles_m, int tiles_n)
+{
+    const int total = tiles_m * tiles_n;
+    const int x = bid % NUM_XCD, idx = bid / NUM_XCD;
+    const int base = total / NUM_XCD, rem = total % NUM_XCD;
+    const int p = x * base + (x < rem ? x : rem) + idx;
+    const int band_tiles = GROUP_M * tiles_n;
+    const int band = p / band_tiles;
+    const int q = p - band * band_tiles;
+    const int rows = min(GROUP_M, tiles_m - band * GROUP_M);
+    TileMap t;
+    t.tm = band * GROUP_M + q % rows;
+    t.tn = q / rows;
+    return t;
+}
+
+// How the products are formed and summed.
+//   ACC_F16: operands widened to fp16 (exact for both FP8 formats), fp16 matrix-core
+//            instructions.  These sum each instruction's products in a window of at least 24
+//            bits: fp32-grade accumulation, at half the FP8 peak rate.
+//   ACC_FP8: FP8 matrix-core instructions at the full FP8 rate.  The hardware adds each run of
+//            8 products (the 8 bytes of a lane's register pair) after aligning them to the
+//            largest and dropping what lies more than 13 bits below its leading bit, then
+//            accumulates the runs in fp32.
+enum { ACC_F16 = 0, ACC_FP8 = 1 };
+
+// 8 FP8 bytes (two dwords) -> 8 fp16 values, exact.
+template <int FMT>
+__device__ __forceinline__ v8h widen8(int lo, int hi)
+{
+    v2h p0, p1, p2, p3;
+    if (FMT == FP8_E4M3) {
+        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, false);
+        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, true);
+        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, false);
+        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, true);
+    } else {
+        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, false);
+        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, true);
+        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, false);
+        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, true);
+    }
+    return (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+}
+
+template <int FMT_A, int FMT_B, int OUT, int ACC>
+__global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int M, int N, int K, float sA, float sB, const float* __restrict__ sA_dev,
+    const float* __restrict__ sB_dev)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
+    const int wm = w >> 1, wn = w & 1;
+    const TileMap tile = map_tile(blockIdx.x, M / BM, N / BN);
+    const int m0 = tile.tm * BM, n0 = tile.tn * BN;
+    const int KT = K / BK;
+
+    // ---- direct global->LDS loads: 4 A and 4 B instructions per wave per stage ----------
+    // A instruction ia (0..15) fills rows 16 ia .. 16 ia + 15 (1 KB): lane -> (row, chunk).
+    // B instruction ib (0..15) fills K-rows 4 ib .. 4 ib + 3 (1 KB).
+    const uint8_t* a_tile = A + (size_t)m0 * K;
+    const uint8_t* b_tile = B + n0;
+    unsigned a_off[4], b_off[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int ia = w * 4 + t;
+        const int row = ia * 16 + (l >> 2);
+        const int lc = (l & 3) ^ swz_a(row);
+        a_off[t] = (unsigned)row * (unsigned)K + lc * 16;
+        const int ib = w * 4 + t;
+        const int krow = ib * 4 + (l >> 4);
+        const int lcb = (l & 15) ^ swz_b(krow);
+        b_off[t] = (unsigned)krow * (unsigned)N + lcb * 16;
+    }
+    // Direct loads are written as inline assembly: the compiler then keeps no account of them
+    // and inserts no waits of its own; completion is tracked by the explicit vmcnt waits below.
+    // LDS placement: M0 holds the wave-uniform base, lane i writes 16 bytes at M0 + 16 i.
+    auto direct_load = [](const uint8_t* base, unsigned off, unsigned lds_addr) {
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
+    };
+    const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
+    auto issue_stage = [&](int kt) {
+        const int slot = kt & (NSTAGE - 1);
+        const uint8_t* ag = a_tile + (size_t)kt * BK;
+        const uint8_t* bg = b_tile + (size_t)kt * BK * N;
+        const unsigned as = lds0 + slot * STAGE + w * 4096;
+        const unsigned bs = as + A_STAGE;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) direct_load(ag, a_off[t], as + t * 1024);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) direct_load(bg, b_off[t], bs + t * 1024);
+    };
+
+    // ---- fragment addresses -----------------------------------------------------------------
+    // A fragment (MFMA operand 1): lane = (m = l % 32, h = l / 32) reads K bytes 32h .. 32h+31
+    // of row m: chunks 2h and 2h+1, swizzled.
+    const int h = l >> 5;
+    const int a_row = wm * 128 + (l & 31);
+    const int a_c0 = (2 * h) ^ swz_a(a_row);
+    const unsigned a_rd0 = a_row * BK + a_c0 * 16;
+    const unsigned a_rd1 = a_row * BK + (a_c0 ^ 1) * 16;
+    // B fragment (MFMA operand 0): lane = (n = l % 32, h): column n, K bytes 32h .. 32h+31,
+    // gathered by four transposing reads of 8 K-rows x 16 columns per 16-lane group.
+    const int t16 = l & 15, gq = (l >> 4) & 1;
+    const int b_krow = 32 * h + (t16 >> 1);     // lanes 2r and 2r+1 of a group address K-row r
+    const int b_half = t16 & 1;
+    const int b_pc = (wn * 8 + gq) ^ swz_b(b_krow);
+    const unsigned b_rd = A_STAGE + b_krow * BN + b_pc * 16 + b_half * 8;
+
+    auto read_frags = [&](int kt, v8i (&af)[4], v8i (&bf)[4]) {
+        const unsigned sbase = (unsigned)(kt & (NSTAGE - 1)) * STAGE;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const v4i lo = *LDS_PTR(v4i, smem + sbase + a_rd0 + mb * 32 * BK);
+            const v4i hi = *LDS_PTR(v4i, smem + sbase + a_rd1 + mb * 32 * BK);
+            af[mb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            const unsigned base = sbase + (b_rd ^ (unsigned)(nb * 32));
+            v2i p[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                p[s] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * BN));
+            bf[nb] = (v8i){p[0].x, p[0].y, p[1].x, p[1].y, p[2].x, p[2].y, p[3].x, p[3].y};
+        }
+    };
+
+    v16f acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // Wait until this wave's loads of stage `kt` have landed: loads complete in order, so it is
+    // enough that no more than the loads of the later stages issued so far are outstanding
+    // (8 per stage per wave).  `issued` = index of the last stage issued so far.
+    auto wait_stage = [&](int kt, int issued) {
+        const int later = issued - kt;
+        if (later >= 2) wait_vmcnt<16>();
+        else if (later == 1) wait_vmcnt<8>();
+        else wait_vmcnt<0>();
+    };
+
+    // The 16 block products of one stage.
+    //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64).
+    //   ACC_F16: the FP8 bytes are widened exactly to fp16 in registers and each block takes
+    //            four v_mfma_f32_32x32x16_f16 (K = 16): 8 bytes of the lane's 32 per instruction.
+    auto compute_stage = [&](v8i (&af)[4], v8i (&bf)[4]) {
+        if (ACC == ACC_FP8) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+                    acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                v8h a16[4], b16[4];
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) a16[mb] = widen8<FMT_A>(af[mb][2 * s], af[mb][2 * s + 1]);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) b16[nb] = widen8<FMT_B>(bf[nb][2 * s], bf[nb][2 * s + 1]);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b16[nb], a16[mb], acc[nb][mb], 0, 0, 0);
+            }
+        }
+    };
+
+    // One K stage (not the last): the frags of stage kt are in (af, bf), their LDS reads were
+    // issued a stage ago.  Stage kt+1 is made visible, stage kt+4 is requested into the slot of
+    // stage kt, and the frags of stage kt+1 are read into (af_n, bf_n) under the MFMAs.
+    auto k_step = [&](int kt, v8i (&af)[4], v8i (&bf)[4], v8i (&af_n)[4], v8i (&bf_n)[4]) {
+        wait_stage(kt + 1, min(kt + NSTAGE - 1, KT - 1));
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
+        __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads stage kt's slot any more
+        if (kt + NSTAGE < KT) issue_stage(kt + NSTAGE);
+        read_frags(kt + 1, af_n, bf_n);
+        compute_stage(af, bf);
+        // issue order: the 24 LDS reads are spread behind the first MFMAs of the stage
+        if (ACC == ACC_FP8) {
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 24; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two VALU (widening)
+            }
+#pragma unroll
+            for (int i = 0; i < 40; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+        }
+    };
+
+    // prologue: stages 0..3 requested, stage 0 visible, its frags read.  KT is even and >= 2.
+    v8i af0[4], bf0[4], af1[4], bf1[4];
+    {
+        const int pre = min(NSTAGE - 1, KT);
+        for (int s = 0; s < pre; ++s) issue_stage(s);
+        wait_stage(0, pre - 1);
+        __builtin_amdgcn_s_barrier();
+        if (NSTAGE - 1 < KT) issue_stage(NSTAGE - 1);
+        read_frags(0, af0, bf0);
+    }
+    for (int kt = 0; kt < KT - 2; kt += 2) {
+        k_step(kt, af0, bf0, af1, bf1);
+        k_step(kt + 1, af1, bf1, af0, bf0);
+    }
+    k_step(KT - 2, af0, bf0, af1, bf1);
+    compute_stage(af1, bf1);
+
+    // ---- epilogue: unscale once per output, convert, store 4 consecutive N per lane ---------
+    const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
+    const int m_lane = m0 + wm * 128 + (l & 31);
+    const int n_lane = n0 + wn * 128 + 4 * h;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const size_t row = (size_t)(m_lane + mb * 32) * N;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n_lane + nb * 32 + 8 * q;
+                const float c0 = acc[nb][mb][4 * q + 0] * alpha, c1 = acc[nb][mb][4 * q + 1] * alpha;
+                const float c2 = acc[nb][mb][4 * q + 2] * alpha, c3 = acc[nb][mb][4 * q + 3] * alpha;
+                if (OUT == FP8_F32) {
+                    v4f o = {c0, c1, c2, c3};
+                    *(v4f*)((float*)C + row + n) = o;
+                } else {
+                    v2i o;
+                    o.x = (int)(bf16_bits(c0) | (bf16_bits(c1) << 16));
+                    o.y = (int)(bf16_bits(c2) | (bf16_bits(c3) << 16));
+                    *(v2i*)((unsigned short*)C + row + n) = o;
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic kernel: 64 x 64 tile per 256-thread workgroup, 4 x 4 outputs per thread, operands
+// decoded to fp32 (exactly) on their way into LDS, fp32 FMAs (each product of two FP8 values
+// is exact in fp32, so this is fp32 accumulation of exact products as well).
+// ------------------------------------------------------------------------------------------
+template <int FMT>
+__device__ __forceinline__ float decode_fp8(unsigned b)
+{
+    if (FMT == FP8_E5M2) {      // the upper byte of an IEEE half
+        return (float)__builtin_bit_cast(_Float16, (unsigned short)(b << 8));
+    }
+    const unsigned sign = (b & 0x80u) << 24;
+    const unsigned e = (b >> 3) & 15u, m = b & 7u;
+    float mag;
+    if (e == 15u && m == 7u) mag = as_f32(0x7fc00000u);
+    else if (e == 0u) mag = (float)m * 0.001953125f;                 // m * 2^-9
+    else mag = as_f32(((e + 120u) << 23) | (m << 20));               // 2^(e-7) * (1 + m/8)
+    return as_f32(as_u32(mag) | sign);
+}
+
+constexpr int GT = 64, GK = 16;
+
+template <int FMT_A, int FMT_B, int OUT>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int64_t M, int64_t N, int64_t K, float sA, float sB, const float* __restrict__ sA_dev,
+    const float* __restrict__ sB_dev)
+{
+    __shared__ float As[GK][GT + 1];
+    __shared__ float Bs[GK][GT + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t m0 = (int64_t)blockIdx.y * GT, n0 = (int64_t)blockIdx.x * GT;
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < K; k0 += GK) {
+        for (int e = tid; e < GT * GK; e += 256) {
+            const int r = e / GK, kk = e % GK;              // A: consecutive lanes along K
+            const int64_t gm = m0 + r, gk = k0 + kk;
+            As[kk][r] = (gm < M && gk < K) ? decode_fp8<FMT_A>(A[gm * K + gk]) : 0.0f;
+            const int kb = e / GT, c = e % GT;              // B: consecutive lanes along N
+            const int64_t gn = n0 + c, gkb = k0 + kb;
+            Bs[kb][c] = (gn < N && gkb < K) ? decode_fp8<FMT_B>(B[gkb * N + gn]) : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < GK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+            if (gm < M && gn < N) {
+                const float c = acc[i][j] * alpha;
+                if (OUT == FP8_F32) ((float*)C)[gm * N + gn] = c;
+                else ((unsigned short*)C)[gm * N + gn] = (unsigned short)bf16_bits(c);
+            }
+        }
+}
+
+// ---- dispatch ----------------------------------------------------------------------------
+struct GemmArgs {
+    const uint8_t* A; const uint8_t* B; void* C;
+    int64_t M, N, K;
+    float sA, sB; const float* sA_dev; const float* sB_dev;
+    hipStream_t stream;
+};
+
+template <int FA, int FB, int OUT, int ACC>
+int launch_fast(const GemmArgs& g)
+{
+    {
+        static bool attr_set = false;
+        auto kern = gemm_fast_kernel<FA, FB, OUT, ACC>;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
+            if (e != hipSuccess)
+                return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
+            attr_set = true;
+        }
+        const int tiles = (int)((g.M / BM) * (g.N / BN));
+        hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
+                           (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev);
+        return check_launch("gemm (fast kernel)");
+    }
+}
+
+template <int FA, int FB, int OUT>
+int launch_typed(const GemmArgs& g, bool fast, int acc)
+{
+    if (fast) return acc == ACC_FP8 ? launch_fast<FA, FB, OUT, ACC_FP8>(g) : launch_fast<FA, FB, OUT, ACC_F16>(g);
+    const dim3 grid((unsigned)((g.N + GT - 1) / GT), (unsigned)((g.M + GT - 1) / GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<FA, FB, OUT>), grid, dim3(256), 0, g.stream, g.A, g.B,
+                       g.C, g.M, g.N, g.K, g.sA, g.sB, g.sA_dev, g.sB_dev);
+    return check_launch("gemm (generic kernel)");
+}
+
+template <int FA, int FB>
+int launch_out(const GemmArgs& g, int out_dtype, bool fast, int acc)
+{
+    return out_dtype == FP8_F32 ? launch_typed<FA, FB, FP8_F32>(g, fast, acc)
+                                : launch_typed<FA, FB, FP8_BF16>(g, fast, acc);
+}
+
+__global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nbytes; i += stride) p[i] = 0;
+}
+
+}  // namespace
+
+// Environment knob, read per call: FP8MM_GEMM=generic forces the generic kernel.
+static bool force_generic()
+{
+    const char* e = getenv("FP8MM_GEMM");
+    return e && e[0] == 'g';
+}
+
+int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
+                int64_t M, int64_t N, int64_t K, int out_dtype,
+                float sA, float sB, const float* sA_dev, const float* sB_dev, bool fp8_accumulate,
+                hipStream_t stream)
+{
+    const int acc = fp8_accumulate ? ACC_FP8 : ACC_F16;
+    if (M == 0 || N == 0) return FP8_OK;
+    if (K == 0) {
+        const size_t nbytes = (size_t)M * (size_t)N * (out_dtype == FP8_F32 ? 4 : 2);
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, stream, (unsigned char*)C, nbytes);
+        return check_launch("gemm (K = 0 fill)");
+    }
+    const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0;
+    const bool fits32 = (uint64_t)BM * (uint64_t)K < (1ull << 32) && (uint64_t)K * (uint64_t)N < (1ull << 32) * 64
+                        && (uint64_t)BK * (uint64_t)N < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
+                        && (M / BM) * (N / BN) < (1ll << 31);
+    const bool fast = !force_generic() && aligned && fits32 && M % BM == 0 && N % BN == 0 && K % (2 * BK) == 0;
+    GemmArgs g{A, B, C, M, N, K, sA, sB, sA_dev, sB_dev, stream};
+    if (fmtA == FP8_E4M3) {
+        return fmtB == FP8_E4M3 ? launch_out<FP8_E4M3, FP8_E4M3>(g, out_dtype, fast, acc)
+                                : launch_out<FP8_E4M3, FP8_E5M2>(g, out_dtype, fast, acc);
+    }
+    return fmtB == FP8_E4M3 ? launch_out<FP8_E5M2, FP8_E4M3>(g, out_dtype, fast, acc)
+                            : launch_out<FP8_E5M2, FP8_E5M2>(g, out_dtype, fast, acc);
+}
+
+}  // namespace fp8mm

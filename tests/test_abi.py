@@ -1,0 +1,82 @@
+"""CPU-only checks of the boundary: the built library loads, exports what include/fp8mm.h
+declares, and rejects bad arguments before touching the GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2209_05433_amd as fp8
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fp8mm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fp8_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fp8.lib()
+    names = declared_symbols()
+    assert set(names) == set(fp8.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_binding_has_the_same_names():
+    for n in declared_symbols():
+        assert callable(getattr(fp8, n)), n
+
+
+def test_version_and_error_strings():
+    assert "gfx950" in fp8.fp8_version()
+    L = fp8.lib()
+    assert L.fp8_amax(None, 4, 0, None, None) == fp8.FP8_ERR_INVALID_ARG
+    assert "amax_out" in fp8.fp8_last_error()
+
+
+def test_invalid_arguments_are_rejected_without_a_launch():
+    L = fp8.lib()
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.addressof(buf)
+    INV = fp8.FP8_ERR_INVALID_ARG
+    assert L.fp8_amax(p, 4, 7, p, None) == INV                       # bad dtype
+    assert L.fp8_amax(None, 4, 0, p, None) == INV                    # null x, n > 0
+    assert L.fp8_amax(p + 2, 4, 0, p, None) == INV                   # misaligned fp32
+    assert L.fp8_scale_from_amax(None, 0, p, None) == INV
+    assert L.fp8_scale_from_amax(p, 5, p, None) == INV
+    assert L.fp8_quantize(p, 4, 0, 9, 1.0, p, None) == INV           # bad format
+    assert L.fp8_quantize(p, 4, 3, 0, 1.0, p, None) == INV           # bad dtype
+    assert L.fp8_quantize(None, 4, 0, 0, 1.0, p, None) == INV
+    assert L.fp8_quantize(p, 0, 0, 0, 1.0, None, None) == fp8.FP8_OK  # n == 0 launches nothing
+    assert L.fp8_quantize_dscale(p, 4, 0, 0, None, p, None) == INV
+    assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, -1, 4, 4, 0, None) == INV
+    assert L.fp8_gemm(p, 2, 1.0, p, 0, 1.0, p, 4, 4, 4, 0, None) == INV
+    assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, 4, 4, 4, 5, None) == INV
+    assert L.fp8_gemm(None, 0, 1.0, p, 0, 1.0, p, 4, 4, 4, 0, None) == INV
+    assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, None, 4, 4, 4, 0, None) == INV
+    assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, 0, 4, 4, 0, None) == fp8.FP8_OK   # empty output
+    assert L.fp8_gemm_dscale(p, 0, None, p, 0, p, p, 4, 4, 4, 0, None) == INV
+    assert "scale pointer" in fp8.fp8_last_error()
+
+
+@pytest.mark.parametrize("fmt", [fp8.FP8_E4M3, fp8.FP8_E5M2])
+def test_host_scale_rule_matches_the_oracle(fmt):
+    rng = np.random.default_rng(17)
+    vals = np.concatenate([2.0 ** rng.uniform(-140, 127, 4000),
+                           [0.0, 1.0, 448.0, 57344.0, np.inf, np.nan, 1e-45, 3.4e38]]).astype(np.float32)
+    for a in vals:
+        got = np.float32(fp8.fp8_scale_from_amax_host(float(a), fmt))
+        assert got == oracle.scale_from_amax(a, fmt), float(a)
+    assert fp8.fp8_scale_from_amax_host(1.0, 3) == 1.0 and "fmt" in fp8.fp8_last_error()
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    x = torch.zeros(8)
+    with pytest.raises(ValueError):
+        fp8.fp8_amax(x, torch.zeros(1))
