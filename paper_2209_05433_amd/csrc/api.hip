@@ -31,7 +31,7 @@ int check_launch(const char* what)
 CastPath cast_path()
 {
     const char* e = getenv("FP8MM_CAST_PATH");     // read per call: a test may switch it
-    return (e && strcmp(e, "cvt") == 0) ? kCastCvt : kCastBits;
+    return (e && strcmp(e, "bits") == 0) ? kCastBits : kCastCvt;
 }
 
 }  // namespace fp8mm

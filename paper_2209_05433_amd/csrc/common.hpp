@@ -23,7 +23,8 @@ inline bool valid_dtype(int d) { return d == FP8_F32 || d == FP8_BF16; }
 //   kCastBits : integer bit manipulation written from the format definition
 //   kCastCvt  : the gfx950 v_cvt_pk_{fp8,bf8}_f32 instructions, with the saturation and
 //               special-value rules applied around them
-// Chosen per call from the environment variable FP8MM_CAST_PATH=bits|cvt.
+// The converter path is the default (it was checked against the bit path on all 2^32 inputs);
+// the environment variable FP8MM_CAST_PATH=bits|cvt, read per call, overrides it.
 enum CastPath { kCastBits = 0, kCastCvt = 1 };
 CastPath cast_path();
 
