@@ -186,16 +186,16 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                      :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
     };
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
-    auto issue_stage = [&](int kt) {
+    // load t of stage kt: t = 0..3 are this wave's four A instructions, 4..7 its four B instructions
+    auto issue_one = [&](int kt, int t) {
         const int slot = kt & (NSTAGE - 1);
-        const uint8_t* ag = a_tile + (size_t)kt * BK;
-        const uint8_t* bg = b_tile + (size_t)kt * BK * N;
         const unsigned as = lds0 + slot * STAGE + w * 4096;
-        const unsigned bs = as + A_STAGE;
+        if (t < 4) direct_load(a_tile + (size_t)kt * BK, a_off[t], as + t * 1024);
+        else direct_load(b_tile + (size_t)kt * BK * N, b_off[t - 4], as + A_STAGE + (t - 4) * 1024);
+    };
+    auto issue_stage = [&](int kt) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) direct_load(ag, a_off[t], as + t * 1024);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) direct_load(bg, b_off[t], bs + t * 1024);
+        for (int t = 0; t < 8; ++t) issue_one(kt, t);
     };
 
     // ---- fragment addresses -----------------------------------------------------------------
@@ -214,23 +214,23 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const int b_pc = (wn * 8 + gq) ^ swz_b(b_krow);
     const unsigned b_rd = A_STAGE + b_krow * BN + b_pc * 16 + b_half * 8;
 
-    auto read_frags = [&](int kt, v8i (&af)[4], v8i (&bf)[4]) {
+    // The 24 fragment reads of a stage come in 8 parts of three: part j is one 16-byte read of A
+    // block j/2 (half j%2 of the lane's 32 bytes) and two transposing reads of B block j/2.
+    auto read_part = [&](int kt, int j, v8i (&af)[4], v8i (&bf)[4]) {
         const unsigned sbase = (unsigned)(kt & (NSTAGE - 1)) * STAGE;
+        const int blk = j >> 1, half = j & 1;
+        const v4i a = *LDS_PTR(v4i, smem + sbase + (half ? a_rd1 : a_rd0) + blk * 32 * BK);
+        af[blk][4 * half + 0] = a.x; af[blk][4 * half + 1] = a.y; af[blk][4 * half + 2] = a.z; af[blk][4 * half + 3] = a.w;
+        const unsigned base = sbase + (b_rd ^ (unsigned)(blk * 32));
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-            const v4i lo = *LDS_PTR(v4i, smem + sbase + a_rd0 + mb * 32 * BK);
-            const v4i hi = *LDS_PTR(v4i, smem + sbase + a_rd1 + mb * 32 * BK);
-            af[mb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        for (int s = 2 * half; s < 2 * half + 2; ++s) {
+            const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * BN));
+            bf[blk][2 * s] = p.x; bf[blk][2 * s + 1] = p.y;
         }
+    };
+    auto read_frags = [&](int kt, v8i (&af)[4], v8i (&bf)[4]) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            const unsigned base = sbase + (b_rd ^ (unsigned)(nb * 32));
-            v2i p[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-                p[s] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * BN));
-            bf[nb] = (v8i){p[0].x, p[0].y, p[1].x, p[1].y, p[2].x, p[2].y, p[3].x, p[3].y};
-        }
+        for (int j = 0; j < 8; ++j) read_part(kt, j, af, bf);
     };
 
     v16f acc[4][4];
@@ -252,63 +252,66 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         else wait_vmcnt<0>();
     };
 
-    // The 16 block products of one stage.
-    //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64).
-    //   ACC_F16: the FP8 bytes are widened exactly to fp16 in registers and each block takes
-    //            four v_mfma_f32_32x32x16_f16 (K = 16): 8 bytes of the lane's 32 per instruction.
-    auto compute_stage = [&](v8i (&af)[4], v8i (&bf)[4]) {
+    // The block products of a stage, in 8 parts.
+    //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64); part j = blocks 2j, 2j+1.
+    //   ACC_F16: the FP8 bytes are widened exactly to fp16 in registers and each block takes four
+    //            v_mfma_f32_32x32x16_f16 (K = 16, 8 of the lane's 32 bytes each); part j = K
+    //            sub-step j/2, B blocks 2(j%2) and 2(j%2)+1 against the four A blocks.
+    v8h a16[4];
+    auto compute_part = [&](int j, v8i (&af)[4], v8i (&bf)[4]) {
         if (ACC == ACC_FP8) {
+            const int nb = j >> 1;
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
+            for (int mb = 2 * (j & 1); mb < 2 * (j & 1) + 2; ++mb)
+                acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
         } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                v8h a16[4], b16[4];
+            const int s = j >> 1;
+            if ((j & 1) == 0) {
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb) a16[mb] = widen8<FMT_A>(af[mb][2 * s], af[mb][2 * s + 1]);
+            }
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) b16[nb] = widen8<FMT_B>(bf[nb][2 * s], bf[nb][2 * s + 1]);
+            for (int nb = 2 * (j & 1); nb < 2 * (j & 1) + 2; ++nb) {
+                const v8h b16 = widen8<FMT_B>(bf[nb][2 * s], bf[nb][2 * s + 1]);
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                    for (int mb = 0; mb < 4; ++mb)
-                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b16[nb], a16[mb], acc[nb][mb], 0, 0, 0);
+                for (int mb = 0; mb < 4; ++mb)
+                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b16, a16[mb], acc[nb][mb], 0, 0, 0);
             }
         }
     };
+    auto compute_stage = [&](v8i (&af)[4], v8i (&bf)[4]) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) compute_part(j, af, bf);
+    };
 
     // One K stage (not the last): the frags of stage kt are in (af, bf), their LDS reads were
-    // issued a stage ago.  Stage kt+1 is made visible, stage kt+4 is requested into the slot of
-    // stage kt, and the frags of stage kt+1 are read into (af_n, bf_n) under the MFMAs.
+    // issued a stage ago.  Stage kt+1 is made visible; then, in 8 parts, one direct load of
+    // stage kt+4 (into the slot of stage kt) is issued, an eighth of the MFMAs of stage kt runs,
+    // and three of the fragment reads of stage kt+1 go out into (af_n, bf_n).  Spreading the
+    // loads and reads matters: the four waves run in step, and a wave that issues its eight
+    // direct loads in one burst waits for the address unit before it reaches its first MFMA.
     auto k_step = [&](int kt, v8i (&af)[4], v8i (&bf)[4], v8i (&af_n)[4], v8i (&bf_n)[4]) {
         wait_stage(kt + 1, min(kt + NSTAGE - 1, KT - 1));
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads stage kt's slot any more
-        if (kt + NSTAGE < KT) issue_stage(kt + NSTAGE);
-        read_frags(kt + 1, af_n, bf_n);
-        compute_stage(af, bf);
-        // issue order: the 24 LDS reads are spread evenly over the MFMAs of the stage (the four
-        // waves run in step, so a burst of reads would queue up on the one LDS pipe)
-        if (ACC == ACC_FP8) {
+        const bool more = kt + NSTAGE < KT;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+        for (int j = 0; j < 8; ++j) {
+            if (more) issue_one(kt + NSTAGE, j);
+            read_part(kt + 1, j, af_n, bf_n);
+            compute_part(j, af, bf);
+            if (ACC == ACC_FP8) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-        } else {
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                    if (j % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 3 LDS reads per 8 MFMAs
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two VALU (widening)
+                for (int i = 0; i < 8; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
+                    if (i % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                   // widening
                 }
             }
         }
