@@ -10,9 +10,11 @@
 //   - one workgroup of 4 waves per 256 x 256 output tile, each wave owns 128 x 128 of it as
 //     4 x 4 blocks of v_mfma_f32_32x32x64_f8f6f4 (K = 64 per instruction, operand formats
 //     selected per operand, so the E5M2 x E4M3 mix costs nothing extra);
-//   - K is walked in stages of 64: a stage is a 256 x 64 slab of A and a 64 x 256 slab of B
-//     (32 KB), four stages live in LDS as a ring (128 KB), filled by direct global->LDS loads
-//     issued three stages ahead of their use;
+//   - K is walked in stages of 64.  B comes as one 64 x 256 slab (16 KB) per stage in a ring of
+//     four; A as one 256 x 128 slab (32 KB) per pair of stages in a ring of three (160 KB of LDS in
+//     all), both filled by direct global->LDS loads issued three to four stages ahead of use.
+//     A rows are fetched 128 bytes at a time because the vector L1 keeps at most 64 requests to
+//     the L2 in flight and asks for whole 128-byte lines: 64-byte row pieces double its requests;
 //   - the MFMA wants, per lane, 32 consecutive-K bytes of one row (A) or one column (B).  A is
 //     K-contiguous in memory, so its fragments are plain 16-byte LDS reads.  B is N-contiguous;
 //     its fragments come from the transposing LDS read ds_read_b64_tr_b8, which hands each lane
@@ -72,19 +74,20 @@ __device__ __forceinline__ double alpha_of(float sA, float sB, const float* sA_d
 // Fast kernel
 // ------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NSTAGE = 4;                    // LDS ring slots
-constexpr int A_STAGE = BM * BK;             // 16 KB
-constexpr int B_STAGE = BK * BN;             // 16 KB
-constexpr int STAGE = A_STAGE + B_STAGE;     // 32 KB
-constexpr int FAST_LDS = NSTAGE * STAGE;
+constexpr int B_SLOTS = 4;                   // B ring: one 64 x 256 slab (16 KB) per stage
+constexpr int A_SLOTS = 3;                   // A ring: one 256 x 128 slab (32 KB) per PAIR of stages
+constexpr int B_SLAB = BK * BN;              // 16 KB
+constexpr int A_SLAB = BM * 2 * BK;          // 32 KB
+constexpr int A_BASE = B_SLOTS * B_SLAB;     // A ring starts behind the B ring
+constexpr int FAST_LDS = A_BASE + A_SLOTS * A_SLAB;   // 160 KB: all of the LDS of a compute unit
 constexpr int FAST_THREADS = 256;
 constexpr int GROUP_M = 8;                   // tile rows per band of the tile order
 constexpr int NUM_XCD = 8;
 
-// Chunk swizzles.  A slab: rows of 64 B = 4 chunks; B slab: rows of 256 B = 16 chunks.
+// Chunk swizzles.  A slab: rows of 128 B = 8 chunks; B slab: rows of 256 B = 16 chunks.
 // Measured on gfx950: with these a 16-byte fragment read of A costs 5 clocks per wave instruction
 // (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read of B 7.3 clocks.
-__device__ __forceinline__ int swz_a(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int swz_a(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int swz_b(int krow) { return krow & 7; }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -161,18 +164,24 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
     const int KT = K / BK;
 
-    // ---- direct global->LDS loads: 4 A and 4 B instructions per wave per stage ----------
-    // A instruction ia (0..15) fills rows 16 ia .. 16 ia + 15 (1 KB): lane -> (row, chunk).
-    // B instruction ib (0..15) fills K-rows 4 ib .. 4 ib + 3 (1 KB).
+    // ---- direct global->LDS loads ------------------------------------------------------------
+    // B, every stage: 4 instructions per wave; instruction ib (0..15) fills K-rows 4 ib .. 4 ib+3
+    // of the 64 x 256 slab (1 KB): lane -> (K-row, 16-byte chunk).
+    // A, every second stage: 8 instructions per wave; instruction ia (0..31) fills rows 8 ia ..
+    // 8 ia + 7 of the 256 x 128 slab that serves two stages, so that every request to the L2 is a
+    // whole 128-byte line (with 64-byte row pieces the vector L1 asks for every line twice).
     const uint8_t* a_tile = A + (size_t)m0 * K;
     const uint8_t* b_tile = B + n0;
-    unsigned a_off[4], b_off[4];
+    unsigned a_off[8], b_off[4];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int ia = w * 8 + t;
+        const int row = ia * 8 + (l >> 3);
+        const int lc = (l & 7) ^ swz_a(row);
+        a_off[t] = (unsigned)row * (unsigned)K + lc * 16;
+    }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        const int ia = w * 4 + t;
-        const int row = ia * 16 + (l >> 2);
-        const int lc = (l & 3) ^ swz_a(row);
-        a_off[t] = (unsigned)row * (unsigned)K + lc * 16;
         const int ib = w * 4 + t;
         const int krow = ib * 4 + (l >> 4);
         const int lcb = (l & 15) ^ swz_b(krow);
@@ -186,51 +195,41 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                      :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
     };
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
-    // load t of stage kt: t = 0..3 are this wave's four A instructions, 4..7 its four B instructions
-    auto issue_one = [&](int kt, int t) {
-        const int slot = kt & (NSTAGE - 1);
-        const unsigned as = lds0 + slot * STAGE + w * 4096;
-        if (t < 4) direct_load(a_tile + (size_t)kt * BK, a_off[t], as + t * 1024);
-        else direct_load(b_tile + (size_t)kt * BK * N, b_off[t - 4], as + A_STAGE + (t - 4) * 1024);
+    auto issue_b = [&](int kt, int t) {          // instruction t (0..3) of the B slab of stage kt
+        direct_load(b_tile + (size_t)kt * BK * N, b_off[t],
+                    lds0 + (kt & (B_SLOTS - 1)) * B_SLAB + w * 4096 + t * 1024);
     };
-    auto issue_stage = [&](int kt) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) issue_one(kt, t);
+    auto issue_a = [&](int pair, int aslot, int t) {   // instruction t (0..7) of the A slab of a stage pair
+        direct_load(a_tile + (size_t)pair * 2 * BK, a_off[t], lds0 + A_BASE + aslot * A_SLAB + w * 8192 + t * 1024);
     };
 
     // ---- fragment addresses -----------------------------------------------------------------
-    // A fragment (MFMA operand 1): lane = (m = l % 32, h = l / 32) reads K bytes 32h .. 32h+31
-    // of row m: chunks 2h and 2h+1, swizzled.
+    // A fragment (MFMA operand 1): lane = (m = l % 32, h = l / 32) reads K bytes 32h .. 32h+31 of
+    // row m of its stage: chunks 4 par + 2h and + 1 of the 128-byte row (par = stage parity).
     const int h = l >> 5;
     const int a_row = wm * 128 + (l & 31);
-    const int a_c0 = (2 * h) ^ swz_a(a_row);
-    const unsigned a_rd0 = a_row * BK + a_c0 * 16;
-    const unsigned a_rd1 = a_row * BK + (a_c0 ^ 1) * 16;
+    const unsigned a_rd = A_BASE + a_row * 128 + (((2 * h) ^ swz_a(a_row)) * 16);   // par 0, first chunk
     // B fragment (MFMA operand 0): lane = (n = l % 32, h): column n, K bytes 32h .. 32h+31,
     // gathered by four transposing reads of 8 K-rows x 16 columns per 16-lane group.
     const int t16 = l & 15, gq = (l >> 4) & 1;
     const int b_krow = 32 * h + (t16 >> 1);     // lanes 2r and 2r+1 of a group address K-row r
     const int b_half = t16 & 1;
     const int b_pc = (wn * 8 + gq) ^ swz_b(b_krow);
-    const unsigned b_rd = A_STAGE + b_krow * BN + b_pc * 16 + b_half * 8;
+    const unsigned b_rd = b_krow * BN + b_pc * 16 + b_half * 8;
 
     // The 24 fragment reads of a stage come in 8 parts of three: part j is one 16-byte read of A
     // block j/2 (half j%2 of the lane's 32 bytes) and two transposing reads of B block j/2.
-    auto read_part = [&](int kt, int j, v8i (&af)[4], v8i (&bf)[4]) {
-        const unsigned sbase = (unsigned)(kt & (NSTAGE - 1)) * STAGE;
+    auto read_part = [&](int kt, int aslot, int j, v8i (&af)[4], v8i (&bf)[4]) {
         const int blk = j >> 1, half = j & 1;
-        const v4i a = *LDS_PTR(v4i, smem + sbase + (half ? a_rd1 : a_rd0) + blk * 32 * BK);
+        const unsigned a_addr = (a_rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + aslot * A_SLAB + blk * 32 * 128;
+        const v4i a = *LDS_PTR(v4i, smem + a_addr);
         af[blk][4 * half + 0] = a.x; af[blk][4 * half + 1] = a.y; af[blk][4 * half + 2] = a.z; af[blk][4 * half + 3] = a.w;
-        const unsigned base = sbase + (b_rd ^ (unsigned)(blk * 32));
+        const unsigned base = (unsigned)(kt & (B_SLOTS - 1)) * B_SLAB + (b_rd ^ (unsigned)(blk * 32));
 #pragma unroll
         for (int s = 2 * half; s < 2 * half + 2; ++s) {
             const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * BN));
             bf[blk][2 * s] = p.x; bf[blk][2 * s + 1] = p.y;
         }
-    };
-    auto read_frags = [&](int kt, v8i (&af)[4], v8i (&bf)[4]) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) read_part(kt, j, af, bf);
     };
 
     v16f acc[4][4];
@@ -240,17 +239,6 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    // Wait until this wave's loads of stage `kt` have landed: loads complete in order, so it is
-    // enough that no more than the loads of the later stages issued so far are outstanding
-    // (8 per stage per wave).  `issued` = index of the last stage issued so far.
-    auto wait_stage = [&](int kt, int issued) {
-        const int later = issued - kt;
-        if (later >= 3) wait_vmcnt<24>();
-        else if (later == 2) wait_vmcnt<16>();
-        else if (later == 1) wait_vmcnt<8>();
-        else wait_vmcnt<0>();
-    };
 
     // The block products of a stage, in 8 parts.
     //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64); part j = blocks 2j, 2j+1.
@@ -280,59 +268,93 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             }
         }
     };
-    auto compute_stage = [&](v8i (&af)[4], v8i (&bf)[4]) {
+    auto sched_part = [&]() {
+        if (ACC == ACC_FP8) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) compute_part(j, af, bf);
-    };
-
-    // One K stage (not the last): the frags of stage kt are in (af, bf), their LDS reads were
-    // issued a stage ago.  Stage kt+1 is made visible; then, in 8 parts, one direct load of
-    // stage kt+4 (into the slot of stage kt) is issued, an eighth of the MFMAs of stage kt runs,
-    // and three of the fragment reads of stage kt+1 go out into (af_n, bf_n).  Spreading the
-    // loads and reads matters: the four waves run in step, and a wave that issues its eight
-    // direct loads in one burst waits for the address unit before it reaches its first MFMA.
-    auto k_step = [&](int kt, v8i (&af)[4], v8i (&bf)[4], v8i (&af_n)[4], v8i (&bf_n)[4]) {
-        wait_stage(kt + 1, min(kt + NSTAGE - 1, KT - 1));
-        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
-        __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads stage kt's slot any more
-        const bool more = kt + NSTAGE < KT;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if (more) issue_one(kt + NSTAGE, j);
-            read_part(kt + 1, j, af_n, bf_n);
-            compute_part(j, af, bf);
-            if (ACC == ACC_FP8) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
-                    if (i % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                   // widening
-                }
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
+                if (i % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                   // widening
             }
         }
     };
 
-    // prologue: stages 0..3 requested, stage 0 visible, its frags read.  KT is even and >= 2.
+    // One K stage kt (not the last).  The frags of stage kt are in (af, bf); their LDS reads were
+    // issued a stage ago.  First stage kt+1 is made visible.  Then, in 8 parts: direct loads are
+    // issued (B slab of stage kt+4 into the slot of stage kt in every stage; in odd stages also the
+    // A slab of stage pair (kt+1)/2+2 into the slot of the pair that stage kt ends), an eighth of
+    // the MFMAs of stage kt runs, and three fragment reads of stage kt+1 go out into (af_n, bf_n).
+    // Order of issue, which the vmcnt arithmetic relies on: within a stage all A loads precede
+    // the B loads; so exactly 16 loads follow the last load of the B slab of stage kt+1 when stage
+    // kt begins (12 of one odd stage, 4 of one even stage).
+    auto k_step = [&](int kt, bool odd, int aslot_next, int aslot_free, v8i (&af)[4], v8i (&bf)[4],
+                      v8i (&af_n)[4], v8i (&bf_n)[4]) {
+        if (kt + B_SLOTS < KT) wait_vmcnt<16>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
+        __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
+        const bool more_b = kt + B_SLOTS < KT;
+        const int pair_new = (kt + 1) / 2 + 2;
+        const bool more_a = odd && 2 * pair_new < KT;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (odd) {                        // odd stage: 8 A loads in parts 0..3, 4 B loads in parts 4..7
+                if (j < 4) { if (more_a) { issue_a(pair_new, aslot_free, 2 * j); issue_a(pair_new, aslot_free, 2 * j + 1); } }
+                else if (more_b) issue_b(kt + B_SLOTS, j - 4);
+            } else if (j >= 4 && more_b) issue_b(kt + B_SLOTS, j - 4);
+            read_part(kt + 1, aslot_next, j, af_n, bf_n);
+            compute_part(j, af, bf);
+            sched_part();
+        }
+    };
+
+    // Prologue: the same order of issue as the steady state would have produced
+    // (A0, B0, A1, B1, B2, A2, B3), stage 0 visible, its frags read.  KT is even and >= 2.
     v8i af0[4], bf0[4], af1[4], bf1[4];
     {
-        const int pre = min(NSTAGE - 1, KT);
-        for (int s = 0; s < pre; ++s) issue_stage(s);
-        wait_stage(0, pre - 1);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) issue_a(0, 0, t);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) issue_b(0, t);
+        if (KT > 2) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) issue_a(1, 1, t);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) issue_b(1, t);
+        if (KT > 2) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) issue_b(2, t);
+        }
+        if (KT > 4) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) issue_a(2, 2, t);
+        }
+        if (KT > 2) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) issue_b(3, t);
+        }
+        // stage 0 = A slab 0 + B slab 0: everything issued after B0 may still be in flight
+        if (KT > 4) wait_vmcnt<28>(); else if (KT > 2) wait_vmcnt<20>(); else wait_vmcnt<4>();
         __builtin_amdgcn_s_barrier();
-        if (NSTAGE - 1 < KT) issue_stage(NSTAGE - 1);
-        read_frags(0, af0, bf0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) read_part(0, 0, j, af0, bf0);
     }
+    // Stage pair p = stages 2p, 2p+1 lives in A slot p % 3.
+    int aslot = 0;                            // slot of the pair the even stage belongs to
     for (int kt = 0; kt < KT - 2; kt += 2) {
-        k_step(kt, af0, bf0, af1, bf1);
-        k_step(kt + 1, af1, bf1, af0, bf0);
+        const int aslot_n = aslot == A_SLOTS - 1 ? 0 : aslot + 1;
+        k_step(kt, false, aslot, aslot, af0, bf0, af1, bf1);         // reads stage kt+1: same pair
+        k_step(kt + 1, true, aslot_n, aslot, af1, bf1, af0, bf0);    // reads stage kt+2: next pair; frees this pair's slot
+        aslot = aslot_n;
     }
-    k_step(KT - 2, af0, bf0, af1, bf1);
-    compute_stage(af1, bf1);
+    k_step(KT - 2, false, aslot, aslot, af0, bf0, af1, bf1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) compute_part(j, af1, bf1);
 
     // ---- epilogue: unscale once per output, convert, store 4 consecutive N per lane ---------
     const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
