@@ -24,8 +24,8 @@
 //     the direct loads (LDS placement of a direct load is fixed: lane i writes 16 bytes at
 //     base + 16 i);
 //   - the instruction computes D[i][j] with operand 0 supplying i.  B fragments are operand 0,
-//     so every lane ends up with 4 consecutive N outputs of one row of C: 16-byte (fp32) or
-//     8-byte (bf16) stores;
+//     so every lane ends up with 4 consecutive N outputs of one row of C; the epilogue turns
+//     32 x 128 blocks around through LDS and stores whole 128-byte lines;
 //   - workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile map
 //     gives every XCD one contiguous run of a column-sweeping order in bands of 8 tile rows,
 //     so the 32 tiles an XCD works on at a time share 8 row slabs of A and 4 column slabs of
@@ -356,31 +356,45 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) compute_part(j, af1, bf1);
 
-    // ---- epilogue: unscale once per output, convert, store 4 consecutive N per lane ---------
+    // ---- epilogue: unscale once per output, convert, write whole rows ----------------------------
+    // A lane holds 4 consecutive N of one C row per accumulator quad; written straight out that
+    // would be 8- or 16-byte pieces scattered over 32 rows per instruction.  Instead every wave
+    // turns each 32 x 128 block of its sub-tile around through its own piece of the (now idle)
+    // LDS and stores it with 16 bytes per lane along N: whole 128-byte lines of C.
+    constexpr int ESZ = OUT == FP8_F32 ? 4 : 2;
+    constexpr int ROWB = 128 * ESZ + 16;                    // padded LDS row of the wave's block
+    constexpr int ROWS_PER_ST = 1024 / (128 * ESZ);         // C rows covered by one store instruction
     const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
-    const int m_lane = m0 + wm * 128 + (l & 31);
-    const int n_lane = n0 + wn * 128 + 4 * h;
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_barrier();                           // every wave is done with the operand slabs
+    uint8_t* blk = smem + w * (32 * ROWB);
+    uint8_t* c_wave = (uint8_t*)C + ((size_t)(m0 + wm * 128) * N + n0 + wn * 128) * ESZ;
+    const int st_row = l / (64 / ROWS_PER_ST), st_col = (l % (64 / ROWS_PER_ST)) * 16;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+    for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-            const size_t row = (size_t)(m_lane + mb * 32) * N;
+        for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n_lane + nb * 32 + 8 * q;
                 const float c0 = acc[nb][mb][4 * q + 0] * alpha, c1 = acc[nb][mb][4 * q + 1] * alpha;
                 const float c2 = acc[nb][mb][4 * q + 2] * alpha, c3 = acc[nb][mb][4 * q + 3] * alpha;
+                uint8_t* dst = blk + (l & 31) * ROWB + (nb * 32 + 8 * q + 4 * h) * ESZ;
                 if (OUT == FP8_F32) {
-                    v4f o = {c0, c1, c2, c3};
-                    *(v4f*)((float*)C + row + n) = o;
+                    *LDS_PTR(v4f, dst) = (v4f){c0, c1, c2, c3};
                 } else {
                     v2i o;
                     o.x = (int)(bf16_bits(c0) | (bf16_bits(c1) << 16));
                     o.y = (int)(bf16_bits(c2) | (bf16_bits(c3) << 16));
-                    *(v2i*)((unsigned short*)C + row + n) = o;
+                    *LDS_PTR(v2i, dst) = o;
                 }
             }
+#pragma unroll
+        for (int i = 0; i < 32 / ROWS_PER_ST; ++i) {
+            const int row = i * ROWS_PER_ST + st_row;
+            const v4i v = *LDS_PTR(v4i, blk + row * ROWB + st_col);
+            *(v4i*)(c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col) = v;
         }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
