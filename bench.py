@@ -119,7 +119,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("gemm_" + args.workload)
+            traffic = json.load(open(tpath)).get("gemm_" + args.workload, {}).get("total_bytes")
         except Exception:
             traffic = None
 

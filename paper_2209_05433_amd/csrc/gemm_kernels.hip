@@ -104,18 +104,18 @@ struct TileMap { int tm, tn; };
 // which are mapped to one contiguous run [start(x), start(x) + count(x)) of the order below.
 // Order: bands of GROUP_M tile rows; inside a band go down the rows first, then to the next
 // tile column.
-__device__ __forceinline__ TileMap map_tile(int bid, int tiles_m, int tiles_n)
+__device__ __forceinline__ TileMap map_tile(int bid, int tiles_m, int tiles_n, int group_m)
 {
     const int total = tiles_m * tiles_n;
     const int x = bid % NUM_XCD, idx = bid / NUM_XCD;
     const int base = total / NUM_XCD, rem = total % NUM_XCD;
     const int p = x * base + (x < rem ? x : rem) + idx;
-    const int band_tiles = GROUP_M * tiles_n;
+    const int band_tiles = group_m * tiles_n;
     const int band = p / band_tiles;
     const int q = p - band * band_tiles;
-    const int rows = min(GROUP_M, tiles_m - band * GROUP_M);
+    const int rows = min(group_m, tiles_m - band * group_m);
     TileMap t;
-    t.tm = band * GROUP_M + q % rows;
+    t.tm = band * group_m + q % rows;
     t.tn = q / rows;
     return t;
 }
@@ -153,14 +153,14 @@ template <int FMT_A, int FMT_B, int OUT, int ACC>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
     int M, int N, int K, float sA, float sB, const float* __restrict__ sA_dev,
-    const float* __restrict__ sB_dev)
+    const float* __restrict__ sB_dev, int group_m)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int wm = w >> 1, wn = w & 1;
-    const TileMap tile = map_tile(blockIdx.x, M / BM, N / BN);
+    const TileMap tile = map_tile(blockIdx.x, M / BM, N / BN, group_m);
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
     const int KT = K / BK;
 
@@ -470,6 +470,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 }
 
 // ---- dispatch ----------------------------------------------------------------------------
+int group_m_setting();
 struct GemmArgs {
     const uint8_t* A; const uint8_t* B; void* C;
     int64_t M, N, K;
@@ -492,7 +493,7 @@ int launch_fast(const GemmArgs& g)
         }
         const int tiles = (int)((g.M / BM) * (g.N / BN));
         hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
-                           (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev);
+                           (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, group_m_setting());
         return check_launch("gemm (fast kernel)");
     }
 }
@@ -522,7 +523,16 @@ __global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
 
 }  // namespace
 
-// Environment knob, read per call: FP8MM_GEMM=generic forces the generic kernel.
+// Environment knobs, read per call: FP8MM_GEMM=generic forces the generic kernel,
+// FP8MM_GROUP_M sets the number of tile rows per band of the tile order (default GROUP_M).
+namespace {
+int group_m_setting()
+{
+    const char* e = getenv("FP8MM_GROUP_M");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : GROUP_M;
+}
+}  // namespace
 static bool force_generic()
 {
     const char* e = getenv("FP8MM_GEMM");

@@ -31,6 +31,7 @@ def main():
     ap.add_argument("--mode", default="f16", choices=["f16", "mfma8"])
     ap.add_argument("--iters", type=int, default=3)
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy")
+    ap.add_argument("--mnk", type=int, nargs=3, default=None, help="GEMM shape overriding the workload's")
     args = ap.parse_args()
 
     n = args.copy_mib << 20
@@ -53,6 +54,8 @@ def main():
                 fp8.fp8_quantize_dscale(x, fmt, scale, q)
     else:
         M, N, K, fmtA, out = SHAPES[args.workload]
+        if args.mnk:
+            M, N, K = args.mnk
         A, B = random_codes((M, K)), random_codes((K, N))
         C = torch.empty((M, N), dtype=out, device="cuda")
         gemm = fp8.fp8_gemm if args.mode == "f16" else fp8.fp8_gemm_mfma8
