@@ -324,3 +324,38 @@ def test_config2_quantize_only_full_size(fmt):
     want = oracle.quantize(h, fmt, s)
     got = q.cpu().numpy()
     assert np.array_equal(got, want), "%d bytes differ" % int((got != want).sum())
+
+
+def test_fp8_instruction_adder_window_is_what_the_header_says():
+    """Documents, through the public entry points, why two GEMM variants exist: a product 2^-j
+    times the largest product of its run of 8 consecutive K survives in fp8_gemm for every j
+    that fp32 can hold, and is dropped by the FP8 matrix-core instructions from j = 14 on;
+    in another run of 8 it survives in both."""
+    M = N = 256
+    K = 128
+    def pow2(e):                      # E4M3 code of 2^e, -9 <= e <= 8
+        return oracle.encode(E4M3, 2.0 ** e)
+    lost_f16, lost_mfma8_same, lost_mfma8_other = [], [], []
+    for j in range(0, 24):
+        e = 16 - j
+        x = max(-9, min(8, e // 2))
+        y = e - x
+        for small_k, bucket in ((1, lost_mfma8_same), (9, lost_mfma8_other)):
+            A = np.zeros((M, K), dtype=np.uint8)
+            B = np.zeros((K, N), dtype=np.uint8)
+            A[0, 0] = pow2(8); B[0, 0] = pow2(8)
+            A[0, small_k] = pow2(x); B[small_k, 0] = pow2(y)
+            want = 2.0 ** 16 + 2.0 ** e
+            S, _ = oracle.gemm_points(A, E4M3, B, E4M3, [0], [0])
+            assert S[0] == want
+            c16 = out_to_f64(run_gemm(A, E4M3, 1.0, B, E4M3, 1.0, fp8.FP8_F32))[0, 0]
+            c8 = out_to_f64(run_gemm(A, E4M3, 1.0, B, E4M3, 1.0, fp8.FP8_F32, mode="mfma8"))[0, 0]
+            if c16 != want and small_k == 1:
+                lost_f16.append(j)
+            if c8 != want:
+                bucket.append(j)
+            assert abs(c8 - want) <= 2.0 ** -10 * (2.0 ** 16 + 2.0 ** e)     # its documented bound
+    assert lost_f16 == []
+    assert lost_mfma8_other == []
+    print("FP8 instructions drop the smaller product of a run of 8 for j in", lost_mfma8_same)
+    assert lost_mfma8_same == list(range(14, 24))
