@@ -86,6 +86,31 @@ int fp8_quantize_dscale(const void* x, size_t n, int in_dtype, int fmt,
                         const float* scale, uint8_t* q_out, void* stream);
 
 /*
+ * fp8_quantize_ex -- fp8_quantize with both ways of passing the scale (scale_dev, if not
+ * NULL, is read from device memory and `scale` is ignored) and conversion flags:
+ *   FP8_QUANT_NOSAT  the strict conversion Section 2 allows for uses that must see
+ *                    overflow: a value whose rounding lands beyond the largest finite value
+ *                    becomes NaN (E4M3) or +-inf (E5M2) instead of the maximum.  Rounding is
+ *                    done against the next point of the exponent/mantissa grid (480 / 65536),
+ *                    so 464 still rounds to 448 and 61440 to inf.
+ * Unknown flag bits are an FP8_ERR_INVALID_ARG.
+ */
+#define FP8_QUANT_NOSAT 1
+int fp8_quantize_ex(const void* x, size_t n, int in_dtype, int fmt, float scale,
+                    const float* scale_dev, int flags, uint8_t* q_out, void* stream);
+
+/*
+ * fp8_dequantize -- out[i] = decode(q[i]) / scale in IEEE single precision, written as fp32
+ * or rounded to bf16 (Section 2: values are unscaled by the inverse of the scaling factor
+ * after conversion from FP8; Section 4: the paper's own experiments cast to FP8 and back).
+ *   q    n FP8 bytes of format fmt;   out  n elements of out_dtype
+ *   scale by value, or from device memory if scale_dev is not NULL
+ * NaN and inf codes decode to NaN and inf.  n == 0 launches nothing.
+ */
+int fp8_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
+                   int out_dtype, void* out, void* stream);
+
+/*
  * fp8_gemm -- C = (1 / (sA * sB)) * (A x B) with FP8 operands, fp32 accumulation
  * and the unscale applied once per output (Section 2: matrix multiplies on FP8
  * inputs produce single-precision results; unscaling is done once per dot product;

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE,
     EXPORTS, LIB_PATH, Fp8Error, lib,
     fp8_amax, fp8_scale_from_amax_host, fp8_scale_from_amax,
-    fp8_quantize, fp8_quantize_dscale, fp8_gemm, fp8_gemm_dscale,
+    fp8_quantize, fp8_quantize_dscale, fp8_quantize_ex, fp8_dequantize, FP8_QUANT_NOSAT, fp8_gemm, fp8_gemm_dscale,
     fp8_gemm_mfma8, fp8_gemm_mfma8_dscale,
     fp8_last_error, fp8_version,
 )

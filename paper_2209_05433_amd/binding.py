@@ -11,12 +11,13 @@ import torch
 FP8_E4M3, FP8_E5M2 = 0, 1
 FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
+FP8_QUANT_NOSAT = 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
 EXPORTS = (
     "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
-    "fp8_quantize_dscale", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
+    "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
     "fp8_gemm_mfma8_dscale", "fp8_last_error", "fp8_version",
 )
 
@@ -46,6 +47,8 @@ def lib() -> ctypes.CDLL:
     L.fp8_scale_from_amax.argtypes, L.fp8_scale_from_amax.restype = [vp, i, vp, vp], i
     L.fp8_quantize.argtypes, L.fp8_quantize.restype = [vp, sz, i, i, f, vp, vp], i
     L.fp8_quantize_dscale.argtypes, L.fp8_quantize_dscale.restype = [vp, sz, i, i, vp, vp, vp], i
+    L.fp8_quantize_ex.argtypes, L.fp8_quantize_ex.restype = [vp, sz, i, i, f, vp, i, vp, vp], i
+    L.fp8_dequantize.argtypes, L.fp8_dequantize.restype = [vp, sz, i, f, vp, i, vp, vp], i
     L.fp8_gemm.argtypes, L.fp8_gemm.restype = [vp, i, f, vp, i, f, vp, i64, i64, i64, i, vp], i
     L.fp8_gemm_dscale.argtypes, L.fp8_gemm_dscale.restype = [vp, i, vp, vp, i, vp, vp, i64, i64, i64, i, vp], i
     L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
@@ -120,6 +123,26 @@ def fp8_quantize_dscale(x: torch.Tensor, fmt: int, scale: torch.Tensor, q_out: t
     _check(lib().fp8_quantize_dscale(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x),
                                      fmt, _dev(scale, "scale"),
                                      _dev(q_out, "q_out") if x.numel() else None, _stream(stream)))
+
+
+def fp8_quantize_ex(x: torch.Tensor, fmt: int, scale, flags: int, q_out: torch.Tensor, stream=None) -> None:
+    """`scale` is a float or a one-element device tensor."""
+    if q_out.dtype != torch.uint8 or q_out.numel() != x.numel():
+        raise ValueError("q_out must be uint8 with as many elements as x")
+    dev = isinstance(scale, torch.Tensor)
+    _check(lib().fp8_quantize_ex(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
+                                 0.0 if dev else float(scale), _dev(scale, "scale") if dev else None,
+                                 int(flags), _dev(q_out, "q_out") if x.numel() else None, _stream(stream)))
+
+
+def fp8_dequantize(q: torch.Tensor, fmt: int, scale, out: torch.Tensor, stream=None) -> None:
+    """`scale` is a float or a one-element device tensor; out is float32 or bfloat16."""
+    if q.dtype != torch.uint8 or out.numel() != q.numel():
+        raise ValueError("q must be uint8 and out must have as many elements")
+    dev = isinstance(scale, torch.Tensor)
+    _check(lib().fp8_dequantize(_dev(q, "q") if q.numel() else None, q.numel(), fmt,
+                                0.0 if dev else float(scale), _dev(scale, "scale") if dev else None,
+                                dtype_code(out), _dev(out, "out") if q.numel() else None, _stream(stream)))
 
 
 def _gemm_dims(A, B, C):

@@ -76,7 +76,7 @@ int fp8_scale_from_amax(const float* amax, int fmt, float* scale_out, void* stre
 }
 
 static int quantize_checked(const char* who, const void* x, size_t n, int in_dtype, int fmt, float scale,
-                            const float* scale_dev, uint8_t* q_out, void* stream)
+                            const float* scale_dev, uint8_t* q_out, void* stream, bool saturate = true)
 {
     clear_error();
     if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
@@ -84,7 +84,7 @@ static int quantize_checked(const char* who, const void* x, size_t n, int in_dty
     if (n > 0 && (!x || !q_out)) return fail(FP8_ERR_INVALID_ARG, "%s: NULL tensor pointer with n = %zu", who, n);
     const uintptr_t esz = in_dtype == FP8_F32 ? 4 : 2;
     if ((uintptr_t)x % esz) return fail(FP8_ERR_INVALID_ARG, "%s: x is not aligned to its element size", who);
-    return launch_quantize(x, n, in_dtype, fmt, scale, scale_dev, q_out, (hipStream_t)stream);
+    return launch_quantize(x, n, in_dtype, fmt, scale, scale_dev, saturate, q_out, (hipStream_t)stream);
 }
 
 int fp8_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale, uint8_t* q_out, void* stream)
@@ -100,6 +100,33 @@ int fp8_quantize_dscale(const void* x, size_t n, int in_dtype, int fmt, const fl
         return fail(FP8_ERR_INVALID_ARG, "fp8_quantize_dscale: scale pointer is NULL or misaligned");
     }
     return quantize_checked("fp8_quantize_dscale", x, n, in_dtype, fmt, 0.0f, scale, q_out, stream);
+}
+
+int fp8_quantize_ex(const void* x, size_t n, int in_dtype, int fmt, float scale, const float* scale_dev,
+                    int flags, uint8_t* q_out, void* stream)
+{
+    if (flags & ~FP8_QUANT_NOSAT) {
+        clear_error();
+        return fail(FP8_ERR_INVALID_ARG, "fp8_quantize_ex: unknown flag bits 0x%x", flags & ~FP8_QUANT_NOSAT);
+    }
+    if (scale_dev && (uintptr_t)scale_dev % 4) {
+        clear_error();
+        return fail(FP8_ERR_INVALID_ARG, "fp8_quantize_ex: scale_dev is misaligned");
+    }
+    return quantize_checked("fp8_quantize_ex", x, n, in_dtype, fmt, scale, scale_dev, q_out, stream,
+                            !(flags & FP8_QUANT_NOSAT));
+}
+
+int fp8_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
+                   int out_dtype, void* out, void* stream)
+{
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "fp8_dequantize: fmt %d is not an fp8_format_t", fmt);
+    if (!valid_dtype(out_dtype)) return fail(FP8_ERR_INVALID_ARG, "fp8_dequantize: out_dtype %d is not an fp8_dtype_t", out_dtype);
+    if (n > 0 && (!q || !out)) return fail(FP8_ERR_INVALID_ARG, "fp8_dequantize: NULL tensor pointer with n = %zu", n);
+    if ((uintptr_t)out % (out_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "fp8_dequantize: out is not aligned to its element size");
+    if (scale_dev && (uintptr_t)scale_dev % 4) return fail(FP8_ERR_INVALID_ARG, "fp8_dequantize: scale_dev is misaligned");
+    return launch_dequantize(q, n, fmt, scale, scale_dev, out_dtype, out, (hipStream_t)stream);
 }
 
 static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,

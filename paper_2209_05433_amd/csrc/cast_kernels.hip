@@ -6,6 +6,7 @@
 // multiply every element by the scale and round it to E4M3 / E5M2 (Table 1) with
 // saturation.
 #include "common.hpp"
+#include "fp8_decode.hpp"
 
 namespace fp8mm {
 namespace {
@@ -168,7 +169,9 @@ __global__ void scale_kernel(const float* __restrict__ amax, int fmt, float* __r
 //                      exponent as it should.
 //   subnormal results: adding 2^(emin - mbits + 23) in fp32 leaves the multiple of the
 //                      subnormal step, rounded to nearest even by the adder, in the low bits.
-template <int FMT>
+//   SAT = false is the strict conversion of Section 2: rounding that lands beyond the largest
+//   finite value gives NaN (E4M3) or inf (E5M2) instead of saturating.
+template <int FMT, bool SAT = true>
 __device__ __forceinline__ unsigned encode_bits(float y)
 {
     constexpr int MB = FMT == FP8_E4M3 ? 3 : 2;                 // mantissa bits
@@ -190,7 +193,8 @@ __device__ __forceinline__ unsigned encode_bits(float y)
     const unsigned sub = as_u32(as_f32(a) + as_f32(MAGIC)) - MAGIC;
 
     unsigned code = a < MIN_NORMAL ? sub : r;
-    code = a >= MAX_BITS ? MAX_CODE : code;
+    if (SAT) code = a >= MAX_BITS ? MAX_CODE : code;
+    else code = code > INF_CODE ? INF_CODE : code;          // rounded past the grid: NaN / inf
     code = a >= 0x7f800000u ? INF_CODE : code;
     code = a > 0x7f800000u ? 0x7Fu : code;
     return sign | code;
@@ -215,11 +219,11 @@ __device__ __forceinline__ bool is_special(float y)      // NaN or +-inf
 }
 
 // Four scaled values -> one dword of FP8 bytes (element 0 in the low byte), integer path.
-template <int FMT>
+template <int FMT, bool SAT = true>
 __device__ __forceinline__ unsigned encode4_bits(float y0, float y1, float y2, float y3)
 {
-    return encode_bits<FMT>(y0) | (encode_bits<FMT>(y1) << 8) | (encode_bits<FMT>(y2) << 16) |
-           (encode_bits<FMT>(y3) << 24);
+    return encode_bits<FMT, SAT>(y0) | (encode_bits<FMT, SAT>(y1) << 8) | (encode_bits<FMT, SAT>(y2) << 16) |
+           (encode_bits<FMT, SAT>(y3) << 24);
 }
 
 // Sixteen scaled values -> four dwords.  Converter path: one test for NaN/inf over all sixteen
@@ -228,6 +232,11 @@ template <int FMT, int PATH>
 __device__ __forceinline__ u32x4 encode16(const float (&y)[16])
 {
     u32x4 o;
+    if (PATH == kCastBitsStrict) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) o[d] = encode4_bits<FMT, false>(y[4 * d], y[4 * d + 1], y[4 * d + 2], y[4 * d + 3]);
+        return o;
+    }
     bool fast = PATH == kCastCvt;
     if (PATH == kCastCvt) {
         bool special = false;
@@ -319,12 +328,12 @@ __global__ __launch_bounds__(kThreads) void quantize_vec_kernel(const void* __re
     }
     if (blockIdx.x == 0) {                          // fewer than 16 tail elements
         const size_t t = nitem * 16 + threadIdx.x;
-        if (t < n) q[t] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, t) * s);
+        if (t < n) q[t] = (uint8_t)encode_bits<FMT, PATH != kCastBitsStrict>(load_scalar<DT>(x, t) * s);
     }
 }
 
 // Any alignment: one element per lane per step, always the integer rounding.
-template <int DT, int FMT>
+template <int DT, int FMT, bool SAT>
 __global__ __launch_bounds__(kThreads) void quantize_scalar_kernel(const void* __restrict__ x, size_t n,
                                                                   float scale,
                                                                   const float* __restrict__ scale_dev,
@@ -333,7 +342,7 @@ __global__ __launch_bounds__(kThreads) void quantize_scalar_kernel(const void* _
     const float s = scale_dev ? *scale_dev : scale;
     const size_t stride = (size_t)gridDim.x * kThreads;
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride)
-        q[i] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, i) * s);
+        q[i] = (uint8_t)encode_bits<FMT, SAT>(load_scalar<DT>(x, i) * s);
 }
 
 inline int grid_for(size_t work_items, int max_blocks)
@@ -381,35 +390,105 @@ int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStre
 namespace {
 template <int DT, int FMT>
 void launch_quantize_typed(const void* x, size_t n, float scale, const float* scale_dev,
-                           uint8_t* q, hipStream_t stream)
+                           uint8_t* q, bool saturate, hipStream_t stream)
 {
     if (aligned16(x) && aligned16(q)) {
         const int grid = grid_for((n / 16 + 3) / 4, kCastBlocks);
-        if (cast_path() == kCastCvt)
+        if (!saturate)
+            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastBitsStrict>), dim3(grid), dim3(kThreads), 0,
+                               stream, x, n, scale, scale_dev, q);
+        else if (cast_path() == kCastCvt)
             hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastCvt>), dim3(grid), dim3(kThreads), 0,
                                stream, x, n, scale, scale_dev, q);
         else
             hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastBits>), dim3(grid), dim3(kThreads), 0,
                                stream, x, n, scale, scale_dev, q);
+    } else if (saturate) {
+        hipLaunchKernelGGL((quantize_scalar_kernel<DT, FMT, true>), dim3(grid_for(n, 2048)), dim3(kThreads), 0,
+                           stream, x, n, scale, scale_dev, q);
     } else {
-        hipLaunchKernelGGL((quantize_scalar_kernel<DT, FMT>), dim3(grid_for(n, 2048)), dim3(kThreads), 0, stream,
-                           x, n, scale, scale_dev, q);
+        hipLaunchKernelGGL((quantize_scalar_kernel<DT, FMT, false>), dim3(grid_for(n, 2048)), dim3(kThreads), 0,
+                           stream, x, n, scale, scale_dev, q);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// dequantize: out[i] = fl_out(decode(q[i]) / scale), one IEEE single division per element
+// (Section 2: values are unscaled by the inverse of the scaling factor after conversion from
+// FP8), then rounding to bf16 if asked.  16 bytes in, 32 or 64 bytes out per lane.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned to_bf16_bits(float f)
+{
+    const unsigned u = as_u32(f);
+    const unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r;
+}
+
+template <int FMT, int OUT>
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __restrict__ q, size_t n, float scale,
+                                                             const float* __restrict__ scale_dev,
+                                                             void* __restrict__ out, bool vec)
+{
+    const float s = scale_dev ? *scale_dev : scale;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    const size_t nitem = vec ? n / 16 : 0;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nitem; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(&((const u32x4*)q)[i]);
+        float y[16];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) y[4 * d + b] = decode_fp8<FMT>((v[d] >> (8 * b)) & 0xffu) / s;
+        if (OUT == FP8_F32) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                ((u32x4*)out)[4 * i + j] = (u32x4){as_u32(y[4 * j]), as_u32(y[4 * j + 1]), as_u32(y[4 * j + 2]), as_u32(y[4 * j + 3])};
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                u32x4 o;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) o[d] = to_bf16_bits(y[8 * j + 2 * d]) | (to_bf16_bits(y[8 * j + 2 * d + 1]) << 16);
+                ((u32x4*)out)[2 * i + j] = o;
+            }
+        }
+    }
+    for (size_t t = nitem * 16 + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
+        const float y = decode_fp8<FMT>(q[t]) / s;
+        if (OUT == FP8_F32) ((float*)out)[t] = y;
+        else ((unsigned short*)out)[t] = (unsigned short)to_bf16_bits(y);
     }
 }
 }  // namespace
 
 int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
-                    const float* scale_dev, uint8_t* q_out, hipStream_t stream)
+                    const float* scale_dev, bool saturate, uint8_t* q_out, hipStream_t stream)
 {
     if (n == 0) return FP8_OK;
     if (in_dtype == FP8_F32) {
-        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_F32, FP8_E4M3>(x, n, scale, scale_dev, q_out, stream);
-        else                 launch_quantize_typed<FP8_F32, FP8_E5M2>(x, n, scale, scale_dev, q_out, stream);
+        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_F32, FP8_E4M3>(x, n, scale, scale_dev, q_out, saturate, stream);
+        else                 launch_quantize_typed<FP8_F32, FP8_E5M2>(x, n, scale, scale_dev, q_out, saturate, stream);
     } else {
-        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_BF16, FP8_E4M3>(x, n, scale, scale_dev, q_out, stream);
-        else                 launch_quantize_typed<FP8_BF16, FP8_E5M2>(x, n, scale, scale_dev, q_out, stream);
+        if (fmt == FP8_E4M3) launch_quantize_typed<FP8_BF16, FP8_E4M3>(x, n, scale, scale_dev, q_out, saturate, stream);
+        else                 launch_quantize_typed<FP8_BF16, FP8_E5M2>(x, n, scale, scale_dev, q_out, saturate, stream);
     }
     return check_launch("quantize");
+}
+
+int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
+                      int out_dtype, void* out, hipStream_t stream)
+{
+    if (n == 0) return FP8_OK;
+    const bool vec = aligned16(q) && aligned16(out);
+    const int grid = grid_for(vec ? n / 16 + 1 : n, 256 * 16);
+    if (fmt == FP8_E4M3) {
+        if (out_dtype == FP8_F32) hipLaunchKernelGGL((dequantize_kernel<FP8_E4M3, FP8_F32>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
+        else hipLaunchKernelGGL((dequantize_kernel<FP8_E4M3, FP8_BF16>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
+    } else {
+        if (out_dtype == FP8_F32) hipLaunchKernelGGL((dequantize_kernel<FP8_E5M2, FP8_F32>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
+        else hipLaunchKernelGGL((dequantize_kernel<FP8_E5M2, FP8_BF16>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
+    }
+    return check_launch("dequantize");
 }
 
 }  // namespace fp8mm

@@ -25,7 +25,7 @@ inline bool valid_dtype(int d) { return d == FP8_F32 || d == FP8_BF16; }
 //               special-value rules applied around them
 // The converter path is the default (it was checked against the bit path on all 2^32 inputs);
 // the environment variable FP8MM_CAST_PATH=bits|cvt, read per call, overrides it.
-enum CastPath { kCastBits = 0, kCastCvt = 1 };
+enum CastPath { kCastBits = 0, kCastCvt = 1, kCastBitsStrict = 2 /* non-saturating, kernels only */ };
 CastPath cast_path();
 
 // ---- launchers (each enqueues on `stream` and returns a status) -------------------------
@@ -33,7 +33,9 @@ int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStrea
 float scale_from_amax_host(float amax, int fmt);
 int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream);
 int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
-                    const float* scale_dev, uint8_t* q_out, hipStream_t stream);
+                    const float* scale_dev, bool saturate, uint8_t* q_out, hipStream_t stream);
+int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
+                      int out_dtype, void* out, hipStream_t stream);
 int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
                 int64_t M, int64_t N, int64_t K, int out_dtype,
                 float sA, float sB, const float* sA_dev, const float* sB_dev,

@@ -37,6 +37,7 @@
 //
 // Generic kernel (any shape, any alignment): decodes to fp32 in LDS and uses plain FMAs.
 #include "common.hpp"
+#include "fp8_decode.hpp"
 
 namespace fp8mm {
 namespace {
@@ -402,21 +403,6 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 // decoded to fp32 (exactly) on their way into LDS, fp32 FMAs (each product of two FP8 values
 // is exact in fp32, so this is fp32 accumulation of exact products as well).
 // ------------------------------------------------------------------------------------------
-template <int FMT>
-__device__ __forceinline__ float decode_fp8(unsigned b)
-{
-    if (FMT == FP8_E5M2) {      // the upper byte of an IEEE half
-        return (float)__builtin_bit_cast(_Float16, (unsigned short)(b << 8));
-    }
-    const unsigned sign = (b & 0x80u) << 24;
-    const unsigned e = (b >> 3) & 15u, m = b & 7u;
-    float mag;
-    if (e == 15u && m == 7u) mag = as_f32(0x7fc00000u);
-    else if (e == 0u) mag = (float)m * 0.001953125f;                 // m * 2^-9
-    else mag = as_f32(((e + 120u) << 23) | (m << 20));               // 2^(e-7) * (1 + m/8)
-    return as_f32(as_u32(mag) | sign);
-}
-
 constexpr int GT = 64, GK = 16;
 
 template <int FMT_A, int FMT_B, int OUT>

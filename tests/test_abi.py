@@ -54,6 +54,11 @@ def test_invalid_arguments_are_rejected_without_a_launch():
     assert L.fp8_quantize(None, 4, 0, 0, 1.0, p, None) == INV
     assert L.fp8_quantize(p, 0, 0, 0, 1.0, None, None) == fp8.FP8_OK  # n == 0 launches nothing
     assert L.fp8_quantize_dscale(p, 4, 0, 0, None, p, None) == INV
+    assert L.fp8_quantize_ex(p, 4, 0, 0, 1.0, None, 2, p, None) == INV          # unknown flag
+    assert L.fp8_quantize_ex(p, 4, 0, 0, 1.0, p + 2, 0, p, None) == INV       # misaligned device scale
+    assert L.fp8_dequantize(p, 4, 3, 1.0, None, 0, p, None) == INV
+    assert L.fp8_dequantize(p, 4, 0, 1.0, None, 0, None, None) == INV
+    assert L.fp8_dequantize(None, 0, 0, 1.0, None, 1, None, None) == fp8.FP8_OK
     assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, -1, 4, 4, 0, None) == INV
     assert L.fp8_gemm(p, 2, 1.0, p, 0, 1.0, p, 4, 4, 4, 0, None) == INV
     assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, 4, 4, 4, 5, None) == INV

@@ -192,3 +192,84 @@ def test_full_fp32_sweep_against_oracle(fmt):
         want = oracle.quantize(x, fmt, 1.0)
         assert np.array_equal(got, want), report_byte_mismatch(bits, got, want)
         print("chunk %d/64 ok" % c, flush=True)
+
+
+# ---- conversion variants: strict (non-saturating) cast and the way back ---------------------------
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_strict_cast_matches_oracle(fmt):
+    bits = structured_fp32_patterns()
+    x = bits.view(np.float32)
+    xd = to_dev(x)
+    q = torch.empty(x.size, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_ex(xd, fmt, 1.0, fp8.FP8_QUANT_NOSAT, q)
+    torch.cuda.synchronize()
+    want = oracle.quantize(x, fmt, 1.0, saturating=False)
+    got = q.cpu().numpy()
+    assert np.array_equal(got, want), report_byte_mismatch(bits, got, want)
+    # bf16 input, real scale from device memory, ragged and misaligned
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)[:65536 - 3]
+    s = torch.tensor([3.3], dtype=torch.float32, device="cuda")
+    hd = to_dev(h)
+    q = torch.empty(h.size + 1, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_ex(hd, fmt, s, fp8.FP8_QUANT_NOSAT, q[1:])
+    torch.cuda.synchronize()
+    assert np.array_equal(q[1:].cpu().numpy(), oracle.quantize(h, fmt, np.float32(3.3), saturating=False))
+    # flags = 0 is the saturating cast
+    fp8.fp8_quantize_ex(hd, fmt, 3.3, 0, q[1:])
+    torch.cuda.synchronize()
+    assert np.array_equal(q[1:].cpu().numpy(), oracle.quantize(h, fmt, np.float32(3.3)))
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_quantize_ex(hd, fmt, 1.0, 8, q[1:])
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("fmt", FMTS)
+def test_dequantize_matches_oracle(fmt, out_dtype):
+    rng = np.random.default_rng(4)
+    q_np = np.concatenate([np.arange(256, dtype=np.uint8), rng.integers(0, 256, 100_003).astype(np.uint8)])
+    for scale in (1.0, 0.0973, 448.0 / 4657.0, 1234.5):
+        qd = to_dev(q_np)
+        out = torch.empty(q_np.size, dtype=out_dtype, device="cuda")
+        fp8.fp8_dequantize(qd, fmt, scale, out)
+        torch.cuda.synchronize()
+        exact = oracle.dequantize(q_np, fmt, np.float32(scale))            # decode / scale in fp64
+        got = out.float().cpu().numpy().astype(np.float64)
+        nan = np.isnan(exact)
+        assert np.array_equal(np.isnan(got), nan)
+        inf = np.isinf(exact)
+        assert np.array_equal(got[inf], exact[inf])
+        ok = ~nan & ~inf
+        # correctly rounded single-precision quotient (numpy's IEEE division), then bf16 RNE if asked
+        want32 = (oracle.decode_all(fmt)[q_np].astype(np.float32) / np.float32(scale))
+        if out_dtype == torch.float32:
+            assert np.array_equal(got[ok], want32[ok].astype(np.float64))
+            assert np.all(np.abs(got[ok] - exact[ok]) <= 0.5 * oracle.ulp(exact[ok], oracle.F32) * (1 + 1e-9))
+        else:
+            want16 = torch.from_numpy(want32).to(torch.bfloat16).float().numpy().astype(np.float64)
+            assert np.array_equal(got[ok], want16[ok])
+            assert np.all(np.abs(got[ok] - exact[ok]) <= 0.5 * oracle.ulp(exact[ok], oracle.BF16) * (1 + 2.0 ** -15))
+        assert np.array_equal(np.signbit(got[ok]), np.signbit(exact[ok]))
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_cast_and_back_is_the_simulated_fp8_of_the_paper(fmt):
+    """Cast to FP8 and back to the 16-bit type (how the paper's experiments simulate FP8,
+    Section 4): the round trip is idempotent and stays within half an FP8 step."""
+    h = synth.config2(1 << 20)
+    x = to_dev(h)
+    amax = torch.zeros(1, device="cuda"); scale = torch.zeros(1, device="cuda")
+    q = torch.empty(h.size, dtype=torch.uint8, device="cuda")
+    back = torch.empty(h.size, dtype=torch.float32, device="cuda")
+    q2 = torch.empty_like(q)
+    fp8.fp8_amax(x, amax)
+    fp8.fp8_scale_from_amax(amax, fmt, scale)
+    fp8.fp8_quantize_dscale(x, fmt, scale, q)
+    fp8.fp8_dequantize(q, fmt, scale, back)
+    fp8.fp8_quantize_dscale(back, fmt, scale, q2)
+    torch.cuda.synchronize()
+    same = (q == q2)
+    # a value can move by one code only if decode/scale*scale rounded across a midpoint in fp32: never for these
+    assert bool(same.all())
+    exact = oracle.dequantize(q.cpu().numpy(), fmt, np.float32(scale.item()))
+    assert np.array_equal(back.cpu().numpy(), exact.astype(np.float32))
