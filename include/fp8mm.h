@@ -152,6 +152,26 @@ int fp8_gemm_mfma8_dscale(const uint8_t* A, int fmtA, const float* sA,
                           const uint8_t* B, int fmtB, const float* sB,
                           void* C, int64_t M, int64_t N, int64_t K, int out_dtype, void* stream);
 
+/*
+ * fp8_gemm_ex -- the general form: C = (1 / (sA sB)) * op(A) x op(B), with each operand in
+ * either storage order.  It covers the three GEMMs of a linear layer's training step
+ * (Section 4.1: activations, weights and activation gradients are the GEMM inputs that are
+ * cast to FP8), without a transposed copy of any operand:
+ *     forward   Y  = X  W^T   X [tokens x in]   transA = 0;  W  [out x in]      transB = 1
+ *     dgrad     dX = dY W     dY[tokens x out]  transA = 0;  W  [out x in]      transB = 0
+ *     wgrad     dW = dY^T X   dY[tokens x out]  transA = 1;  X  [tokens x in]   transB = 0
+ *   transA = 0: A is M x K row-major;   transA = 1: A is given as K x M row-major
+ *   transB = 0: B is K x N row-major;   transB = 1: B is given as N x K row-major
+ *   sA_dev / sB_dev: both NULL (scales by value) or both device pointers (values ignored)
+ *   flags: FP8_GEMM_MFMA8 selects the FP8 matrix-core instructions (see fp8_gemm_mfma8)
+ * Error bounds, shape rules and error behaviour are those of fp8_gemm / fp8_gemm_mfma8.
+ */
+#define FP8_GEMM_MFMA8 1
+int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
+                float sA, float sB, const float* sA_dev, const float* sB_dev, int flags,
+                void* stream);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage. */
 const char* fp8_last_error(void);
 

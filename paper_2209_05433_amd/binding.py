@@ -12,13 +12,14 @@ FP8_E4M3, FP8_E5M2 = 0, 1
 FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
+FP8_GEMM_MFMA8 = 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
 EXPORTS = (
     "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_last_error", "fp8_version",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_last_error", "fp8_version",
 )
 
 _lib = None
@@ -53,6 +54,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_dscale.argtypes, L.fp8_gemm_dscale.restype = [vp, i, vp, vp, i, vp, vp, i64, i64, i64, i, vp], i
     L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
+    L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
     L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
     L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
     _lib = L
@@ -178,3 +180,24 @@ def fp8_gemm_mfma8(A, fmtA: int, sA: float, B, fmtB: int, sB: float, C, stream=N
 def fp8_gemm_mfma8_dscale(A, fmtA: int, sA: torch.Tensor, B, fmtB: int, sB: torch.Tensor, C,
                           stream=None) -> None:
     _gemm(lib().fp8_gemm_mfma8_dscale, A, fmtA, _dev(sA, "sA"), B, fmtB, _dev(sB, "sB"), C, stream)
+
+
+def fp8_gemm_ex(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, sB, flags: int = 0,
+                stream=None) -> None:
+    """A is [M, K] (or [K, M] if transA), B is [K, N] (or [N, K] if transB); sA and sB are both
+    floats or both one-element device tensors."""
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8 or A.dim() != 2 or B.dim() != 2:
+        raise ValueError("A and B must be 2-D uint8 tensors of FP8 bytes")
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    N, K2 = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not form C[M,N] = op(A)[M,K] op(B)[K,N]")
+    dev = isinstance(sA, torch.Tensor)
+    if dev != isinstance(sB, torch.Tensor):
+        raise ValueError("sA and sB must both be floats or both device tensors")
+    _check(lib().fp8_gemm_ex(_dev(A, "A") if A.numel() else None, fmtA, int(bool(transA)),
+                             _dev(B, "B") if B.numel() else None, fmtB, int(bool(transB)),
+                             _dev(C, "C") if C.numel() else None, M, N, K, dtype_code(C),
+                             0.0 if dev else float(sA), 0.0 if dev else float(sB),
+                             _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
+                             int(flags), _stream(stream)))

@@ -1,22 +1,31 @@
-"""Builds libfp8mm.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libfp8mm.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree.
+
+Every translation unit is compiled to an object of its own, in parallel; the tiled GEMM source is
+compiled four times, once per pair of operand storage orders (-DFP8MM_LAYOUT=0..3)."""
 from __future__ import annotations
 
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
+OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfp8mm.so")
-SOURCES = ["api.hip", "cast_kernels.hip", "gemm_kernels.hip"]
+
+# (source, extra defines, object name)
+UNITS = [("api.hip", [], "api.o"), ("cast_kernels.hip", [], "cast_kernels.o"),
+         ("gemm_kernels.hip", [], "gemm_dispatch.o")] + \
+        [("gemm_kernels.hip", ["-DFP8MM_LAYOUT=%d" % k], "gemm_layout%d.o" % k) for k in range(4)]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32
 # instructions from the scalar float code of the kernels.
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",
+    "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-unused-function",
 ]
 
 
@@ -27,10 +36,7 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source every time it is called; returns the path of the library."""
-    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -39,6 +45,18 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source every time it is called; returns the path of the library."""
+    os.makedirs(OBJ, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    jobs = [[hipcc(), *HIPCC_FLAGS, *inc, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ, obj)]
+            for src, defs, obj in UNITS]
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        list(ex.map(lambda c: _run(c, verbose), jobs))
+    _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB,
+          *[os.path.join(OBJ, obj) for _, _, obj in UNITS]], verbose)
     return LIB
 
 

@@ -131,7 +131,8 @@ int fp8_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float
 
 static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
                         int64_t M, int64_t N, int64_t K, int out_dtype, float sA, float sB,
-                        const float* sA_dev, const float* sB_dev, bool fp8_accumulate, void* stream)
+                        const float* sA_dev, const float* sB_dev, bool fp8_accumulate, void* stream,
+                        bool transA = false, bool transB = false)
 {
     clear_error();
     if (!valid_format(fmtA) || !valid_format(fmtB))
@@ -144,7 +145,7 @@ static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8
         const uintptr_t osz = out_dtype == FP8_F32 ? 4 : 2;
         if ((uintptr_t)C % osz) return fail(FP8_ERR_INVALID_ARG, "%s: C is not aligned to its element size", who);
     }
-    return launch_gemm(A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev, fp8_accumulate, (hipStream_t)stream);
+    return launch_gemm(A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev, transA, transB, fp8_accumulate, (hipStream_t)stream);
 }
 
 int fp8_gemm(const uint8_t* A, int fmtA, float sA, const uint8_t* B, int fmtB, float sB,
@@ -177,6 +178,19 @@ int fp8_gemm_mfma8_dscale(const uint8_t* A, int fmtA, const float* sA, const uin
         return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_mfma8_dscale: scale pointer is NULL or misaligned");
     }
     return gemm_checked("fp8_gemm_mfma8_dscale", A, fmtA, B, fmtB, C, M, N, K, out_dtype, 1.0f, 1.0f, sA, sB, true, stream);
+}
+
+int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
+                float sA, float sB, const float* sA_dev, const float* sB_dev, int flags, void* stream)
+{
+    clear_error();
+    if (flags & ~FP8_GEMM_MFMA8) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: unknown flag bits 0x%x", flags & ~FP8_GEMM_MFMA8);
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: transA/transB must be 0 or 1");
+    if ((sA_dev == nullptr) != (sB_dev == nullptr)) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: give both scales on the device or neither");
+    if (sA_dev && ((uintptr_t)sA_dev | (uintptr_t)sB_dev) % 4) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: scale pointer is misaligned");
+    return gemm_checked("fp8_gemm_ex", A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev,
+                        (flags & FP8_GEMM_MFMA8) != 0, stream, transA != 0, transB != 0);
 }
 
 }  // extern "C"

@@ -39,6 +39,6 @@ int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const fl
 int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
                 int64_t M, int64_t N, int64_t K, int out_dtype,
                 float sA, float sB, const float* sA_dev, const float* sB_dev,
-                bool fp8_accumulate, hipStream_t stream);
+                bool transA, bool transB, bool fp8_accumulate, hipStream_t stream);
 
 }  // namespace fp8mm

@@ -40,6 +40,19 @@
 #include "fp8_decode.hpp"
 
 namespace fp8mm {
+
+struct GemmArgs {
+    const uint8_t* A; const uint8_t* B; void* C;
+    int64_t M, N, K;
+    float sA, sB; const float* sA_dev; const float* sB_dev;
+    bool transA, transB;
+    hipStream_t stream;
+};
+int launch_tiled_nn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
+int launch_tiled_nt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
+int launch_tiled_tn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
+int launch_tiled_tt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
+
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -75,21 +88,25 @@ __device__ __forceinline__ double alpha_of(float sA, float sB, const float* sA_d
 // Fast kernel
 // ------------------------------------------------------------------------------------------
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int B_SLOTS = 4;                   // B ring: one 64 x 256 slab (16 KB) per stage
-constexpr int A_SLOTS = 3;                   // A ring: one 256 x 128 slab (32 KB) per PAIR of stages
-constexpr int B_SLAB = BK * BN;              // 16 KB
-constexpr int A_SLAB = BM * 2 * BK;          // 32 KB
-constexpr int A_BASE = B_SLOTS * B_SLAB;     // A ring starts behind the B ring
-constexpr int FAST_LDS = A_BASE + A_SLOTS * A_SLAB;   // 160 KB: all of the LDS of a compute unit
+// An operand tile is staged in one of two ways, depending on how the operand lies in memory:
+//   K-contiguous  (A row-major M x K; B given as N x K): one 256 x 128 slab (32 KB) per PAIR of
+//                 stages, fragments by 16-byte LDS reads;
+//   MN-contiguous (B row-major K x N; A given as K x M): one 64 x 256 slab (16 KB) per stage,
+//                 ring of four, fragments by the transposing 8-byte LDS read.
+constexpr int KC_SLAB = 256 * 128;           // 32 KB
+constexpr int MC_SLAB = 64 * 256;            // 16 KB
+constexpr int MC_SLOTS = 4;
+constexpr int FAST_LDS = 160 * 1024;         // all of the LDS of a compute unit
 constexpr int FAST_THREADS = 256;
 constexpr int GROUP_M = 8;                   // tile rows per band of the tile order
 constexpr int NUM_XCD = 8;
 
-// Chunk swizzles.  A slab: rows of 128 B = 8 chunks; B slab: rows of 256 B = 16 chunks.
-// Measured on gfx950: with these a 16-byte fragment read of A costs 5 clocks per wave instruction
-// (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read of B 7.3 clocks.
-__device__ __forceinline__ int swz_a(int row) { return (row >> 1) & 7; }
-__device__ __forceinline__ int swz_b(int krow) { return krow & 7; }
+// Chunk swizzles.  K-contiguous slab: rows of 128 B = 8 chunks; MN-contiguous slab: rows of
+// 256 B = 16 chunks.  Measured on gfx950: with these a 16-byte fragment read costs 5 clocks per
+// wave instruction (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read
+// 7.3 clocks.
+__device__ __forceinline__ int swz_kc(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ int swz_mc(int krow) { return krow & 7; }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
 // vmcnt = bits 3:0 and 15:14, expcnt = 6:4, lgkmcnt = 11:8).
@@ -150,13 +167,98 @@ __device__ __forceinline__ v8h widen8(int lo, int hi)
     return (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
 }
 
-template <int FMT_A, int FMT_B, int OUT, int ACC>
+// One operand of the tile as the kernel sees it.  r = row of A / column of B inside the 256-wide
+// tile, k = position along K:
+//   KC: element (r, k) at tile + r * ld + k;   MC: element (r, k) at tile + k * ld + r.
+struct Operand {
+    const uint8_t* tile;     // first byte of the tile's rows (KC) or columns (MC)
+    unsigned ld;             // leading dimension in bytes
+    unsigned off[8];         // per-lane offsets of this wave's direct loads (8 used by KC, 4 by MC)
+    unsigned region;         // LDS byte offset of the operand's ring
+    unsigned rd;             // per-lane LDS offset of its first fragment read (region included)
+};
+
+template <bool KC>
+__device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, unsigned ld, int r0, unsigned region,
+                                              int w, int l, int wsel)
+{
+    op.ld = ld;
+    op.region = region;
+    const int h = l >> 5;
+    if (KC) {
+        op.tile = base + (size_t)r0 * ld;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {                 // instruction ia fills rows 8 ia .. 8 ia + 7 (1 KB)
+            const int row = (w * 8 + t) * 8 + (l >> 3);
+            op.off[t] = (unsigned)row * ld + (((l & 7) ^ swz_kc(row)) * 16);
+        }
+        // lane = (r = l % 32, h = l / 32) reads K bytes 32h .. 32h+31 of row r of its stage:
+        // chunks 4 par + 2h and + 1 of the 128-byte row (par = stage parity)
+        const int row = wsel * 128 + (l & 31);
+        op.rd = region + row * 128 + (((2 * h) ^ swz_kc(row)) * 16);
+    } else {
+        op.tile = base + r0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {                 // instruction ib fills K-rows 4 ib .. 4 ib + 3 (1 KB)
+            const int krow = (w * 4 + t) * 4 + (l >> 4);
+            op.off[t] = (unsigned)krow * ld + (((l & 15) ^ swz_mc(krow)) * 16);
+        }
+#pragma unroll
+        for (int t = 4; t < 8; ++t) op.off[t] = 0;
+        // lane = (r = l % 32, h): column r, K bytes 32h .. 32h+31, gathered by four transposing
+        // reads of 8 K-rows x 16 columns per 16-lane group; lanes 2q and 2q+1 address K-row q
+        const int t16 = l & 15, gq = (l >> 4) & 1;
+        const int krow = 32 * h + (t16 >> 1);
+        op.rd = region + krow * 256 + (((wsel * 8 + gq) ^ swz_mc(krow)) * 16) + (t16 & 1) * 8;
+    }
+}
+
+// Direct loads are written as inline assembly: the compiler then keeps no account of them and
+// inserts no waits of its own; completion is tracked by explicit vmcnt waits.  LDS placement:
+// M0 holds the wave-uniform base, lane i writes 16 bytes at M0 + 16 i.
+__device__ __forceinline__ void direct_load(const uint8_t* base, unsigned off, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
+}
+
+// Part j (0..7) of the fragment reads of stage kt: 16 bytes per lane of block j/2 (half j%2 of
+// the lane's 32 bytes) of one operand, as one 16-byte read (KC) or two transposing reads (MC).
+template <bool KC>
+__device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op, int kt, int kc_slot, int j,
+                                          v8i (&f)[4])
+{
+    const int blk = j >> 1, half = j & 1;
+    if (KC) {
+        const unsigned addr = (op.rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + kc_slot * KC_SLAB + blk * 32 * 128;
+        const v4i a = *LDS_PTR(v4i, smem + addr);
+        f[blk][4 * half + 0] = a.x; f[blk][4 * half + 1] = a.y; f[blk][4 * half + 2] = a.z; f[blk][4 * half + 3] = a.w;
+    } else {
+        const unsigned base = (unsigned)(kt & (MC_SLOTS - 1)) * MC_SLAB + (op.rd ^ (unsigned)(blk * 32));
+#pragma unroll
+        for (int s = 2 * half; s < 2 * half + 2; ++s) {
+            const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * 256));
+            f[blk][2 * s] = p.x; f[blk][2 * s + 1] = p.y;
+        }
+    }
+}
+
+// A_KC / B_KC: how the operand lies in memory (see Operand).  LDS: an MN-contiguous operand takes
+// 64 KB (ring of four stages); a K-contiguous one 96 KB (ring of three stage pairs), or 64 KB
+// (ring of two pairs) for B when both operands are K-contiguous.
+template <int FMT_A, int FMT_B, int OUT, int ACC, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
     int M, int N, int K, float sA, float sB, const float* __restrict__ sA_dev,
     const float* __restrict__ sB_dev, int group_m)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    constexpr int A_RING = 3;                               // stage pairs in A's ring (if A_KC)
+    constexpr int B_RING = A_KC ? 2 : 3;                    // stage pairs in B's ring (if B_KC)
+    constexpr bool HAS_MC = !A_KC || !B_KC;
+    // LDS map: the 64 KB operand (MN-contiguous, or B when both are K-contiguous) first.
+    constexpr unsigned A_REGION = A_KC ? 65536u : 0u;
+    constexpr unsigned B_REGION = A_KC ? 0u : 65536u;
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
@@ -164,72 +266,71 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const TileMap tile = map_tile(blockIdx.x, M / BM, N / BN, group_m);
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
     const int KT = K / BK;
-
-    // ---- direct global->LDS loads ------------------------------------------------------------
-    // B, every stage: 4 instructions per wave; instruction ib (0..15) fills K-rows 4 ib .. 4 ib+3
-    // of the 64 x 256 slab (1 KB): lane -> (K-row, 16-byte chunk).
-    // A, every second stage: 8 instructions per wave; instruction ia (0..31) fills rows 8 ia ..
-    // 8 ia + 7 of the 256 x 128 slab that serves two stages, so that every request to the L2 is a
-    // whole 128-byte line (with 64-byte row pieces the vector L1 asks for every line twice).
-    const uint8_t* a_tile = A + (size_t)m0 * K;
-    const uint8_t* b_tile = B + n0;
-    unsigned a_off[8], b_off[4];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const int ia = w * 8 + t;
-        const int row = ia * 8 + (l >> 3);
-        const int lc = (l & 7) ^ swz_a(row);
-        a_off[t] = (unsigned)row * (unsigned)K + lc * 16;
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int ib = w * 4 + t;
-        const int krow = ib * 4 + (l >> 4);
-        const int lcb = (l & 15) ^ swz_b(krow);
-        b_off[t] = (unsigned)krow * (unsigned)N + lcb * 16;
-    }
-    // Direct loads are written as inline assembly: the compiler then keeps no account of them
-    // and inserts no waits of its own; completion is tracked by the explicit vmcnt waits below.
-    // LDS placement: M0 holds the wave-uniform base, lane i writes 16 bytes at M0 + 16 i.
-    auto direct_load = [](const uint8_t* base, unsigned off, unsigned lds_addr) {
-        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                     :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
-    };
-    const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
-    auto issue_b = [&](int kt, int t) {          // instruction t (0..3) of the B slab of stage kt
-        direct_load(b_tile + (size_t)kt * BK * N, b_off[t],
-                    lds0 + (kt & (B_SLOTS - 1)) * B_SLAB + w * 4096 + t * 1024);
-    };
-    auto issue_a = [&](int pair, int aslot, int t) {   // instruction t (0..7) of the A slab of a stage pair
-        direct_load(a_tile + (size_t)pair * 2 * BK, a_off[t], lds0 + A_BASE + aslot * A_SLAB + w * 8192 + t * 1024);
-    };
-
-    // ---- fragment addresses -----------------------------------------------------------------
-    // A fragment (MFMA operand 1): lane = (m = l % 32, h = l / 32) reads K bytes 32h .. 32h+31 of
-    // row m of its stage: chunks 4 par + 2h and + 1 of the 128-byte row (par = stage parity).
     const int h = l >> 5;
-    const int a_row = wm * 128 + (l & 31);
-    const unsigned a_rd = A_BASE + a_row * 128 + (((2 * h) ^ swz_a(a_row)) * 16);   // par 0, first chunk
-    // B fragment (MFMA operand 0): lane = (n = l % 32, h): column n, K bytes 32h .. 32h+31,
-    // gathered by four transposing reads of 8 K-rows x 16 columns per 16-lane group.
-    const int t16 = l & 15, gq = (l >> 4) & 1;
-    const int b_krow = 32 * h + (t16 >> 1);     // lanes 2r and 2r+1 of a group address K-row r
-    const int b_half = t16 & 1;
-    const int b_pc = (wn * 8 + gq) ^ swz_b(b_krow);
-    const unsigned b_rd = b_krow * BN + b_pc * 16 + b_half * 8;
+    const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
 
-    // The 24 fragment reads of a stage come in 8 parts of three: part j is one 16-byte read of A
-    // block j/2 (half j%2 of the lane's 32 bytes) and two transposing reads of B block j/2.
-    auto read_part = [&](int kt, int aslot, int j, v8i (&af)[4], v8i (&bf)[4]) {
-        const int blk = j >> 1, half = j & 1;
-        const unsigned a_addr = (a_rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + aslot * A_SLAB + blk * 32 * 128;
-        const v4i a = *LDS_PTR(v4i, smem + a_addr);
-        af[blk][4 * half + 0] = a.x; af[blk][4 * half + 1] = a.y; af[blk][4 * half + 2] = a.z; af[blk][4 * half + 3] = a.w;
-        const unsigned base = (unsigned)(kt & (B_SLOTS - 1)) * B_SLAB + (b_rd ^ (unsigned)(blk * 32));
-#pragma unroll
-        for (int s = 2 * half; s < 2 * half + 2; ++s) {
-            const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * BN));
-            bf[blk][2 * s] = p.x; bf[blk][2 * s + 1] = p.y;
+    Operand opA, opB;
+    operand_setup<A_KC>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, A_REGION, w, l, wm);
+    operand_setup<B_KC>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, B_REGION, w, l, wn);
+
+    // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
+    // the steps -5 .. -1).  Step s issues, in this order:
+    //   if s is odd: for each K-contiguous operand the slab of stage pair (s+1)/2 + ring - 1
+    //                (8 loads per wave, in parts 0..3), A before B;
+    //   for each MN-contiguous operand the slab of stage s + 4 (4 loads per wave, parts 4..7).
+    auto kc_pair_of = [](int s, int ring) { return (s + 1) / 2 + ring - 1; };     // s odd (may be negative)
+    auto pair_valid = [&](int p) { return p >= 0 && 2 * p < KT; };
+    auto stage_valid = [&](int st) { return st >= 0 && st < KT; };
+    auto count_step = [&](int s) {
+        int n = 0;
+        if (s & 1) {
+            if (A_KC && pair_valid(kc_pair_of(s, A_RING))) n += 8;
+            if (B_KC && pair_valid(kc_pair_of(s, B_RING))) n += 8;
+        }
+        if (!A_KC && stage_valid(s + 4)) n += 4;
+        if (!B_KC && stage_valid(s + 4)) n += 4;
+        return n;
+    };
+    // Loads complete in order.  Stage t is complete once the last load issued for it is: that is
+    // the last load of step t - 4 if an operand is MN-contiguous, else of the step that issued
+    // B's pair t/2.  `upto` = last step whose loads have been issued when the wait is placed.
+    // When a step waits for the stage after its own and every step of the window issues its full
+    // set, the count depends on the parity of the step alone and is a compile-time constant.
+    constexpr int KC_OPS = (A_KC ? 1 : 0) + (B_KC ? 1 : 0);
+    constexpr int STEADY_EVEN = HAS_MC ? 8 * KC_OPS + 8 * (2 - KC_OPS) : 16;   // the wait at the start of an even step
+    constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : 0;
+    auto wait_stage = [&](int t, int upto) {
+        const int s_need = HAS_MC ? t - 4 : 2 * (t / 2) - 2 * B_RING + 1;
+        int allowed = 0;
+        for (int s = s_need + 1; s <= upto; ++s) allowed += count_step(s);
+        switch (allowed) {
+            case 0: wait_vmcnt<0>(); break;   case 4: wait_vmcnt<4>(); break;
+            case 8: wait_vmcnt<8>(); break;   case 12: wait_vmcnt<12>(); break;
+            case 16: wait_vmcnt<16>(); break; case 20: wait_vmcnt<20>(); break;
+            case 24: wait_vmcnt<24>(); break; case 28: wait_vmcnt<28>(); break;
+            case 32: wait_vmcnt<32>(); break; case 36: wait_vmcnt<36>(); break;
+            default: wait_vmcnt<0>(); break;
+        }
+    };
+    auto issue_kc = [&](const Operand& op, int pair, int slot, int t) {
+        direct_load(op.tile + (size_t)pair * 2 * BK, op.off[t],
+                    lds0 + op.region + slot * KC_SLAB + w * 8192 + t * 1024);
+    };
+    auto issue_mc = [&](const Operand& op, int st, int t) {
+        direct_load(op.tile + (size_t)st * BK * op.ld, op.off[t],
+                    lds0 + op.region + (st & (MC_SLOTS - 1)) * MC_SLAB + w * 4096 + t * 1024);
+    };
+    // the loads of step s that fall into part j; sa, sb = ring slots the K-contiguous slabs of
+    // this step go to (the slots of the pair that stage s ends)
+    auto issue_part = [&](int s, bool odd, int j, int sa, int sb) {
+        if (j < 4) {
+            if (odd) {
+                if (A_KC) { const int p = kc_pair_of(s, A_RING); if (pair_valid(p)) { issue_kc(opA, p, sa, 2 * j); issue_kc(opA, p, sa, 2 * j + 1); } }
+                if (B_KC) { const int p = kc_pair_of(s, B_RING); if (pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); } }
+            }
+        } else if (stage_valid(s + 4)) {
+            if (!A_KC) issue_mc(opA, s + 4, j - 4);
+            if (!B_KC) issue_mc(opB, s + 4, j - 4);
         }
     };
 
@@ -269,91 +370,74 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             }
         }
     };
+    constexpr int READS_PER_PART = (A_KC ? 1 : 2) + (B_KC ? 1 : 2);
     auto sched_part = [&]() {
         if (ACC == ACC_FP8) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // two LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, (READS_PER_PART + 1) / 2, 0); // LDS reads
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, READS_PER_PART / 2, 0);
         } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // MFMA
-                if (i % 3 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                   // widening
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
+                if (i % 2 == 0 && i / 2 < READS_PER_PART) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                    // widening
             }
         }
     };
+    auto read_both = [&](int kt, int j, int sa, int sb, v8i (&af)[4], v8i (&bf)[4]) {
+        read_part<A_KC>(smem, opA, kt, sa, j, af);
+        read_part<B_KC>(smem, opB, kt, sb, j, bf);
+    };
 
     // One K stage kt (not the last).  The frags of stage kt are in (af, bf); their LDS reads were
-    // issued a stage ago.  First stage kt+1 is made visible.  Then, in 8 parts: direct loads are
-    // issued (B slab of stage kt+4 into the slot of stage kt in every stage; in odd stages also the
-    // A slab of stage pair (kt+1)/2+2 into the slot of the pair that stage kt ends), an eighth of
-    // the MFMAs of stage kt runs, and three fragment reads of stage kt+1 go out into (af_n, bf_n).
-    // Order of issue, which the vmcnt arithmetic relies on: within a stage all A loads precede
-    // the B loads; so exactly 16 loads follow the last load of the B slab of stage kt+1 when stage
-    // kt begins (12 of one odd stage, 4 of one even stage).
-    auto k_step = [&](int kt, bool odd, int aslot_next, int aslot_free, v8i (&af)[4], v8i (&bf)[4],
+    // issued a stage ago.  First stage kt+1 is made visible.  Then, in 8 parts, the direct loads of
+    // step kt are issued (into the slots that stage kt, whose frags are in registers, has freed),
+    // an eighth of the MFMAs of stage kt runs, and the fragment reads of stage kt+1 go out into
+    // (af_n, bf_n).  Spreading matters: the four waves run in step, and a wave that issues its
+    // loads in one burst waits for the address unit before it reaches its first MFMA.
+    // (sa, sb) = ring slots of the pair of stage kt, (sa_n, sb_n) = of the pair of stage kt+1.
+    auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[4],
                       v8i (&af_n)[4], v8i (&bf_n)[4]) {
-        if (kt + B_SLOTS < KT) wait_vmcnt<16>(); else wait_vmcnt<0>();
+        if (kt + 8 < KT) {
+            if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
+        } else {
+            wait_stage(kt + 1, kt - 1);
+        }
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
-        const bool more_b = kt + B_SLOTS < KT;
-        const int pair_new = (kt + 1) / 2 + 2;
-        const bool more_a = odd && 2 * pair_new < KT;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (odd) {                        // odd stage: 8 A loads in parts 0..3, 4 B loads in parts 4..7
-                if (j < 4) { if (more_a) { issue_a(pair_new, aslot_free, 2 * j); issue_a(pair_new, aslot_free, 2 * j + 1); } }
-                else if (more_b) issue_b(kt + B_SLOTS, j - 4);
-            } else if (j >= 4 && more_b) issue_b(kt + B_SLOTS, j - 4);
-            read_part(kt + 1, aslot_next, j, af_n, bf_n);
+            issue_part(kt, odd, j, sa, sb);
+            read_both(kt + 1, j, sa_n, sb_n, af_n, bf_n);
             compute_part(j, af, bf);
             sched_part();
         }
     };
 
-    // Prologue: the same order of issue as the steady state would have produced
-    // (A0, B0, A1, B1, B2, A2, B3), stage 0 visible, its frags read.  KT is even and >= 2.
+    // Prologue: steps -5 .. -1 of the same schedule, then stage 0 visible and its frags read.
+    // KT is even and >= 2.
     v8i af0[4], bf0[4], af1[4], bf1[4];
-    {
+    for (int s = -5; s < 0; ++s) {
+        // pair issued by odd step s < 0 is (s+1)/2 + ring - 1 < ring: slot = pair
+        const int sa = A_KC ? (s + 1) / 2 + A_RING - 1 : 0, sb = B_KC ? (s + 1) / 2 + B_RING - 1 : 0;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) issue_a(0, 0, t);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) issue_b(0, t);
-        if (KT > 2) {
-#pragma unroll
-            for (int t = 0; t < 8; ++t) issue_a(1, 1, t);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) issue_b(1, t);
-        if (KT > 2) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) issue_b(2, t);
-        }
-        if (KT > 4) {
-#pragma unroll
-            for (int t = 0; t < 8; ++t) issue_a(2, 2, t);
-        }
-        if (KT > 2) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) issue_b(3, t);
-        }
-        // stage 0 = A slab 0 + B slab 0: everything issued after B0 may still be in flight
-        if (KT > 4) wait_vmcnt<28>(); else if (KT > 2) wait_vmcnt<20>(); else wait_vmcnt<4>();
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int j = 0; j < 8; ++j) read_part(0, 0, j, af0, bf0);
+        for (int j = 0; j < 8; ++j) issue_part(s, s & 1, j, sa, sb);
     }
-    // Stage pair p = stages 2p, 2p+1 lives in A slot p % 3.
-    int aslot = 0;                            // slot of the pair the even stage belongs to
+    wait_stage(0, -1);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) read_both(0, j, 0, 0, af0, bf0);
+    int sa = 0, sb = 0;                       // ring slots of the current stage pair
     for (int kt = 0; kt < KT - 2; kt += 2) {
-        const int aslot_n = aslot == A_SLOTS - 1 ? 0 : aslot + 1;
-        k_step(kt, false, aslot, aslot, af0, bf0, af1, bf1);         // reads stage kt+1: same pair
-        k_step(kt + 1, true, aslot_n, aslot, af1, bf1, af0, bf0);    // reads stage kt+2: next pair; frees this pair's slot
-        aslot = aslot_n;
+        const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+        const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+        k_step(kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
+        k_step(kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
+        sa = sa_n; sb = sb_n;
     }
-    k_step(KT - 2, false, aslot, aslot, af0, bf0, af1, bf1);
+    k_step(KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) compute_part(j, af1, bf1);
 
@@ -409,7 +493,7 @@ template <int FMT_A, int FMT_B, int OUT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
     int64_t M, int64_t N, int64_t K, float sA, float sB, const float* __restrict__ sA_dev,
-    const float* __restrict__ sB_dev)
+    const float* __restrict__ sB_dev, bool transA, bool transB)
 {
     __shared__ float As[GK][GT + 1];
     __shared__ float Bs[GK][GT + 1];
@@ -421,10 +505,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
         for (int e = tid; e < GT * GK; e += 256) {
             const int r = e / GK, kk = e % GK;              // A: consecutive lanes along K
             const int64_t gm = m0 + r, gk = k0 + kk;
-            As[kk][r] = (gm < M && gk < K) ? decode_fp8<FMT_A>(A[gm * K + gk]) : 0.0f;
+            As[kk][r] = (gm < M && gk < K) ? decode_fp8<FMT_A>(A[transA ? gk * M + gm : gm * K + gk]) : 0.0f;
             const int kb = e / GT, c = e % GT;              // B: consecutive lanes along N
             const int64_t gn = n0 + c, gkb = k0 + kb;
-            Bs[kb][c] = (gn < N && gkb < K) ? decode_fp8<FMT_B>(B[gkb * N + gn]) : 0.0f;
+            Bs[kb][c] = (gn < N && gkb < K) ? decode_fp8<FMT_B>(B[transB ? gn * K + gkb : gkb * N + gn]) : 0.0f;
         }
         __syncthreads();
 #pragma unroll
@@ -457,48 +541,59 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 
 // ---- dispatch ----------------------------------------------------------------------------
 int group_m_setting();
-struct GemmArgs {
-    const uint8_t* A; const uint8_t* B; void* C;
-    int64_t M, N, K;
-    float sA, sB; const float* sA_dev; const float* sB_dev;
-    hipStream_t stream;
-};
 
-template <int FA, int FB, int OUT, int ACC>
+template <int FA, int FB, int OUT, int ACC, bool A_KC, bool B_KC>
 int launch_fast(const GemmArgs& g)
 {
-    {
-        static bool attr_set = false;
-        auto kern = gemm_fast_kernel<FA, FB, OUT, ACC>;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void*)kern,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
-            if (e != hipSuccess)
-                return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
-            attr_set = true;
-        }
-        const int tiles = (int)((g.M / BM) * (g.N / BN));
-        hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
-                           (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, group_m_setting());
-        return check_launch("gemm (fast kernel)");
+    static bool attr_set = false;
+    auto kern = gemm_fast_kernel<FA, FB, OUT, ACC, A_KC, B_KC>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
+        if (e != hipSuccess)
+            return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
+        attr_set = true;
     }
+    const int tiles = (int)((g.M / BM) * (g.N / BN));
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
+                       (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, group_m_setting());
+    return check_launch("gemm (tiled kernel)");
+}
+
+// The tiled kernel is instantiated in four translation units, one per pair of storage orders
+// (FP8MM_LAYOUT = 2 * transA + transB), so that they compile in parallel; the unit without
+// FP8MM_LAYOUT holds the generic kernel and the dispatcher.
+template <bool A_KC, bool B_KC>
+int launch_tiled(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc)
+{
+#define FP8MM_CASE(FA, FB)                                                                                  \
+    if (fmtA == FA && fmtB == FB) {                                                                        \
+        if (out_dtype == FP8_F32)                                                                          \
+            return acc == ACC_FP8 ? launch_fast<FA, FB, FP8_F32, ACC_FP8, A_KC, B_KC>(g)                   \
+                                  : launch_fast<FA, FB, FP8_F32, ACC_F16, A_KC, B_KC>(g);                  \
+        return acc == ACC_FP8 ? launch_fast<FA, FB, FP8_BF16, ACC_FP8, A_KC, B_KC>(g)                      \
+                              : launch_fast<FA, FB, FP8_BF16, ACC_F16, A_KC, B_KC>(g);                     \
+    }
+    FP8MM_CASE(FP8_E4M3, FP8_E4M3)
+    FP8MM_CASE(FP8_E4M3, FP8_E5M2)
+    FP8MM_CASE(FP8_E5M2, FP8_E4M3)
+    FP8MM_CASE(FP8_E5M2, FP8_E5M2)
+#undef FP8MM_CASE
+    return fail(FP8_ERR_INVALID_ARG, "gemm: bad operand formats");
 }
 
 template <int FA, int FB, int OUT>
-int launch_typed(const GemmArgs& g, bool fast, int acc)
+int launch_generic_typed(const GemmArgs& g)
 {
-    if (fast) return acc == ACC_FP8 ? launch_fast<FA, FB, OUT, ACC_FP8>(g) : launch_fast<FA, FB, OUT, ACC_F16>(g);
     const dim3 grid((unsigned)((g.N + GT - 1) / GT), (unsigned)((g.M + GT - 1) / GT));
     hipLaunchKernelGGL((gemm_generic_kernel<FA, FB, OUT>), grid, dim3(256), 0, g.stream, g.A, g.B,
-                       g.C, g.M, g.N, g.K, g.sA, g.sB, g.sA_dev, g.sB_dev);
+                       g.C, g.M, g.N, g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, g.transA, g.transB);
     return check_launch("gemm (generic kernel)");
 }
 
 template <int FA, int FB>
-int launch_out(const GemmArgs& g, int out_dtype, bool fast, int acc)
+int launch_generic_out(const GemmArgs& g, int out_dtype)
 {
-    return out_dtype == FP8_F32 ? launch_typed<FA, FB, FP8_F32>(g, fast, acc)
-                                : launch_typed<FA, FB, FP8_BF16>(g, fast, acc);
+    return out_dtype == FP8_F32 ? launch_generic_typed<FA, FB, FP8_F32>(g) : launch_generic_typed<FA, FB, FP8_BF16>(g);
 }
 
 __global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
@@ -519,6 +614,18 @@ int group_m_setting()
     return v > 0 ? v : GROUP_M;
 }
 }  // namespace
+
+#if defined(FP8MM_LAYOUT)
+#if FP8MM_LAYOUT == 0
+int launch_tiled_nn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<true, false>(g, fmtA, fmtB, out_dtype, acc); }
+#elif FP8MM_LAYOUT == 1
+int launch_tiled_nt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<true, true>(g, fmtA, fmtB, out_dtype, acc); }
+#elif FP8MM_LAYOUT == 2
+int launch_tiled_tn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<false, false>(g, fmtA, fmtB, out_dtype, acc); }
+#else
+int launch_tiled_tt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<false, true>(g, fmtA, fmtB, out_dtype, acc); }
+#endif
+#else
 static bool force_generic()
 {
     const char* e = getenv("FP8MM_GEMM");
@@ -527,8 +634,8 @@ static bool force_generic()
 
 int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
                 int64_t M, int64_t N, int64_t K, int out_dtype,
-                float sA, float sB, const float* sA_dev, const float* sB_dev, bool fp8_accumulate,
-                hipStream_t stream)
+                float sA, float sB, const float* sA_dev, const float* sB_dev, bool transA, bool transB,
+                bool fp8_accumulate, hipStream_t stream)
 {
     const int acc = fp8_accumulate ? ACC_FP8 : ACC_F16;
     if (M == 0 || N == 0) return FP8_OK;
@@ -538,17 +645,22 @@ int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
         return check_launch("gemm (K = 0 fill)");
     }
     const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0;
-    const bool fits32 = (uint64_t)BM * (uint64_t)K < (1ull << 32) && (uint64_t)K * (uint64_t)N < (1ull << 32) * 64
-                        && (uint64_t)BK * (uint64_t)N < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
+    const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
+    const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
                         && (M / BM) * (N / BN) < (1ll << 31);
     const bool fast = !force_generic() && aligned && fits32 && M % BM == 0 && N % BN == 0 && K % (2 * BK) == 0;
-    GemmArgs g{A, B, C, M, N, K, sA, sB, sA_dev, sB_dev, stream};
-    if (fmtA == FP8_E4M3) {
-        return fmtB == FP8_E4M3 ? launch_out<FP8_E4M3, FP8_E4M3>(g, out_dtype, fast, acc)
-                                : launch_out<FP8_E4M3, FP8_E5M2>(g, out_dtype, fast, acc);
+    GemmArgs g{A, B, C, M, N, K, sA, sB, sA_dev, sB_dev, transA, transB, stream};
+    if (fast) {
+        if (!transA) return transB ? launch_tiled_nt(g, fmtA, fmtB, out_dtype, acc) : launch_tiled_nn(g, fmtA, fmtB, out_dtype, acc);
+        return transB ? launch_tiled_tt(g, fmtA, fmtB, out_dtype, acc) : launch_tiled_tn(g, fmtA, fmtB, out_dtype, acc);
     }
-    return fmtB == FP8_E4M3 ? launch_out<FP8_E5M2, FP8_E4M3>(g, out_dtype, fast, acc)
-                            : launch_out<FP8_E5M2, FP8_E5M2>(g, out_dtype, fast, acc);
+    if (fmtA == FP8_E4M3) {
+        return fmtB == FP8_E4M3 ? launch_generic_out<FP8_E4M3, FP8_E4M3>(g, out_dtype)
+                                : launch_generic_out<FP8_E4M3, FP8_E5M2>(g, out_dtype);
+    }
+    return fmtB == FP8_E4M3 ? launch_generic_out<FP8_E5M2, FP8_E4M3>(g, out_dtype)
+                            : launch_generic_out<FP8_E5M2, FP8_E5M2>(g, out_dtype);
 }
+#endif
 
 }  // namespace fp8mm
