@@ -275,18 +275,22 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 
     // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
     // the steps -5 .. -1).  Step s issues, in this order:
-    //   if s is odd: for each K-contiguous operand the slab of stage pair (s+1)/2 + ring - 1
-    //                (8 loads per wave, in parts 0..3), A before B;
-    //   for each MN-contiguous operand the slab of stage s + 4 (4 loads per wave, parts 4..7).
+    //   for a K-contiguous operand, in parts 0..3: if s is odd the first four loads of the slab of
+    //                stage pair (s+1)/2 + ring - 1 (into the slot that stage s frees), if s is
+    //                even the other four loads of pair s/2 + ring - 1;
+    //   for an MN-contiguous operand the slab of stage s + 4 (4 loads per wave, parts 4..7).
+    // If both operands are K-contiguous, B's ring holds two pairs only and its loads have less
+    // than two steps to arrive; they must not queue behind A's.  Then the odd steps issue B alone
+    // and the even step s issues A's pair s/2 + 2, one load per part, into the slot of the pair
+    // that ended a step ago (three steps of lead are left).
     auto kc_pair_of = [](int s, int ring) { return (s + 1) / 2 + ring - 1; };     // s odd (may be negative)
     auto pair_valid = [&](int p) { return p >= 0 && 2 * p < KT; };
     auto stage_valid = [&](int st) { return st >= 0 && st < KT; };
     auto count_step = [&](int s) {
         int n = 0;
-        if (s & 1) {
-            if (A_KC && pair_valid(kc_pair_of(s, A_RING))) n += 8;
-            if (B_KC && pair_valid(kc_pair_of(s, B_RING))) n += 8;
-        }
+        if (A_KC && B_KC) return ((s & 1) ? pair_valid(kc_pair_of(s, B_RING)) : pair_valid(s / 2 + A_RING - 1)) ? 8 : 0;
+        if (A_KC && pair_valid((s & 1) ? kc_pair_of(s, A_RING) : s / 2 + A_RING - 1)) n += 4;
+        if (B_KC && pair_valid((s & 1) ? kc_pair_of(s, B_RING) : s / 2 + B_RING - 1)) n += 4;
         if (!A_KC && stage_valid(s + 4)) n += 4;
         if (!B_KC && stage_valid(s + 4)) n += 4;
         return n;
@@ -298,7 +302,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // set, the count depends on the parity of the step alone and is a compile-time constant.
     constexpr int KC_OPS = (A_KC ? 1 : 0) + (B_KC ? 1 : 0);
     constexpr int STEADY_EVEN = HAS_MC ? 8 * KC_OPS + 8 * (2 - KC_OPS) : 16;   // the wait at the start of an even step
-    constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : 0;
+    constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : 8;
     auto wait_stage = [&](int t, int upto) {
         const int s_need = HAS_MC ? t - 4 : 2 * (t / 2) - 2 * B_RING + 1;
         int allowed = 0;
@@ -321,13 +325,22 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                     lds0 + op.region + (st & (MC_SLOTS - 1)) * MC_SLAB + w * 4096 + t * 1024);
     };
     // the loads of step s that fall into part j; sa, sb = ring slots the K-contiguous slabs of
-    // this step go to (the slots of the pair that stage s ends)
+    // this step go to (the slots of the pair that stage s ends; for A in an even step when both
+    // operands are K-contiguous: of the pair before the one stage s begins)
     auto issue_part = [&](int s, bool odd, int j, int sa, int sb) {
-        if (j < 4) {
+        if (A_KC && B_KC) {
             if (odd) {
-                if (A_KC) { const int p = kc_pair_of(s, A_RING); if (pair_valid(p)) { issue_kc(opA, p, sa, 2 * j); issue_kc(opA, p, sa, 2 * j + 1); } }
-                if (B_KC) { const int p = kc_pair_of(s, B_RING); if (pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); } }
+                const int p = kc_pair_of(s, B_RING);
+                if (j < 4 && pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); }
+            } else {
+                const int p = s / 2 + A_RING - 1;
+                if (pair_valid(p)) issue_kc(opA, p, sa, j);
             }
+        } else if (j < 4) {
+            // the first half of a pair slab in the odd step that frees its slot, the second half
+            // in the even step after it: every step issues the same number of loads
+            if (A_KC) { const int p = odd ? kc_pair_of(s, A_RING) : s / 2 + A_RING - 1; if (pair_valid(p)) issue_kc(opA, p, sa, odd ? j : 4 + j); }
+            if (B_KC) { const int p = odd ? kc_pair_of(s, B_RING) : s / 2 + B_RING - 1; if (pair_valid(p)) issue_kc(opB, p, sb, odd ? j : 4 + j); }
         } else if (stage_valid(s + 4)) {
             if (!A_KC) issue_mc(opA, s + 4, j - 4);
             if (!B_KC) issue_mc(opB, s + 4, j - 4);
@@ -400,6 +413,9 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // (sa, sb) = ring slots of the pair of stage kt, (sa_n, sb_n) = of the pair of stage kt+1.
     auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[4],
                       v8i (&af_n)[4], v8i (&bf_n)[4]) {
+        // slot that A's loads of this step go to
+        const int sa_ld = (A_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
+        const int sb_ld = (B_KC && !A_KC && !odd) ? (sb == 0 ? B_RING - 1 : sb - 1) : sb;
         if (kt + 8 < KT) {
             if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
         } else {
@@ -409,7 +425,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            issue_part(kt, odd, j, sa, sb);
+            issue_part(kt, odd, j, sa_ld, sb_ld);
             read_both(kt + 1, j, sa_n, sb_n, af_n, bf_n);
             compute_part(j, af, bf);
             sched_part();
@@ -420,8 +436,9 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // KT is even and >= 2.
     v8i af0[4], bf0[4], af1[4], bf1[4];
     for (int s = -5; s < 0; ++s) {
-        // pair issued by odd step s < 0 is (s+1)/2 + ring - 1 < ring: slot = pair
-        const int sa = A_KC ? (s + 1) / 2 + A_RING - 1 : 0, sb = B_KC ? (s + 1) / 2 + B_RING - 1 : 0;
+        // a pair issued by a step s < 0 has an index below the ring size: slot = pair
+        const int sa = !A_KC ? 0 : (s & 1) ? (s + 1) / 2 + A_RING - 1 : s / 2 + A_RING - 1;
+        const int sb = !B_KC ? 0 : (s & 1) ? (s + 1) / 2 + B_RING - 1 : s / 2 + B_RING - 1;
 #pragma unroll
         for (int j = 0; j < 8; ++j) issue_part(s, s & 1, j, sa, sb);
     }

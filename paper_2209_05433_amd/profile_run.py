@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--iters", type=int, default=3)
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy")
     ap.add_argument("--mnk", type=int, nargs=3, default=None, help="GEMM shape overriding the workload's")
+    ap.add_argument("--trans-a", type=int, default=0, help="1: A stored K x M")
+    ap.add_argument("--trans-b", type=int, default=0, help="1: B stored N x K")
     args = ap.parse_args()
 
     n = args.copy_mib << 20
@@ -56,11 +58,12 @@ def main():
         M, N, K, fmtA, out = SHAPES[args.workload]
         if args.mnk:
             M, N, K = args.mnk
-        A, B = random_codes((M, K)), random_codes((K, N))
+        A = random_codes((K, M) if args.trans_a else (M, K))
+        B = random_codes((N, K) if args.trans_b else (K, N))
         C = torch.empty((M, N), dtype=out, device="cuda")
-        gemm = fp8.fp8_gemm if args.mode == "f16" else fp8.fp8_gemm_mfma8
+        flags = 0 if args.mode == "f16" else fp8.FP8_GEMM_MFMA8
         for _ in range(args.iters):
-            gemm(A, fmtA, 1.0, B, fp8.FP8_E4M3, 1.0, C)
+            fp8.fp8_gemm_ex(A, fmtA, args.trans_a, B, fp8.FP8_E4M3, args.trans_b, C, 1.0, 1.0, flags)
     torch.cuda.synchronize()
 
 
