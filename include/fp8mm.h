@@ -172,6 +172,38 @@ int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fm
                 float sA, float sB, const float* sA_dev, const float* sB_dev, int flags,
                 void* stream);
 
+/*
+ * fp8_gemm_fused -- the GEMM with the scale granularities and the output conversions that
+ * training recipes build on:
+ *     c_ij    = (sum_k a_ik b_kj) / (sA_i * sB_j)
+ *     amax    = max_ij |c_ij|                                   (if amax_out is given)
+ *     D_ij    = cast_out(c_ij)            for FP8_OUT_F32 / FP8_OUT_BF16
+ *     D_ij    = encode_fmt(fl32(c_ij * sD))  for FP8_OUT_E4M3 / FP8_OUT_E5M2
+ * Section 2: results of FP8 matrix products may be converted to FP8 before they are written
+ * to memory, with a scaling factor of their own; Section 5 uses per-channel scaling factors
+ * for weights; Section 4.3 / Section 2 leave the choice of the factor to software -- the
+ * output amax is what a recipe that derives the next step's factor from past maxima needs.
+ *   A, B, transA, transB, M, N, K, flags: as for fp8_gemm_ex
+ *   D        device, M x N row-major, element type given by out_kind (1 byte for FP8 kinds)
+ *   sA_dev   device, nsA values: nsA = 1 one factor for A, nsA = M one per row of op(A)
+ *   sB_dev   device, nsB values: nsB = 1 one factor for B, nsB = N one per column of op(B)
+ *   sD_dev   device, one value, or NULL for 1; FP8 output kinds only (else must be NULL)
+ *   amax_out device, one fp32, or NULL.  Written, not accumulated: NaN if any c_ij is NaN,
+ *            else the largest |c_ij| as computed (before the output scale and rounding)
+ * The FP8 conversion is the one of fp8_quantize (nearest even, saturating, NaN -> NaN,
+ * inf -> NaN for E4M3 / inf for E5M2).  c_ij meets the bound of fp8_gemm (fp8_gemm_mfma8 with
+ * FP8_GEMM_MFMA8); an FP8 output byte is the encoding of a value within that bound of
+ * c_ref * sD, so it can differ from the encoding of c_ref * sD itself only where that lies
+ * within the bound of a rounding boundary.  Scales must be finite and non-zero.
+ * Errors: as fp8_gemm; also FP8_ERR_INVALID_ARG for nsA not in {1, M}, nsB not in {1, N},
+ * NULL scale pointers, a bad out_kind, or sD_dev with a non-FP8 output.
+ */
+typedef enum { FP8_OUT_F32 = 0, FP8_OUT_BF16 = 1, FP8_OUT_E4M3 = 2, FP8_OUT_E5M2 = 3 } fp8_out_t;
+int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                   void* D, int out_kind, int64_t M, int64_t N, int64_t K,
+                   const float* sA_dev, int64_t nsA, const float* sB_dev, int64_t nsB,
+                   const float* sD_dev, float* amax_out, int flags, void* stream);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage. */
 const char* fp8_last_error(void);
 

@@ -167,6 +167,20 @@ def unscale(S, sA, sB):
     return alpha * np.asarray(S, dtype=np.float64), alpha
 
 
+def unscale_channels(S, sA, sB):
+    """C_ref[i, j] = S[i, j] / (sA[i] * sB[j]) in double precision: per-channel scaling factors
+    (Section 5 uses them for weights) taken out once per dot product.  sA: one value or one per
+    row of S; sB: one value or one per column.  Returns (C_ref, alpha) with alpha[i, j] =
+    1 / (sA[i] * sB[j]) broadcast to the shape of S."""
+    S = np.asarray(S, dtype=np.float64)
+    a = np.asarray(sA, dtype=np.float32).astype(np.float64).reshape(-1)
+    b = np.asarray(sB, dtype=np.float32).astype(np.float64).reshape(-1)
+    if a.size not in (1, S.shape[0]) or b.size not in (1, S.shape[1]):
+        raise ValueError("scale vectors do not match the rows / columns of S")
+    alpha = np.broadcast_to(1.0 / (a[:, None] * b[None, :]), S.shape)
+    return alpha * S, alpha
+
+
 def ulp(c_ref, out_dtype: int) -> np.ndarray:
     """Spacing of the output type at |c_ref|: 2^(e-23) for fp32, 2^(e-7) for
     bfloat16, e = floor(log2|c_ref|), clamped at the smallest normal exponent."""
@@ -180,6 +194,6 @@ def ulp(c_ref, out_dtype: int) -> np.ndarray:
 def gemm_bound(S, T, sA, sB, out_dtype: int):
     """Reference value and acceptance bound for GEMM outputs:
     |C - C_ref| <= 2^-20 * alpha * T + ulp_out(C_ref)/2 with C_ref = alpha * S."""
-    c_ref, alpha = unscale(S, sA, sB)
+    c_ref, alpha = unscale_channels(S, sA, sB) if (np.size(sA) > 1 or np.size(sB) > 1) else unscale(S, sA, sB)
     bound = 2.0 ** -20 * alpha * np.asarray(T, dtype=np.float64) + 0.5 * ulp(c_ref, out_dtype)
     return c_ref, bound

@@ -13,13 +13,14 @@ FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
 FP8_GEMM_MFMA8 = 1
+FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
 EXPORTS = (
     "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_last_error", "fp8_version",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_last_error", "fp8_version",
 )
 
 _lib = None
@@ -55,6 +56,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
+    L.fp8_gemm_fused.argtypes, L.fp8_gemm_fused.restype = [vp, i, i, vp, i, i, vp, i, i64, i64, i64, vp, i64, vp, i64, vp, vp, i, vp], i
     L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
     L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
     _lib = L
@@ -201,3 +203,29 @@ def fp8_gemm_ex(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, s
                              0.0 if dev else float(sA), 0.0 if dev else float(sB),
                              _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
                              int(flags), _stream(stream)))
+
+
+def fp8_gemm_fused(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, D, out_kind: int, sA, sB,
+                   sD=None, amax_out=None, flags: int = 0, stream=None) -> None:
+    """A is [M, K] (or [K, M] if transA), B is [K, N] (or [N, K] if transB), D is [M, N] of the
+    element type of out_kind (uint8 for the FP8 kinds).  sA: fp32 device tensor of 1 or M values,
+    sB: of 1 or N values; sD: None or one value; amax_out: None or one fp32 cell."""
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8 or A.dim() != 2 or B.dim() != 2:
+        raise ValueError("A and B must be 2-D uint8 tensors of FP8 bytes")
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    N, K2 = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != K2 or tuple(D.shape) != (M, N):
+        raise ValueError("shapes do not form D[M,N] = op(A)[M,K] op(B)[K,N]")
+    want = {FP8_OUT_F32: torch.float32, FP8_OUT_BF16: torch.bfloat16}.get(out_kind, torch.uint8)
+    if D.dtype != want:
+        raise ValueError("D must be %s for out_kind %d" % (want, out_kind))
+    for name, t in (("sA", sA), ("sB", sB), ("sD", sD), ("amax_out", amax_out)):
+        if t is not None and t.dtype != torch.float32:
+            raise ValueError("%s must be an fp32 device tensor" % name)
+    _check(lib().fp8_gemm_fused(_dev(A, "A") if A.numel() else None, fmtA, int(bool(transA)),
+                                _dev(B, "B") if B.numel() else None, fmtB, int(bool(transB)),
+                                _dev(D, "D") if D.numel() else None, int(out_kind), M, N, K,
+                                _dev(sA, "sA"), sA.numel(), _dev(sB, "sB"), sB.numel(),
+                                _dev(sD, "sD") if sD is not None else None,
+                                _dev(amax_out, "amax_out") if amax_out is not None else None,
+                                int(flags), _stream(stream)))

@@ -1,7 +1,8 @@
 """Builds libfp8mm.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree.
 
 Every translation unit is compiled to an object of its own, in parallel; the tiled GEMM source is
-compiled four times, once per pair of operand storage orders (-DFP8MM_LAYOUT=0..3)."""
+compiled eight times, once per pair of operand storage orders (-DFP8MM_LAYOUT=0..3) and
+accumulation mode (-DFP8MM_ACC=0|1)."""
 from __future__ import annotations
 
 import os
@@ -16,9 +17,10 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfp8mm.so")
 
 # (source, extra defines, object name)
-UNITS = [("api.hip", [], "api.o"), ("cast_kernels.hip", [], "cast_kernels.o"),
-         ("gemm_kernels.hip", [], "gemm_dispatch.o")] + \
-        [("gemm_kernels.hip", ["-DFP8MM_LAYOUT=%d" % k], "gemm_layout%d.o" % k) for k in range(4)]
+UNITS = [("gemm_tiled.hip", ["-DFP8MM_LAYOUT=%d" % k, "-DFP8MM_ACC=%d" % a], "gemm_tiled_l%d_a%d.o" % (k, a))
+         for k in range(4) for a in range(2)] + \
+        [("gemm_dispatch.hip", [], "gemm_dispatch.o"), ("cast_kernels.hip", [], "cast_kernels.o"),
+         ("api.hip", [], "api.o")]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32
 # instructions from the scalar float code of the kernels.

@@ -1,5 +1,5 @@
 // extern "C" entry points of libfp8mm: argument validation, then one launcher each.
-#include "common.hpp"
+#include "gemm_common.hpp"
 
 #include <stdarg.h>
 #include <stdio.h>
@@ -145,7 +145,13 @@ static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8
         const uintptr_t osz = out_dtype == FP8_F32 ? 4 : 2;
         if ((uintptr_t)C % osz) return fail(FP8_ERR_INVALID_ARG, "%s: C is not aligned to its element size", who);
     }
-    return launch_gemm(A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev, transA, transB, fp8_accumulate, (hipStream_t)stream);
+    GemmArgs g{};
+    g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.fmtA = fmtA; g.fmtB = fmtB;
+    g.transA = transA; g.transB = transB; g.acc = fp8_accumulate ? ACC_FP8 : ACC_F16;
+    g.ep.sA = sA; g.ep.sB = sB; g.ep.sA_dev = sA_dev; g.ep.sB_dev = sB_dev;
+    g.ep.out_kind = out_dtype;                      // fp8_dtype_t values are the first two output kinds
+    g.stream = (hipStream_t)stream;
+    return launch_gemm(g);
 }
 
 int fp8_gemm(const uint8_t* A, int fmtA, float sA, const uint8_t* B, int fmtB, float sB,
@@ -191,6 +197,41 @@ int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fm
     if (sA_dev && ((uintptr_t)sA_dev | (uintptr_t)sB_dev) % 4) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: scale pointer is misaligned");
     return gemm_checked("fp8_gemm_ex", A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev,
                         (flags & FP8_GEMM_MFMA8) != 0, stream, transA != 0, transB != 0);
+}
+
+int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                   void* D, int out_kind, int64_t M, int64_t N, int64_t K,
+                   const float* sA_dev, int64_t nsA, const float* sB_dev, int64_t nsB,
+                   const float* sD_dev, float* amax_out, int flags, void* stream)
+{
+    const char* who = "fp8_gemm_fused";
+    clear_error();
+    if (flags & ~FP8_GEMM_MFMA8) return fail(FP8_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags & ~FP8_GEMM_MFMA8);
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return fail(FP8_ERR_INVALID_ARG, "%s: transA/transB must be 0 or 1", who);
+    if (!valid_format(fmtA) || !valid_format(fmtB))
+        return fail(FP8_ERR_INVALID_ARG, "%s: operand formats (%d, %d) are not fp8_format_t", who, fmtA, fmtB);
+    if (out_kind < FP8_OUT_F32 || out_kind > FP8_OUT_E5M2) return fail(FP8_ERR_INVALID_ARG, "%s: out_kind %d is not an fp8_out_t", who, out_kind);
+    if (M < 0 || N < 0 || K < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (M=%lld N=%lld K=%lld)", who, (long long)M, (long long)N, (long long)K);
+    if (!sA_dev || !sB_dev) return fail(FP8_ERR_INVALID_ARG, "%s: sA_dev or sB_dev is NULL", who);
+    if (nsA != 1 && nsA != M) return fail(FP8_ERR_INVALID_ARG, "%s: nsA = %lld is neither 1 nor M", who, (long long)nsA);
+    if (nsB != 1 && nsB != N) return fail(FP8_ERR_INVALID_ARG, "%s: nsB = %lld is neither 1 nor N", who, (long long)nsB);
+    if (((uintptr_t)sA_dev | (uintptr_t)sB_dev | (uintptr_t)sD_dev | (uintptr_t)amax_out) % 4)
+        return fail(FP8_ERR_INVALID_ARG, "%s: a scale or amax pointer is misaligned", who);
+    if (sD_dev && out_kind < FP8_OUT_E4M3) return fail(FP8_ERR_INVALID_ARG, "%s: sD_dev applies to FP8 outputs only", who);
+    if (M > 0 && N > 0) {
+        if (!D) return fail(FP8_ERR_INVALID_ARG, "%s: D is NULL", who);
+        if (K > 0 && (!A || !B)) return fail(FP8_ERR_INVALID_ARG, "%s: A or B is NULL", who);
+        if ((uintptr_t)D % (uintptr_t)out_elem_size(out_kind)) return fail(FP8_ERR_INVALID_ARG, "%s: D is not aligned to its element size", who);
+    }
+    GemmArgs g{};
+    g.A = A; g.B = B; g.C = D; g.M = M; g.N = N; g.K = K; g.fmtA = fmtA; g.fmtB = fmtB;
+    g.transA = transA != 0; g.transB = transB != 0; g.acc = (flags & FP8_GEMM_MFMA8) ? ACC_FP8 : ACC_F16;
+    g.ep.sA = 1.0f; g.ep.sB = 1.0f; g.ep.sA_dev = sA_dev; g.ep.sB_dev = sB_dev; g.ep.sD_dev = sD_dev;
+    g.ep.amax_out = amax_out; g.ep.out_kind = out_kind;
+    g.ep.a_per_row = nsA == M && M != 1;
+    g.ep.b_per_col = nsB == N && N != 1;
+    g.stream = (hipStream_t)stream;
+    return launch_gemm(g);
 }
 
 }  // extern "C"

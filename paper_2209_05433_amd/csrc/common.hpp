@@ -36,9 +36,5 @@ int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
                     const float* scale_dev, bool saturate, uint8_t* q_out, hipStream_t stream);
 int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
                       int out_dtype, void* out, hipStream_t stream);
-int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
-                int64_t M, int64_t N, int64_t K, int out_dtype,
-                float sA, float sB, const float* sA_dev, const float* sB_dev,
-                bool transA, bool transB, bool fp8_accumulate, hipStream_t stream);
 
 }  // namespace fp8mm

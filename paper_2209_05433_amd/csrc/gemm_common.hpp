@@ -1,0 +1,82 @@
+// Declarations shared by the translation units of the GEMM (tiled kernel instances and the
+// dispatcher with the generic kernel).
+#pragma once
+
+#include "common.hpp"
+#include "fp8_decode.hpp"
+#include "fp8_encode.hpp"
+
+namespace fp8mm {
+
+// Output kinds.  The first two are fp8_dtype_t; the FP8 kinds write one byte per output.
+enum { OUT_F32 = 0, OUT_BF16 = 1, OUT_E4M3 = 2, OUT_E5M2 = 3 };
+inline int out_elem_size(int kind) { return kind == OUT_F32 ? 4 : kind == OUT_BF16 ? 2 : 1; }
+
+// How the products are formed and summed.
+//   ACC_F16: operands widened to fp16 (exact for both FP8 formats), fp16 matrix-core
+//            instructions.  These sum each instruction's products in a window of at least 24
+//            bits: fp32-grade accumulation, at half the FP8 peak rate.
+//   ACC_FP8: FP8 matrix-core instructions at the full FP8 rate.  The hardware adds each run of
+//            8 products (the 8 bytes of a lane's register pair) after aligning them to the
+//            largest and dropping what lies more than 13 bits below its leading bit, then
+//            accumulates the runs in fp32.
+enum { ACC_F16 = 0, ACC_FP8 = 1 };
+
+// What happens to an accumulator on its way out (Section 2: the scaling factors are taken out
+// once per dot product; results may be converted to FP8 before they are written):
+//   c_ij = acc_ij / (sA_i * sB_j);  amax = max |c_ij|;  D_ij = cast_out(c_ij * sD)
+// sA is one value or one per row of op(A), sB one value or one per column of op(B); sD applies
+// to FP8 outputs only.
+struct EpilogueArgs {
+    float sA, sB;                 // host values, used where the device pointer is null
+    const float* sA_dev;          // null, one value, or M values if a_per_row
+    const float* sB_dev;          // null, one value, or N values if b_per_col
+    const float* sD_dev;          // null (= 1) or one value
+    float* amax_out;              // null or one cell, zeroed by the launcher, raised with atomicMax
+    int out_kind;
+    int a_per_row, b_per_col;
+};
+
+struct GemmArgs {
+    const uint8_t* A; const uint8_t* B; void* C;
+    int64_t M, N, K;
+    int fmtA, fmtB;
+    bool transA, transB;          // A stored K x M / B stored N x K
+    int acc;                      // ACC_*
+    EpilogueArgs ep;
+    hipStream_t stream;
+};
+
+// Tiled kernel, one translation unit per (storage orders, accumulation mode):
+// layout = 2 * transA + transB.
+#define FP8MM_TILED_NAME_(l, a) launch_tiled_l##l##_a##a
+#define FP8MM_TILED_NAME(l, a) FP8MM_TILED_NAME_(l, a)
+#define FP8MM_DECLARE_TILED(l) \
+    int FP8MM_TILED_NAME(l, 0)(const GemmArgs& g); \
+    int FP8MM_TILED_NAME(l, 1)(const GemmArgs& g);
+FP8MM_DECLARE_TILED(0)
+FP8MM_DECLARE_TILED(1)
+FP8MM_DECLARE_TILED(2)
+FP8MM_DECLARE_TILED(3)
+#undef FP8MM_DECLARE_TILED
+
+constexpr int TILE_M = 256, TILE_N = 256, TILE_K = 64;
+
+int launch_gemm(const GemmArgs& g);
+
+// ---- small device helpers used by both kernels ----------------------------------------------
+__device__ __forceinline__ float scale_value(const float* dev, float host) { return dev ? *dev : host; }
+
+// Largest of `bits` (sign-stripped fp32 patterns; NaN patterns sort above infinity) over the wave,
+// then one atomic per wave.
+__device__ __forceinline__ void wave_amax_commit(unsigned bits, float* amax_out)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned o = (unsigned)__shfl_xor((int)bits, d, 64);
+        bits = o > bits ? o : bits;
+    }
+    if ((threadIdx.x & 63) == 0) atomicMax((unsigned*)amax_out, bits);
+}
+
+}  // namespace fp8mm

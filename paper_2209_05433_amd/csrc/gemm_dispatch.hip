@@ -1,0 +1,146 @@
+// GEMM dispatcher and the generic kernel for gfx950 (MI355X).
+//
+// Shapes and pointers that meet the tiled kernel's conditions (M, N multiples of 256, K a multiple
+// of 128, 16-byte aligned pointers) go to one of its instances; everything else is computed by the
+// generic kernel below: any shape, any alignment, every storage order, the same epilogue
+// (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
+#include "gemm_common.hpp"
+
+namespace fp8mm {
+namespace {
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ unsigned bf16_bits(float f)
+{
+    const unsigned u = as_u32(f);
+    const unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r;
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic kernel: 64 x 64 tile per 256-thread workgroup, 4 x 4 outputs per thread, operands
+// decoded to fp32 (exactly) on their way into LDS, fp32 FMAs (each product of two FP8 values
+// is exact in fp32, so this is fp32 accumulation of exact products as well).
+// ------------------------------------------------------------------------------------------
+constexpr int GT = 64, GK = 16;
+
+template <int FMT_A, int FMT_B>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int64_t M, int64_t N, int64_t K, EpilogueArgs ep, bool transA, bool transB)
+{
+    __shared__ float As[GK][GT + 1];
+    __shared__ float Bs[GK][GT + 1];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t m0 = (int64_t)blockIdx.y * GT, n0 = (int64_t)blockIdx.x * GT;
+    float acc[4][4] = {};
+    for (int64_t k0 = 0; k0 < K; k0 += GK) {
+        for (int e = tid; e < GT * GK; e += 256) {
+            const int r = e / GK, kk = e % GK;              // A: consecutive lanes along K
+            const int64_t gm = m0 + r, gk = k0 + kk;
+            As[kk][r] = (gm < M && gk < K) ? decode_fp8<FMT_A>(A[transA ? gk * M + gm : gm * K + gk]) : 0.0f;
+            const int kb = e / GT, c = e % GT;              // B: consecutive lanes along N
+            const int64_t gn = n0 + c, gkb = k0 + kb;
+            Bs[kb][c] = (gn < N && gkb < K) ? decode_fp8<FMT_B>(B[transB ? gn * K + gkb : gkb * N + gn]) : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < GK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    const float sD = (ep.out_kind >= OUT_E4M3) ? scale_value(ep.sD_dev, 1.0f) : 1.0f;
+    unsigned amax_bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+            if (gm < M && gn < N) {
+                const double a = ep.a_per_row ? (double)ep.sA_dev[gm] : (double)scale_value(ep.sA_dev, ep.sA);
+                const double b = ep.b_per_col ? (double)ep.sB_dev[gn] : (double)scale_value(ep.sB_dev, ep.sB);
+                const float c = acc[i][j] * (float)(1.0 / (a * b));
+                amax_bits = max(amax_bits, as_u32(c) & 0x7fffffffu);
+                const int64_t o = gm * N + gn;
+                switch (ep.out_kind) {
+                    case OUT_F32: ((float*)C)[o] = c; break;
+                    case OUT_BF16: ((unsigned short*)C)[o] = (unsigned short)bf16_bits(c); break;
+                    case OUT_E4M3: ((uint8_t*)C)[o] = (uint8_t)encode_bits<FP8_E4M3>(c * sD); break;
+                    default: ((uint8_t*)C)[o] = (uint8_t)encode_bits<FP8_E5M2>(c * sD); break;
+                }
+            }
+        }
+    if (ep.amax_out) wave_amax_commit(amax_bits, ep.amax_out);
+}
+
+template <int FA, int FB>
+int launch_generic(const GemmArgs& g)
+{
+    const dim3 grid((unsigned)((g.N + GT - 1) / GT), (unsigned)((g.M + GT - 1) / GT));
+    hipLaunchKernelGGL((gemm_generic_kernel<FA, FB>), grid, dim3(256), 0, g.stream, g.A, g.B, g.C, g.M, g.N, g.K,
+                       g.ep, g.transA, g.transB);
+    return check_launch("gemm (generic kernel)");
+}
+
+__global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nbytes; i += stride) p[i] = 0;
+}
+
+__global__ void zero_cell_kernel(unsigned* p) { *p = 0u; }
+
+// FP8MM_GEMM=generic (environment, read per call) forces the generic kernel.
+bool force_generic()
+{
+    const char* e = getenv("FP8MM_GEMM");
+    return e && e[0] == 'g';
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+int launch_gemm(const GemmArgs& g)
+{
+    const int64_t M = g.M, N = g.N, K = g.K;
+    if (g.ep.amax_out) {                                     // written, not accumulated
+        hipLaunchKernelGGL(zero_cell_kernel, dim3(1), dim3(1), 0, g.stream, (unsigned*)g.ep.amax_out);
+        if (M == 0 || N == 0) return check_launch("gemm (amax init)");
+    }
+    if (M == 0 || N == 0) return FP8_OK;
+    if (K == 0) {                                            // empty sums: every output is +0
+        const size_t nbytes = (size_t)M * (size_t)N * (size_t)out_elem_size(g.ep.out_kind);
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, g.stream, (unsigned char*)g.C, nbytes);
+        return check_launch("gemm (K = 0 fill)");
+    }
+    const bool aligned = aligned16(g.A) && aligned16(g.B) && aligned16(g.C) &&
+                         (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
+    const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
+    const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
+                        && (M / TILE_M) * (N / TILE_N) < (1ll << 31);
+    const bool fast = !force_generic() && aligned && fits32 && M % TILE_M == 0 && N % TILE_N == 0 &&
+                      K % (2 * TILE_K) == 0;
+    if (fast) {
+        typedef int (*tiled_fn)(const GemmArgs&);
+        static const tiled_fn table[4][2] = {
+            {FP8MM_TILED_NAME(0, 0), FP8MM_TILED_NAME(0, 1)}, {FP8MM_TILED_NAME(1, 0), FP8MM_TILED_NAME(1, 1)},
+            {FP8MM_TILED_NAME(2, 0), FP8MM_TILED_NAME(2, 1)}, {FP8MM_TILED_NAME(3, 0), FP8MM_TILED_NAME(3, 1)}};
+        return table[(g.transA ? 2 : 0) + (g.transB ? 1 : 0)][g.acc == ACC_FP8 ? 1 : 0](g);
+    }
+    if (g.fmtA == FP8_E4M3)
+        return g.fmtB == FP8_E4M3 ? launch_generic<FP8_E4M3, FP8_E4M3>(g) : launch_generic<FP8_E4M3, FP8_E5M2>(g);
+    return g.fmtB == FP8_E4M3 ? launch_generic<FP8_E5M2, FP8_E4M3>(g) : launch_generic<FP8_E5M2, FP8_E5M2>(g);
+}
+
+}  // namespace fp8mm

@@ -35,24 +35,10 @@
 //     widening of the bytes to fp16 in registers, by v_mfma_f32_32x32x16_f16 (ACC_F16, the
 //     default): see the note at the ACC_* constants for why both exist.
 //
-// Generic kernel (any shape, any alignment): decodes to fp32 in LDS and uses plain FMAs.
-#include "common.hpp"
-#include "fp8_decode.hpp"
+// This file is compiled once per (storage orders, accumulation mode): -DFP8MM_LAYOUT, -DFP8MM_ACC.
+#include "gemm_common.hpp"
 
 namespace fp8mm {
-
-struct GemmArgs {
-    const uint8_t* A; const uint8_t* B; void* C;
-    int64_t M, N, K;
-    float sA, sB; const float* sA_dev; const float* sB_dev;
-    bool transA, transB;
-    hipStream_t stream;
-};
-int launch_tiled_nn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
-int launch_tiled_nt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
-int launch_tiled_tn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
-int launch_tiled_tt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc);
-
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
@@ -60,29 +46,12 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-
-__device__ __forceinline__ float as_f32(unsigned u) { return __builtin_bit_cast(float, u); }
-__device__ __forceinline__ unsigned as_u32(float f) { return __builtin_bit_cast(unsigned, f); }
-
-// fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
-__device__ __forceinline__ unsigned bf16_bits(float f)
-{
-    const unsigned u = as_u32(f);
-    const unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    return (u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r;
-}
-
-__device__ __forceinline__ double alpha_of(float sA, float sB, const float* sA_dev, const float* sB_dev)
-{
-    const double a = sA_dev ? (double)*sA_dev : (double)sA;
-    const double b = sB_dev ? (double)*sB_dev : (double)sB;
-    return 1.0 / (a * b);
-}
 
 // ------------------------------------------------------------------------------------------
 // Fast kernel
@@ -137,16 +106,6 @@ __device__ __forceinline__ TileMap map_tile(int bid, int tiles_m, int tiles_n, i
     t.tn = q / rows;
     return t;
 }
-
-// How the products are formed and summed.
-//   ACC_F16: operands widened to fp16 (exact for both FP8 formats), fp16 matrix-core
-//            instructions.  These sum each instruction's products in a window of at least 24
-//            bits: fp32-grade accumulation, at half the FP8 peak rate.
-//   ACC_FP8: FP8 matrix-core instructions at the full FP8 rate.  The hardware adds each run of
-//            8 products (the 8 bytes of a lane's register pair) after aligning them to the
-//            largest and dropping what lies more than 13 bits below its leading bit, then
-//            accumulates the runs in fp32.
-enum { ACC_F16 = 0, ACC_FP8 = 1 };
 
 // 8 FP8 bytes (two dwords) -> 8 fp16 values, exact.
 template <int FMT>
@@ -243,14 +202,108 @@ __device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op
     }
 }
 
+// The epilogue of one wave: its 128 x 128 sub-tile of accumulators -> memory.
+//   c = acc * ra(row) [* cb(column)]: the reciprocal scales, applied once per output;
+//   amax of |c| (if asked for); conversion to the output kind; whole-line stores.
+// A lane holds 4 consecutive N of one C row per accumulator quad; written straight out that would
+// be small pieces scattered over 32 rows per instruction.  Instead the wave turns each 32 x 128
+// block around through its own piece of the (now idle) LDS and stores it with 16 bytes per lane
+// along N: whole 128-byte lines.  fp32 and bf16 outputs are converted before the turn; FP8 outputs
+// pass through LDS as fp32 (already multiplied by the output scale) and are rounded after it,
+// 16 consecutive columns per lane, by the same routine as in the cast kernel.
+template <int OUT, bool BVEC>
+__device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int N,
+                                         int wave_m0, int wave_n0, int w, int l)
+{
+    constexpr bool FP8OUT = OUT == OUT_E4M3 || OUT == OUT_E5M2;
+    constexpr int ESZ = OUT == OUT_F32 ? 4 : OUT == OUT_BF16 ? 2 : 1;     // bytes per output in memory
+    constexpr int LSZ = FP8OUT ? 4 : ESZ;                                 // bytes per output in LDS
+    constexpr int ROWB = 128 * LSZ + 16;                                  // padded LDS row of the wave's block
+    constexpr int ROWS_PER_ST = 1024 / (128 * ESZ);                       // C rows covered by one store instruction
+    const int h = l >> 5;
+
+    // reciprocal scales: per row in ra (with the per-tensor sB folded in), per column in cb
+    float ra[4];
+    {
+        const double b = BVEC ? 1.0 : (double)scale_value(ep.sB_dev, ep.sB);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const float a = ep.a_per_row ? ep.sA_dev[wave_m0 + mb * 32 + (l & 31)] : scale_value(ep.sA_dev, ep.sA);
+            ra[mb] = (float)(1.0 / ((double)a * b));
+        }
+    }
+    v4f cb[BVEC ? 4 : 1][BVEC ? 4 : 1];
+    if (BVEC) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4f s = *(const v4f*)(ep.sB_dev + wave_n0 + nb * 32 + 8 * q + 4 * h);
+                cb[BVEC ? nb : 0][BVEC ? q : 0] = (v4f){1.0f / s.x, 1.0f / s.y, 1.0f / s.z, 1.0f / s.w};
+            }
+    }
+    const float sD = FP8OUT ? scale_value(ep.sD_dev, 1.0f) : 1.0f;
+    unsigned amax_bits = 0;
+
+    uint8_t* blk = smem + w * (32 * ROWB);
+    uint8_t* c_wave = (uint8_t*)C + ((size_t)wave_m0 * N + wave_n0) * ESZ;
+    const int st_row = l / (64 / ROWS_PER_ST), st_col = (l % (64 / ROWS_PER_ST)) * 16;   // byte column in memory
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float c0 = acc[nb][mb][4 * q + 0] * ra[mb], c1 = acc[nb][mb][4 * q + 1] * ra[mb];
+                float c2 = acc[nb][mb][4 * q + 2] * ra[mb], c3 = acc[nb][mb][4 * q + 3] * ra[mb];
+                if (BVEC) {
+                    const v4f s = cb[BVEC ? nb : 0][BVEC ? q : 0];
+                    c0 *= s.x; c1 *= s.y; c2 *= s.z; c3 *= s.w;
+                }
+                if (ep.amax_out) {
+                    const unsigned m01 = max(as_u32(c0) & 0x7fffffffu, as_u32(c1) & 0x7fffffffu);
+                    const unsigned m23 = max(as_u32(c2) & 0x7fffffffu, as_u32(c3) & 0x7fffffffu);
+                    amax_bits = max(amax_bits, max(m01, m23));
+                }
+                uint8_t* dst = blk + (l & 31) * ROWB + (nb * 32 + 8 * q + 4 * h) * LSZ;
+                if (OUT == OUT_F32) {
+                    *LDS_PTR(v4f, dst) = (v4f){c0, c1, c2, c3};
+                } else if (OUT == OUT_BF16) {
+                    v2i o;
+                    o.x = (int)__builtin_bit_cast(unsigned, __builtin_convertvector((v2f){c0, c1}, v2bf));
+                    o.y = (int)__builtin_bit_cast(unsigned, __builtin_convertvector((v2f){c2, c3}, v2bf));
+                    *LDS_PTR(v2i, dst) = o;
+                } else {
+                    *LDS_PTR(v4f, dst) = (v4f){c0 * sD, c1 * sD, c2 * sD, c3 * sD};
+                }
+            }
+#pragma unroll
+        for (int i = 0; i < 32 / ROWS_PER_ST; ++i) {
+            const int row = i * ROWS_PER_ST + st_row;
+            uint8_t* out = c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col;
+            if (FP8OUT) {
+                float y[16];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const v4f v = *LDS_PTR(v4f, blk + row * ROWB + st_col * 4 + j * 16);
+                    y[4 * j] = v.x; y[4 * j + 1] = v.y; y[4 * j + 2] = v.z; y[4 * j + 3] = v.w;
+                }
+                *(u32x4*)out = encode16<OUT == OUT_E4M3 ? FP8_E4M3 : FP8_E5M2, kCastCvt>(y);
+            } else {
+                *(v4i*)out = *LDS_PTR(v4i, blk + row * ROWB + st_col);
+            }
+        }
+    }
+    if (ep.amax_out) wave_amax_commit(amax_bits, ep.amax_out);
+}
+
 // A_KC / B_KC: how the operand lies in memory (see Operand).  LDS: an MN-contiguous operand takes
 // 64 KB (ring of four stages); a K-contiguous one 96 KB (ring of three stage pairs), or 64 KB
 // (ring of two pairs) for B when both operands are K-contiguous.
-template <int FMT_A, int FMT_B, int OUT, int ACC, bool A_KC, bool B_KC>
+template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
-    int M, int N, int K, float sA, float sB, const float* __restrict__ sA_dev,
-    const float* __restrict__ sB_dev, int group_m)
+    int M, int N, int K, EpilogueArgs ep, int group_m)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     constexpr int A_RING = 3;                               // stage pairs in A's ring (if A_KC)
@@ -458,112 +511,42 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) compute_part(j, af1, bf1);
 
-    // ---- epilogue: unscale once per output, convert, write whole rows ----------------------------
-    // A lane holds 4 consecutive N of one C row per accumulator quad; written straight out that
-    // would be 8- or 16-byte pieces scattered over 32 rows per instruction.  Instead every wave
-    // turns each 32 x 128 block of its sub-tile around through its own piece of the (now idle)
-    // LDS and stores it with 16 bytes per lane along N: whole 128-byte lines of C.
-    constexpr int ESZ = OUT == FP8_F32 ? 4 : 2;
-    constexpr int ROWB = 128 * ESZ + 16;                    // padded LDS row of the wave's block
-    constexpr int ROWS_PER_ST = 1024 / (128 * ESZ);         // C rows covered by one store instruction
-    const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
+    // ---- epilogue (wave-uniform choice of the output kind and of the scale granularity) --------
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();                           // every wave is done with the operand slabs
-    uint8_t* blk = smem + w * (32 * ROWB);
-    uint8_t* c_wave = (uint8_t*)C + ((size_t)(m0 + wm * 128) * N + n0 + wn * 128) * ESZ;
-    const int st_row = l / (64 / ROWS_PER_ST), st_col = (l % (64 / ROWS_PER_ST)) * 16;
-#pragma unroll
-    for (int mb = 0; mb < 4; ++mb) {
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float c0 = acc[nb][mb][4 * q + 0] * alpha, c1 = acc[nb][mb][4 * q + 1] * alpha;
-                const float c2 = acc[nb][mb][4 * q + 2] * alpha, c3 = acc[nb][mb][4 * q + 3] * alpha;
-                uint8_t* dst = blk + (l & 31) * ROWB + (nb * 32 + 8 * q + 4 * h) * ESZ;
-                if (OUT == FP8_F32) {
-                    *LDS_PTR(v4f, dst) = (v4f){c0, c1, c2, c3};
-                } else {
-                    v2i o;
-                    o.x = (int)(bf16_bits(c0) | (bf16_bits(c1) << 16));
-                    o.y = (int)(bf16_bits(c2) | (bf16_bits(c3) << 16));
-                    *LDS_PTR(v2i, dst) = o;
-                }
-            }
-#pragma unroll
-        for (int i = 0; i < 32 / ROWS_PER_ST; ++i) {
-            const int row = i * ROWS_PER_ST + st_row;
-            const v4i v = *LDS_PTR(v4i, blk + row * ROWB + st_col);
-            *(v4i*)(c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col) = v;
+    const int wave_m0 = m0 + wm * 128, wave_n0 = n0 + wn * 128;
+    if (ep.b_per_col) {
+        switch (ep.out_kind) {
+            case OUT_F32: epilogue<OUT_F32, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+        }
+    } else {
+        switch (ep.out_kind) {
+            case OUT_F32: epilogue<OUT_F32, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
         }
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// Generic kernel: 64 x 64 tile per 256-thread workgroup, 4 x 4 outputs per thread, operands
-// decoded to fp32 (exactly) on their way into LDS, fp32 FMAs (each product of two FP8 values
-// is exact in fp32, so this is fp32 accumulation of exact products as well).
-// ------------------------------------------------------------------------------------------
-constexpr int GT = 64, GK = 16;
-
-template <int FMT_A, int FMT_B, int OUT>
-__global__ __launch_bounds__(256) void gemm_generic_kernel(
-    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
-    int64_t M, int64_t N, int64_t K, float sA, float sB, const float* __restrict__ sA_dev,
-    const float* __restrict__ sB_dev, bool transA, bool transB)
+// ---- launch ------------------------------------------------------------------------------
+// FP8MM_GROUP_M (environment, read per call) sets the number of tile rows per band of the tile
+// order (default GROUP_M).
+int group_m_setting()
 {
-    __shared__ float As[GK][GT + 1];
-    __shared__ float Bs[GK][GT + 1];
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int64_t m0 = (int64_t)blockIdx.y * GT, n0 = (int64_t)blockIdx.x * GT;
-    float acc[4][4] = {};
-    for (int64_t k0 = 0; k0 < K; k0 += GK) {
-        for (int e = tid; e < GT * GK; e += 256) {
-            const int r = e / GK, kk = e % GK;              // A: consecutive lanes along K
-            const int64_t gm = m0 + r, gk = k0 + kk;
-            As[kk][r] = (gm < M && gk < K) ? decode_fp8<FMT_A>(A[transA ? gk * M + gm : gm * K + gk]) : 0.0f;
-            const int kb = e / GT, c = e % GT;              // B: consecutive lanes along N
-            const int64_t gn = n0 + c, gkb = k0 + kb;
-            Bs[kb][c] = (gn < N && gkb < K) ? decode_fp8<FMT_B>(B[transB ? gn * K + gkb : gkb * N + gn]) : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < GK; ++kk) {
-            float a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-    const float alpha = (float)alpha_of(sA, sB, sA_dev, sB_dev);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
-            if (gm < M && gn < N) {
-                const float c = acc[i][j] * alpha;
-                if (OUT == FP8_F32) ((float*)C)[gm * N + gn] = c;
-                else ((unsigned short*)C)[gm * N + gn] = (unsigned short)bf16_bits(c);
-            }
-        }
+    const char* e = getenv("FP8MM_GROUP_M");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : GROUP_M;
 }
 
-// ---- dispatch ----------------------------------------------------------------------------
-int group_m_setting();
-
-template <int FA, int FB, int OUT, int ACC, bool A_KC, bool B_KC>
+template <int FA, int FB, int ACC, bool A_KC, bool B_KC>
 int launch_fast(const GemmArgs& g)
 {
     static bool attr_set = false;
-    auto kern = gemm_fast_kernel<FA, FB, OUT, ACC, A_KC, B_KC>;
+    auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
         if (e != hipSuccess)
@@ -572,112 +555,26 @@ int launch_fast(const GemmArgs& g)
     }
     const int tiles = (int)((g.M / BM) * (g.N / BN));
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
-                       (int)g.M, (int)g.N, (int)g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, group_m_setting());
+                       (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting());
     return check_launch("gemm (tiled kernel)");
 }
 
-// The tiled kernel is instantiated in four translation units, one per pair of storage orders
-// (FP8MM_LAYOUT = 2 * transA + transB), so that they compile in parallel; the unit without
-// FP8MM_LAYOUT holds the generic kernel and the dispatcher.
-template <bool A_KC, bool B_KC>
-int launch_tiled(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc)
-{
-#define FP8MM_CASE(FA, FB)                                                                                  \
-    if (fmtA == FA && fmtB == FB) {                                                                        \
-        if (out_dtype == FP8_F32)                                                                          \
-            return acc == ACC_FP8 ? launch_fast<FA, FB, FP8_F32, ACC_FP8, A_KC, B_KC>(g)                   \
-                                  : launch_fast<FA, FB, FP8_F32, ACC_F16, A_KC, B_KC>(g);                  \
-        return acc == ACC_FP8 ? launch_fast<FA, FB, FP8_BF16, ACC_FP8, A_KC, B_KC>(g)                      \
-                              : launch_fast<FA, FB, FP8_BF16, ACC_F16, A_KC, B_KC>(g);                     \
-    }
-    FP8MM_CASE(FP8_E4M3, FP8_E4M3)
-    FP8MM_CASE(FP8_E4M3, FP8_E5M2)
-    FP8MM_CASE(FP8_E5M2, FP8_E4M3)
-    FP8MM_CASE(FP8_E5M2, FP8_E5M2)
-#undef FP8MM_CASE
-    return fail(FP8_ERR_INVALID_ARG, "gemm: bad operand formats");
-}
-
-template <int FA, int FB, int OUT>
-int launch_generic_typed(const GemmArgs& g)
-{
-    const dim3 grid((unsigned)((g.N + GT - 1) / GT), (unsigned)((g.M + GT - 1) / GT));
-    hipLaunchKernelGGL((gemm_generic_kernel<FA, FB, OUT>), grid, dim3(256), 0, g.stream, g.A, g.B,
-                       g.C, g.M, g.N, g.K, g.sA, g.sB, g.sA_dev, g.sB_dev, g.transA, g.transB);
-    return check_launch("gemm (generic kernel)");
-}
-
-template <int FA, int FB>
-int launch_generic_out(const GemmArgs& g, int out_dtype)
-{
-    return out_dtype == FP8_F32 ? launch_generic_typed<FA, FB, FP8_F32>(g) : launch_generic_typed<FA, FB, FP8_BF16>(g);
-}
-
-__global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nbytes; i += stride) p[i] = 0;
-}
-
 }  // namespace
 
-// Environment knobs, read per call: FP8MM_GEMM=generic forces the generic kernel,
-// FP8MM_GROUP_M sets the number of tile rows per band of the tile order (default GROUP_M).
-namespace {
-int group_m_setting()
-{
-    const char* e = getenv("FP8MM_GROUP_M");
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : GROUP_M;
-}
-}  // namespace
-
-#if defined(FP8MM_LAYOUT)
-#if FP8MM_LAYOUT == 0
-int launch_tiled_nn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<true, false>(g, fmtA, fmtB, out_dtype, acc); }
-#elif FP8MM_LAYOUT == 1
-int launch_tiled_nt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<true, true>(g, fmtA, fmtB, out_dtype, acc); }
-#elif FP8MM_LAYOUT == 2
-int launch_tiled_tn(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<false, false>(g, fmtA, fmtB, out_dtype, acc); }
-#else
-int launch_tiled_tt(const GemmArgs& g, int fmtA, int fmtB, int out_dtype, int acc) { return launch_tiled<false, true>(g, fmtA, fmtB, out_dtype, acc); }
+#if !defined(FP8MM_LAYOUT) || !defined(FP8MM_ACC)
+#error "compile with -DFP8MM_LAYOUT=0..3 (2 * transA + transB) and -DFP8MM_ACC=0|1"
 #endif
-#else
-static bool force_generic()
-{
-    const char* e = getenv("FP8MM_GEMM");
-    return e && e[0] == 'g';
-}
 
-int launch_gemm(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
-                int64_t M, int64_t N, int64_t K, int out_dtype,
-                float sA, float sB, const float* sA_dev, const float* sB_dev, bool transA, bool transB,
-                bool fp8_accumulate, hipStream_t stream)
+int FP8MM_TILED_NAME(FP8MM_LAYOUT, FP8MM_ACC)(const GemmArgs& g)
 {
-    const int acc = fp8_accumulate ? ACC_FP8 : ACC_F16;
-    if (M == 0 || N == 0) return FP8_OK;
-    if (K == 0) {
-        const size_t nbytes = (size_t)M * (size_t)N * (out_dtype == FP8_F32 ? 4 : 2);
-        hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, stream, (unsigned char*)C, nbytes);
-        return check_launch("gemm (K = 0 fill)");
-    }
-    const bool aligned = (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15u) == 0;
-    const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
-    const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
-                        && (M / BM) * (N / BN) < (1ll << 31);
-    const bool fast = !force_generic() && aligned && fits32 && M % BM == 0 && N % BN == 0 && K % (2 * BK) == 0;
-    GemmArgs g{A, B, C, M, N, K, sA, sB, sA_dev, sB_dev, transA, transB, stream};
-    if (fast) {
-        if (!transA) return transB ? launch_tiled_nt(g, fmtA, fmtB, out_dtype, acc) : launch_tiled_nn(g, fmtA, fmtB, out_dtype, acc);
-        return transB ? launch_tiled_tt(g, fmtA, fmtB, out_dtype, acc) : launch_tiled_tn(g, fmtA, fmtB, out_dtype, acc);
-    }
-    if (fmtA == FP8_E4M3) {
-        return fmtB == FP8_E4M3 ? launch_generic_out<FP8_E4M3, FP8_E4M3>(g, out_dtype)
-                                : launch_generic_out<FP8_E4M3, FP8_E5M2>(g, out_dtype);
-    }
-    return fmtB == FP8_E4M3 ? launch_generic_out<FP8_E5M2, FP8_E4M3>(g, out_dtype)
-                            : launch_generic_out<FP8_E5M2, FP8_E5M2>(g, out_dtype);
+    constexpr bool A_KC = (FP8MM_LAYOUT & 2) == 0;   // A row-major M x K is K-contiguous
+    constexpr bool B_KC = (FP8MM_LAYOUT & 1) != 0;   // B stored N x K is K-contiguous
+    constexpr int ACC = FP8MM_ACC;
+    if (g.fmtA == FP8_E4M3)
+        return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC>(g)
+                                  : launch_fast<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC>(g);
+    return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E5M2, FP8_E4M3, ACC, A_KC, B_KC>(g)
+                              : launch_fast<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC>(g);
 }
-#endif
 
 }  // namespace fp8mm

@@ -152,3 +152,32 @@ def test_ulp_matches_library_spacing():
     lo = ((bits & 0x7FFF) << 16).view(np.float32).astype(np.float64)
     hi = (((bits & 0x7FFF) + 1) << 16).view(np.float32).astype(np.float64)
     assert np.array_equal(oracle.ulp(lo, BF16), hi - lo)
+
+
+def test_unscale_channels_is_row_and_column_scaling_of_the_operands():
+    """Per-channel factors taken out after the product equal the product of operands that were
+    divided by them first (a diagonal matrix commutes out of a matrix product); power-of-two
+    factors make both sides exact, so the identity is checked bit for bit against numpy's matmul."""
+    rng = np.random.default_rng(5)
+    M, N, K = 7, 9, 24
+    A = rng.integers(0, 0x60, (M, K)).astype(np.uint8) | (rng.integers(0, 2, (M, K)).astype(np.uint8) << 7)
+    B = rng.integers(0, 0x60, (K, N)).astype(np.uint8) | (rng.integers(0, 2, (K, N)).astype(np.uint8) << 7)
+    sA = np.ldexp(1.0, rng.integers(-6, 7, M)).astype(np.float32)
+    sB = np.ldexp(1.0, rng.integers(-6, 7, N)).astype(np.float32)
+    S, T = oracle.gemm_rows(A, E4M3, B, E4M3)
+    c, alpha = oracle.unscale_channels(S, sA, sB)
+    dec = oracle.decode_all(E4M3)
+    want = (dec[A] / sA[:, None].astype(np.float64)) @ (dec[B] / sB[None, :].astype(np.float64))
+    assert np.array_equal(c, want)
+    assert np.array_equal(alpha, 1.0 / np.outer(sA.astype(np.float64), sB.astype(np.float64)))
+    # one value per tensor is the special case of constant vectors, and equals unscale()
+    c1, _ = oracle.unscale_channels(S, np.float32(0.3), np.float32(7.0))
+    c2, _ = oracle.unscale_channels(S, np.full(M, 0.3, np.float32), np.full(N, 7.0, np.float32))
+    c3, _ = oracle.unscale(S, np.float32(0.3), np.float32(7.0))
+    assert np.array_equal(c1, c2) and np.allclose(c1, c3, rtol=1e-15)
+    # a transposed or swapped use of the vectors is noticed
+    with pytest.raises(ValueError):
+        oracle.unscale_channels(S, sB, sA)
+    # bound with vectors: 2^-20 * alpha_ij * T_ij + ulp/2
+    _, bound = oracle.gemm_bound(S, T, sA, sB, F32)
+    assert np.allclose(bound, 2.0 ** -20 * alpha * T + 0.5 * oracle.ulp(c, F32), rtol=1e-15)
