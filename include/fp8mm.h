@@ -111,6 +111,54 @@ int fp8_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float
                    int out_dtype, void* out, void* stream);
 
 /*
+ * fp8_quantize_amax -- the cast of fp8_quantize_dscale and the amax of fp8_amax over the same
+ * input, in one pass over x.  For recipes that pick the scaling factor before the tensor
+ * exists (Section 2 leaves the choice of the factor to software), e.g. from the maxima of
+ * earlier steps: the tensor is then read once instead of twice.
+ *   scale_dev  device, one fp32: the factor applied in this call
+ *   q_out      device, n bytes;  amax_out  device, one fp32 = max |x[i]| (NaN propagates);
+ *              written, not accumulated; n == 0 gives 0
+ * Same rounding, specials and errors as fp8_quantize / fp8_amax.
+ */
+int fp8_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const float* scale_dev,
+                      uint8_t* q_out, float* amax_out, void* stream);
+
+/*
+ * fp8_scale_from_amax_history -- scale = fmt_max / max(amax_history[0 .. len-1]) by the rule
+ * of fp8_scale_from_amax (a NaN entry propagates into the maximum; a zero, NaN or infinite
+ * maximum, or len == 0, gives 1).  amax_history: device, len fp32 values.
+ * fp8_scale_from_amax_n -- n factors from n maxima, element by element (per-row scaling).
+ */
+int fp8_scale_from_amax_history(const float* amax_history, size_t len, int fmt,
+                                float* scale_out, void* stream);
+int fp8_scale_from_amax_n(const float* amax, size_t n, int fmt, float* scale_out, void* stream);
+
+/*
+ * fp8_amax_rows / fp8_quantize_rows -- one maximum / one scaling factor per row of a
+ * rows x cols row-major matrix (Section 5: per-channel scaling factors for weights; a weight
+ * stored [out x in] with one factor per output channel is the N x K form of operand B, and its
+ * factors are the per-column factors of fp8_gemm_fused).
+ *   amax_out   device, rows fp32:  amax_out[r] = max_c |x[r][c]| (NaN propagates; cols == 0: 0)
+ *   scale_dev  device, rows fp32:  q[r][c] = FP8(fl32(x[r][c] * scale_dev[r]))
+ * Same rounding, specials and errors as fp8_amax / fp8_quantize.
+ */
+int fp8_amax_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, float* amax_out,
+                  void* stream);
+int fp8_quantize_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt,
+                      const float* scale_dev, uint8_t* q_out, void* stream);
+
+/*
+ * fp8_quantize_transpose -- the cast of fp8_quantize_dscale applied to a rows x cols row-major
+ * matrix, written in both storage orders by one pass over x (Section 4.1: activations, weights
+ * and activation gradients all feed GEMMs, and the backward pass consumes them transposed):
+ *   q_out   device, rows x cols bytes, q[r][c] = FP8(fl32(x[r][c] * scale)); may be NULL
+ *   qt_out  device, cols x rows bytes, qt[c][r] = q[r][c]
+ * Any shape; rows and cols multiples of 16 with 16-byte aligned pointers take the tiled kernel.
+ */
+int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt,
+                           const float* scale_dev, uint8_t* q_out, uint8_t* qt_out, void* stream);
+
+/*
  * fp8_gemm -- C = (1 / (sA * sB)) * (A x B) with FP8 operands, fp32 accumulation
  * and the unscale applied once per output (Section 2: matrix multiplies on FP8
  * inputs produce single-precision results; unscaling is done once per dot product;

@@ -114,6 +114,33 @@ def quantize(x: np.ndarray, fmt: int, scale, saturating: bool = True) -> np.ndar
     return q
 
 
+def amax_rows(x: np.ndarray) -> np.ndarray:
+    """amax of every row of a 2-D tensor: the per-tensor definition applied to each row on its own
+    (per-channel granularity, Section 5)."""
+    return np.array([amax(x[r]) for r in range(x.shape[0])], dtype=np.float32)
+
+
+def scale_from_amax_n(amax_values, fmt: int) -> np.ndarray:
+    return np.array([scale_from_amax(a, fmt) for a in np.asarray(amax_values, dtype=np.float32).reshape(-1)],
+                    dtype=np.float32)
+
+
+def quantize_rows(x: np.ndarray, fmt: int, scales, saturating: bool = True) -> np.ndarray:
+    """Row r of a 2-D tensor quantized with its own scaling factor scales[r]."""
+    scales = np.asarray(scales, dtype=np.float32).reshape(-1)
+    if scales.size != x.shape[0]:
+        raise ValueError("one scale per row expected")
+    return np.stack([quantize(x[r], fmt, scales[r], saturating) for r in range(x.shape[0])]) if x.shape[0] else \
+        np.empty(x.shape, dtype=np.uint8)
+
+
+def scale_from_amax_history(history, fmt: int) -> np.float32:
+    """Scaling factor from the largest of a list of earlier maxima (the maxima are magnitudes, so
+    their amax is their maximum, NaN propagating); an empty history gives the factor 1."""
+    h = np.ascontiguousarray(history, dtype=np.float32).reshape(-1)
+    return scale_from_amax(amax(h) if h.size else np.float32(0.0), fmt)
+
+
 def dequantize(q: np.ndarray, fmt: int, scale) -> np.ndarray:
     q = np.ascontiguousarray(q, dtype=np.uint8)
     out = np.empty(q.shape, dtype=np.float64)

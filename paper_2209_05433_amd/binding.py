@@ -19,7 +19,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so
 
 EXPORTS = (
     "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
-    "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
+    "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax",
+    "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
+    "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
     "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_last_error", "fp8_version",
 )
 
@@ -57,6 +59,12 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
     L.fp8_gemm_fused.argtypes, L.fp8_gemm_fused.restype = [vp, i, i, vp, i, i, vp, i, i64, i64, i64, vp, i64, vp, i64, vp, vp, i, vp], i
+    L.fp8_quantize_amax.argtypes, L.fp8_quantize_amax.restype = [vp, sz, i, i, vp, vp, vp, vp], i
+    L.fp8_scale_from_amax_history.argtypes, L.fp8_scale_from_amax_history.restype = [vp, sz, i, vp, vp], i
+    L.fp8_scale_from_amax_n.argtypes, L.fp8_scale_from_amax_n.restype = [vp, sz, i, vp, vp], i
+    L.fp8_amax_rows.argtypes, L.fp8_amax_rows.restype = [vp, i64, i64, i, vp, vp], i
+    L.fp8_quantize_rows.argtypes, L.fp8_quantize_rows.restype = [vp, i64, i64, i, i, vp, vp, vp], i
+    L.fp8_quantize_transpose.argtypes, L.fp8_quantize_transpose.restype = [vp, i64, i64, i, i, vp, vp, vp, vp], i
     L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
     L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
     _lib = L
@@ -229,3 +237,64 @@ def fp8_gemm_fused(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, D, ou
                                 _dev(sD, "sD") if sD is not None else None,
                                 _dev(amax_out, "amax_out") if amax_out is not None else None,
                                 int(flags), _stream(stream)))
+
+
+def _f32_cells(t, what, count=None):
+    if t.dtype != torch.float32 or (count is not None and t.numel() != count):
+        raise ValueError("%s must be an fp32 device tensor%s" % (what, "" if count is None else " of %d values" % count))
+    return _dev(t, what)
+
+
+def fp8_quantize_amax(x, fmt: int, scale, q_out, amax_out, stream=None) -> None:
+    """Cast x with the one-element device tensor `scale` and write max |x| into amax_out."""
+    if q_out.dtype != torch.uint8 or q_out.numel() != x.numel():
+        raise ValueError("q_out must be uint8 with as many elements as x")
+    _check(lib().fp8_quantize_amax(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
+                                   _f32_cells(scale, "scale", 1), _dev(q_out, "q_out") if x.numel() else None,
+                                   _f32_cells(amax_out, "amax_out", 1), _stream(stream)))
+
+
+def fp8_scale_from_amax_history(amax_history, fmt: int, scale_out, stream=None) -> None:
+    _check(lib().fp8_scale_from_amax_history(_f32_cells(amax_history, "amax_history") if amax_history.numel() else None,
+                                             amax_history.numel(), fmt, _f32_cells(scale_out, "scale_out", 1),
+                                             _stream(stream)))
+
+
+def fp8_scale_from_amax_n(amax, fmt: int, scale_out, stream=None) -> None:
+    n = amax.numel()
+    _check(lib().fp8_scale_from_amax_n(_f32_cells(amax, "amax") if n else None, n, fmt,
+                                       _f32_cells(scale_out, "scale_out", n) if n else None, _stream(stream)))
+
+
+def _matrix(x, what):
+    if x.dim() != 2:
+        raise ValueError("%s must be a 2-D tensor" % what)
+    return x.shape[0], x.shape[1]
+
+
+def fp8_amax_rows(x, amax_out, stream=None) -> None:
+    rows, cols = _matrix(x, "x")
+    _check(lib().fp8_amax_rows(_dev(x, "x") if x.numel() else None, rows, cols, dtype_code(x),
+                               _f32_cells(amax_out, "amax_out", rows) if rows else None, _stream(stream)))
+
+
+def fp8_quantize_rows(x, fmt: int, scale, q_out, stream=None) -> None:
+    rows, cols = _matrix(x, "x")
+    if q_out.dtype != torch.uint8 or tuple(q_out.shape) != (rows, cols):
+        raise ValueError("q_out must be a uint8 tensor of the shape of x")
+    _check(lib().fp8_quantize_rows(_dev(x, "x") if x.numel() else None, rows, cols, dtype_code(x), fmt,
+                                   _f32_cells(scale, "scale", rows) if x.numel() else None,
+                                   _dev(q_out, "q_out") if x.numel() else None, _stream(stream)))
+
+
+def fp8_quantize_transpose(x, fmt: int, scale, q_out, qt_out, stream=None) -> None:
+    """q_out (rows x cols, may be None) and qt_out (cols x rows) receive the FP8 bytes of x."""
+    rows, cols = _matrix(x, "x")
+    if qt_out.dtype != torch.uint8 or tuple(qt_out.shape) != (cols, rows):
+        raise ValueError("qt_out must be a uint8 tensor of shape (cols, rows)")
+    if q_out is not None and (q_out.dtype != torch.uint8 or tuple(q_out.shape) != (rows, cols)):
+        raise ValueError("q_out must be None or a uint8 tensor of the shape of x")
+    _check(lib().fp8_quantize_transpose(_dev(x, "x") if x.numel() else None, rows, cols, dtype_code(x), fmt,
+                                        _f32_cells(scale, "scale", 1) if x.numel() else None,
+                                        _dev(q_out, "q_out") if (q_out is not None and x.numel()) else None,
+                                        _dev(qt_out, "qt_out") if x.numel() else None, _stream(stream)))

@@ -20,6 +20,7 @@ LIB = os.path.join(PKG, "libfp8mm.so")
 UNITS = [("gemm_tiled.hip", ["-DFP8MM_LAYOUT=%d" % k, "-DFP8MM_ACC=%d" % a], "gemm_tiled_l%d_a%d.o" % (k, a))
          for k in range(4) for a in range(2)] + \
         [("gemm_dispatch.hip", [], "gemm_dispatch.o"), ("cast_kernels.hip", [], "cast_kernels.o"),
+         ("cast_variants.hip", [], "cast_variants.o"),
          ("api.hip", [], "api.o")]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32

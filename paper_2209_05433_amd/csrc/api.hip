@@ -129,6 +129,93 @@ int fp8_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float
     return launch_dequantize(q, n, fmt, scale, scale_dev, out_dtype, out, (hipStream_t)stream);
 }
 
+// ---- scaling-recipe variants of the amax / cast steps ------------------------------------------
+static int check_tensor(const char* who, const void* x, int in_dtype, bool nonempty)
+{
+    if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
+    if (nonempty && !x) return fail(FP8_ERR_INVALID_ARG, "%s: x is NULL", who);
+    if ((uintptr_t)x % (in_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "%s: x is not aligned to its element size", who);
+    return FP8_OK;
+}
+
+static int check_f32_ptr(const char* who, const char* name, const void* p, bool required)
+{
+    if (required && !p) return fail(FP8_ERR_INVALID_ARG, "%s: %s is NULL", who, name);
+    if ((uintptr_t)p % 4) return fail(FP8_ERR_INVALID_ARG, "%s: %s is misaligned", who, name);
+    return FP8_OK;
+}
+
+int fp8_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const float* scale_dev,
+                      uint8_t* q_out, float* amax_out, void* stream)
+{
+    const char* who = "fp8_quantize_amax";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (int e = check_tensor(who, x, in_dtype, n > 0)) return e;
+    if (n > 0 && !q_out) return fail(FP8_ERR_INVALID_ARG, "%s: q_out is NULL", who);
+    if (int e = check_f32_ptr(who, "scale_dev", scale_dev, n > 0)) return e;
+    if (int e = check_f32_ptr(who, "amax_out", amax_out, true)) return e;
+    return launch_quantize_amax(x, n, in_dtype, fmt, scale_dev, q_out, amax_out, (hipStream_t)stream);
+}
+
+int fp8_scale_from_amax_history(const float* amax_history, size_t len, int fmt, float* scale_out, void* stream)
+{
+    const char* who = "fp8_scale_from_amax_history";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (int e = check_f32_ptr(who, "amax_history", amax_history, len > 0)) return e;
+    if (int e = check_f32_ptr(who, "scale_out", scale_out, true)) return e;
+    return launch_scale_from_history(amax_history, len, fmt, scale_out, (hipStream_t)stream);
+}
+
+int fp8_scale_from_amax_n(const float* amax, size_t n, int fmt, float* scale_out, void* stream)
+{
+    const char* who = "fp8_scale_from_amax_n";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (int e = check_f32_ptr(who, "amax", amax, n > 0)) return e;
+    if (int e = check_f32_ptr(who, "scale_out", scale_out, n > 0)) return e;
+    return launch_scale_n(amax, n, fmt, scale_out, (hipStream_t)stream);
+}
+
+int fp8_amax_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, float* amax_out, void* stream)
+{
+    const char* who = "fp8_amax_rows";
+    clear_error();
+    if (rows < 0 || cols < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (rows=%lld cols=%lld)", who, (long long)rows, (long long)cols);
+    if (int e = check_tensor(who, x, in_dtype, rows > 0 && cols > 0)) return e;
+    if (int e = check_f32_ptr(who, "amax_out", amax_out, rows > 0)) return e;
+    return launch_amax_rows(x, rows, cols, in_dtype, amax_out, (hipStream_t)stream);
+}
+
+int fp8_quantize_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt,
+                      const float* scale_dev, uint8_t* q_out, void* stream)
+{
+    const char* who = "fp8_quantize_rows";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (rows < 0 || cols < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (rows=%lld cols=%lld)", who, (long long)rows, (long long)cols);
+    const bool work = rows > 0 && cols > 0;
+    if (int e = check_tensor(who, x, in_dtype, work)) return e;
+    if (work && !q_out) return fail(FP8_ERR_INVALID_ARG, "%s: q_out is NULL", who);
+    if (int e = check_f32_ptr(who, "scale_dev", scale_dev, work)) return e;
+    return launch_quantize_rows(x, rows, cols, in_dtype, fmt, scale_dev, q_out, (hipStream_t)stream);
+}
+
+int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt,
+                           const float* scale_dev, uint8_t* q_out, uint8_t* qt_out, void* stream)
+{
+    const char* who = "fp8_quantize_transpose";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (rows < 0 || cols < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (rows=%lld cols=%lld)", who, (long long)rows, (long long)cols);
+    const bool work = rows > 0 && cols > 0;
+    if (int e = check_tensor(who, x, in_dtype, work)) return e;
+    if (work && !qt_out) return fail(FP8_ERR_INVALID_ARG, "%s: qt_out is NULL", who);
+    if (int e = check_f32_ptr(who, "scale_dev", scale_dev, work)) return e;
+    return launch_quantize_transpose(x, rows, cols, in_dtype, fmt, scale_dev, q_out, qt_out, (hipStream_t)stream);
+}
+
 static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, void* C,
                         int64_t M, int64_t N, int64_t K, int out_dtype, float sA, float sB,
                         const float* sA_dev, const float* sB_dev, bool fp8_accumulate, void* stream,

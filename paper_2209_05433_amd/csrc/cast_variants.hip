@@ -1,0 +1,353 @@
+// Variants of the amax / cast kernels for gfx950 (MI355X) that scaling recipes beyond the plain
+// two-pass per-tensor one build on (arXiv 2209.05433: Section 2 leaves the choice of the scaling
+// factor to software; Section 5 uses per-channel factors for weights; Section 4.1: activations,
+// weights and activation gradients are all GEMM inputs, so a tensor is consumed in both storage
+// orders during training):
+//   - cast + amax in one pass, for a factor chosen beforehand from past maxima (3 bytes per bf16
+//     element instead of 5);
+//   - the factor from a history of maxima;
+//   - per-row amax, per-row factors, per-row cast;
+//   - cast that also writes the transposed bytes.
+// The rounding itself is the routine of the plain cast (fp8_encode.hpp).
+#include "cast_common.hpp"
+
+namespace fp8mm {
+namespace {
+
+// Packed running maximum (see vec_mag_max) -> sign-stripped fp32 bits.
+template <int DT>
+__device__ __forceinline__ unsigned run_to_bits(unsigned run)
+{
+    if (DT == FP8_F32) return run;
+    const u16x2 p = __builtin_bit_cast(u16x2, run);
+    return (unsigned)(p.x > p.y ? p.x : p.y) << 16;
+}
+
+// Raises *cell to at least `bits`.  Most workgroups find the cell already large enough and skip
+// the atomic, so thousands of workgroups do not queue on one address.
+__device__ __forceinline__ void raise_cell(unsigned* cell, unsigned bits)
+{
+    if (bits > __hip_atomic_load(cell, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(cell, bits);
+}
+
+// ------------------------------------------------------------------------------------------
+// cast + amax in one pass
+// ------------------------------------------------------------------------------------------
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_amax_kernel(const void* __restrict__ x, size_t n,
+                                                                const float* __restrict__ scale_dev,
+                                                                uint8_t* __restrict__ q,
+                                                                unsigned* __restrict__ amax_bits, bool vec)
+{
+    constexpr int V = DT == FP8_BF16 ? 2 : 4;       // 16-byte vectors per item of 16 elements
+    constexpr int U = DT == FP8_BF16 ? 4 : 2;       // items per lane per step
+    const float s = *scale_dev;
+    unsigned run = 0;
+    size_t done = 0;
+    if (vec) {
+        const u32x4* xv = (const u32x4*)x;
+        u32x4* qv = (u32x4*)q;
+        const size_t nitem = n / 16;
+        const size_t per = (nitem + gridDim.x - 1) / gridDim.x;
+        const size_t lo = (size_t)blockIdx.x * per;
+        const size_t hi = lo + per < nitem ? lo + per : nitem;
+        size_t i = lo + threadIdx.x;
+        for (; i + (U - 1) * kThreads < hi; i += U * kThreads) {
+            u32x4 v[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int j = 0; j < V; ++j) v[u][j] = __builtin_nontemporal_load(&xv[V * (i + u * kThreads) + j]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) run = vec_mag_max<DT>(v[u][j], run);
+                float y[16];
+                scale_item<DT>(v[u], s, y);
+                qv[i + u * kThreads] = encode16<FMT, kCastCvt>(y);
+            }
+        }
+        for (; i < hi; i += kThreads) {
+            u32x4 v[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                v[j] = __builtin_nontemporal_load(&xv[V * i + j]);
+                run = vec_mag_max<DT>(v[j], run);
+            }
+            float y[16];
+            scale_item<DT>(v, s, y);
+            qv[i] = encode16<FMT, kCastCvt>(y);
+        }
+        done = nitem * 16;
+    }
+    unsigned r = run_to_bits<DT>(run);
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t t = done + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
+        const unsigned m = scalar_mag<DT>(x, t);
+        r = r > m ? r : m;
+        q[t] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, t) * s);
+    }
+    r = block_max_u32(r);
+    if (threadIdx.x == 0) raise_cell(amax_bits, r);
+}
+
+// ------------------------------------------------------------------------------------------
+// factors from maxima
+// ------------------------------------------------------------------------------------------
+// One factor from the largest entry of a history of maxima (NaN entries propagate, and a NaN
+// maximum gives the factor 1 like every degenerate maximum).
+__global__ __launch_bounds__(kThreads) void scale_from_history_kernel(const float* __restrict__ hist, size_t len, int fmt,
+                                                                     float* __restrict__ out)
+{
+    unsigned r = 0;
+    for (size_t i = threadIdx.x; i < len; i += kThreads) {
+        const unsigned m = as_u32(hist[i]) & 0x7fffffffu;
+        r = r > m ? r : m;
+    }
+    r = block_max_u32(r);
+    if (threadIdx.x == 0) *out = scale_rule(as_f32(r), fmt);
+}
+
+__global__ __launch_bounds__(kThreads) void scale_n_kernel(const float* __restrict__ amax, size_t n, int fmt,
+                                                          float* __restrict__ out)
+{
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) out[i] = scale_rule(amax[i], fmt);
+}
+
+// ------------------------------------------------------------------------------------------
+// per-row amax and cast: one workgroup per row at a time
+// ------------------------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(kThreads) void amax_rows_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
+                                                            float* __restrict__ amax_out, bool vec)
+{
+    constexpr int PV = Elem<DT>::per_vec;
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+        const char* xr = (const char*)x + (size_t)row * (size_t)cols * Elem<DT>::size;
+        unsigned run = 0;
+        int64_t done = 0;
+        if (vec) {
+            const u32x4* xv = (const u32x4*)xr;
+            const int64_t nvec = cols / PV;
+            for (int64_t i = threadIdx.x; i < nvec; i += kThreads) run = vec_mag_max<DT>(__builtin_nontemporal_load(&xv[i]), run);
+            done = nvec * PV;
+        }
+        unsigned r = run_to_bits<DT>(run);
+        for (int64_t t = done + threadIdx.x; t < cols; t += kThreads) {
+            const unsigned m = scalar_mag<DT>(xr, (size_t)t);
+            r = r > m ? r : m;
+        }
+        r = block_max_u32(r);
+        if (threadIdx.x == 0) amax_out[row] = as_f32(r);
+        __syncthreads();                    // the reduction's staging cells are reused by the next row
+    }
+}
+
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
+                                                                const float* __restrict__ scale_dev,
+                                                                uint8_t* __restrict__ q, bool vec)
+{
+    constexpr int V = DT == FP8_BF16 ? 2 : 4;
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+        const char* xr = (const char*)x + (size_t)row * (size_t)cols * Elem<DT>::size;
+        uint8_t* qr = q + (size_t)row * (size_t)cols;
+        const float s = scale_dev[row];
+        int64_t done = 0;
+        if (vec) {
+            const u32x4* xv = (const u32x4*)xr;
+            u32x4* qv = (u32x4*)qr;
+            const int64_t nitem = cols / 16;
+            for (int64_t i = threadIdx.x; i < nitem; i += kThreads) {
+                u32x4 v[V];
+#pragma unroll
+                for (int j = 0; j < V; ++j) v[j] = __builtin_nontemporal_load(&xv[V * i + j]);
+                float y[16];
+                scale_item<DT>(v, s, y);
+                qv[i] = encode16<FMT, kCastCvt>(y);
+            }
+            done = nitem * 16;
+        }
+        for (int64_t t = done + threadIdx.x; t < cols; t += kThreads)
+            qr[t] = (uint8_t)encode_bits<FMT>(load_scalar<DT>(xr, (size_t)t) * s);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// cast + transpose.  One workgroup per 128 x 128 tile of x.  A lane converts 8 (bf16) or 4 (fp32)
+// consecutive elements of a row: their bytes go straight to q (a wave instruction covers whole
+// 128-byte rows of the tile) and into an LDS copy of the tile.  The transposed tile leaves through
+// the transposing LDS read of gfx950 (ds_read_b64_tr_b8: 16 lanes read an 8 x 16 byte block and
+// each receives one column of it), two per lane = 16 consecutive bytes of a row of q^T.
+// ------------------------------------------------------------------------------------------
+constexpr int TT = 128;                       // tile edge
+constexpr int TT_PITCH = TT + 16;             // LDS row pitch in bytes (16-byte pad spreads the rows over the banks)
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+// Four scaled values -> 4 FP8 bytes, converter path with the special values routed to the integer path.
+template <int FMT>
+__device__ __forceinline__ unsigned encode4(float y0, float y1, float y2, float y3)
+{
+    if (is_special(y0) | is_special(y1) | is_special(y2) | is_special(y3)) return encode4_bits<FMT>(y0, y1, y2, y3);
+    const unsigned w = cvt_pair<FMT, false>(y0, y1, 0u);
+    return cvt_pair<FMT, true>(y2, y3, w);
+}
+
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
+                                                                     const float* __restrict__ scale_dev,
+                                                                     uint8_t* __restrict__ q, uint8_t* __restrict__ qt)
+{
+    constexpr int EPL = DT == FP8_BF16 ? 8 : 4;          // elements per lane per load (16 bytes)
+    constexpr int LPR = TT / EPL;                        // lanes per tile row
+    constexpr int RPP = kThreads / LPR;                  // tile rows per pass of the workgroup
+    constexpr int PASSES = TT / RPP;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[TT * TT_PITCH];
+    const float s = *scale_dev;
+    const int64_t r0 = (int64_t)blockIdx.y * TT, c0 = (int64_t)blockIdx.x * TT;
+    const int tid = threadIdx.x;
+    const int lr = tid / LPR, lc = (tid % LPR) * EPL;    // lane's row within a pass, first column
+
+    // load everything first (PASSES 16-byte loads in flight per lane), then convert
+    u32x4 v[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int64_t r = r0 + p * RPP + lr, c = c0 + lc;
+        v[p] = (u32x4){0u, 0u, 0u, 0u};
+        if (r < rows && c < cols)
+            v[p] = __builtin_nontemporal_load((const u32x4*)((const char*)x + ((size_t)r * (size_t)cols + (size_t)c) * Elem<DT>::size));
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int tr = p * RPP + lr;
+        const int64_t r = r0 + tr, c = c0 + lc;
+        unsigned b0, b1 = 0;
+        if (DT == FP8_BF16) {
+            b0 = encode4<FMT>(as_f32(v[p].x << 16) * s, as_f32(v[p].x & 0xffff0000u) * s,
+                              as_f32(v[p].y << 16) * s, as_f32(v[p].y & 0xffff0000u) * s);
+            b1 = encode4<FMT>(as_f32(v[p].z << 16) * s, as_f32(v[p].z & 0xffff0000u) * s,
+                              as_f32(v[p].w << 16) * s, as_f32(v[p].w & 0xffff0000u) * s);
+            *LDS_PTR(v2i, tile + tr * TT_PITCH + lc) = (v2i){(int)b0, (int)b1};
+            if (q && r < rows && c < cols) *(v2i*)(q + (size_t)r * (size_t)cols + (size_t)c) = (v2i){(int)b0, (int)b1};
+        } else {
+            b0 = encode4<FMT>(as_f32(v[p].x) * s, as_f32(v[p].y) * s, as_f32(v[p].z) * s, as_f32(v[p].w) * s);
+            *LDS_PTR(unsigned, tile + tr * TT_PITCH + lc) = b0;
+            if (q && r < rows && c < cols) *(unsigned*)(q + (size_t)r * (size_t)cols + (size_t)c) = b0;
+        }
+    }
+    __syncthreads();
+    // q^T: tile column tc (a row of q^T), 16 consecutive tile rows per lane.  A wave instruction
+    // covers 16 columns x 64 rows; wave w owns the columns 32 w .. 32 w + 31.
+    const int w = tid >> 6, l = tid & 63;
+    const int g = l >> 4, t16 = l & 15;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int tc0 = w * 32 + cb * 16;                 // first tile column of the 16-lane group's block
+            const int tr0 = half * 64 + g * 16;               // first tile row of the lane's 16 bytes
+            // lanes 2 k and 2 k + 1 of a group address the two 8-byte halves of tile row tr0 + k (+ 8)
+            const uint8_t* src = tile + (tr0 + (t16 >> 1)) * TT_PITCH + tc0 + (t16 & 1) * 8;
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, src));
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, src + 8 * TT_PITCH));
+            const int64_t orow = c0 + tc0 + t16, ocol = r0 + tr0;  // position in q^T (cols x rows)
+            if (orow < cols && ocol < rows)
+                *(u32x4*)(qt + (size_t)orow * (size_t)rows + (size_t)ocol) = (u32x4){(unsigned)lo.x, (unsigned)lo.y, (unsigned)hi.x, (unsigned)hi.y};
+        }
+}
+
+// Any shape and alignment: one element per lane, both outputs written directly.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_transpose_scalar_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
+                                                                            const float* __restrict__ scale_dev,
+                                                                            uint8_t* __restrict__ q, uint8_t* __restrict__ qt)
+{
+    const float s = *scale_dev;
+    const size_t n = (size_t)rows * (size_t)cols, stride = (size_t)gridDim.x * kThreads;
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const uint8_t b = (uint8_t)encode_bits<FMT>(load_scalar<DT>(x, i) * s);
+        if (q) q[i] = b;
+        qt[(i % (size_t)cols) * (size_t)rows + i / (size_t)cols] = b;
+    }
+}
+
+#define FP8MM_DISPATCH_DT_FMT(KERNEL, grid, ...)                                                           \
+    do {                                                                                                   \
+        if (in_dtype == FP8_F32) {                                                                         \
+            if (fmt == FP8_E4M3) hipLaunchKernelGGL((KERNEL<FP8_F32, FP8_E4M3>), grid, dim3(kThreads), 0, stream, __VA_ARGS__); \
+            else hipLaunchKernelGGL((KERNEL<FP8_F32, FP8_E5M2>), grid, dim3(kThreads), 0, stream, __VA_ARGS__);                 \
+        } else {                                                                                           \
+            if (fmt == FP8_E4M3) hipLaunchKernelGGL((KERNEL<FP8_BF16, FP8_E4M3>), grid, dim3(kThreads), 0, stream, __VA_ARGS__); \
+            else hipLaunchKernelGGL((KERNEL<FP8_BF16, FP8_E5M2>), grid, dim3(kThreads), 0, stream, __VA_ARGS__);                \
+        }                                                                                                  \
+    } while (0)
+
+}  // namespace
+
+int launch_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const float* scale_dev, uint8_t* q_out,
+                         float* amax_out, hipStream_t stream)
+{
+    unsigned* bits = (unsigned*)amax_out;
+    hipLaunchKernelGGL(store_u32_kernel, dim3(1), dim3(1), 0, stream, bits, 0u);
+    if (n == 0) return check_launch("quantize_amax init");
+    const bool vec = aligned16(x) && aligned16(q_out);
+    const dim3 grid(vec ? grid_for((n / 16 + 3) / 4, kCastBlocks) : grid_for(n, 2048));
+    FP8MM_DISPATCH_DT_FMT(quantize_amax_kernel, grid, x, n, scale_dev, q_out, bits, vec);
+    return check_launch("quantize_amax");
+}
+
+int launch_scale_from_history(const float* hist, size_t len, int fmt, float* scale_out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(scale_from_history_kernel, dim3(1), dim3(kThreads), 0, stream, hist, len, fmt, scale_out);
+    return check_launch("scale_from_amax_history");
+}
+
+int launch_scale_n(const float* amax, size_t n, int fmt, float* scale_out, hipStream_t stream)
+{
+    if (n == 0) return FP8_OK;
+    hipLaunchKernelGGL(scale_n_kernel, dim3(grid_for(n, 1024)), dim3(kThreads), 0, stream, amax, n, fmt, scale_out);
+    return check_launch("scale_from_amax_n");
+}
+
+int launch_amax_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, float* amax_out, hipStream_t stream)
+{
+    if (rows == 0) return FP8_OK;
+    const size_t esz = in_dtype == FP8_F32 ? 4 : 2;
+    const bool vec = aligned16(x) && ((size_t)cols * esz) % 16 == 0;
+    const dim3 grid((unsigned)(rows < 65536 ? rows : 65536));
+    if (in_dtype == FP8_F32) hipLaunchKernelGGL(amax_rows_kernel<FP8_F32>, grid, dim3(kThreads), 0, stream, x, rows, cols, amax_out, vec);
+    else hipLaunchKernelGGL(amax_rows_kernel<FP8_BF16>, grid, dim3(kThreads), 0, stream, x, rows, cols, amax_out, vec);
+    return check_launch("amax_rows");
+}
+
+int launch_quantize_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt, const float* scale_dev,
+                         uint8_t* q_out, hipStream_t stream)
+{
+    if (rows == 0 || cols == 0) return FP8_OK;
+    const bool vec = aligned16(x) && aligned16(q_out) && cols % 16 == 0;
+    const dim3 grid((unsigned)(rows < 65536 ? rows : 65536));
+    FP8MM_DISPATCH_DT_FMT(quantize_rows_kernel, grid, x, rows, cols, scale_dev, q_out, vec);
+    return check_launch("quantize_rows");
+}
+
+int launch_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt, const float* scale_dev,
+                              uint8_t* q_out, uint8_t* qt_out, hipStream_t stream)
+{
+    if (rows == 0 || cols == 0) return FP8_OK;
+    const int64_t tiles_r = (rows + TT - 1) / TT, tiles_c = (cols + TT - 1) / TT;
+    const bool vec = aligned16(x) && aligned16(qt_out) && (!q_out || aligned16(q_out)) && rows % 16 == 0 && cols % 16 == 0 &&
+                     tiles_r < 65536 && tiles_c < (1ll << 31);
+    if (vec) {
+        const dim3 grid((unsigned)tiles_c, (unsigned)tiles_r);
+        FP8MM_DISPATCH_DT_FMT(quantize_transpose_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);
+    } else {
+        const dim3 grid(grid_for((size_t)rows * (size_t)cols, 4096));
+        FP8MM_DISPATCH_DT_FMT(quantize_transpose_scalar_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);
+    }
+    return check_launch("quantize_transpose");
+}
+
+}  // namespace fp8mm

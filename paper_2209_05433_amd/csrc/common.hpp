@@ -34,6 +34,15 @@ float scale_from_amax_host(float amax, int fmt);
 int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream);
 int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
                     const float* scale_dev, bool saturate, uint8_t* q_out, hipStream_t stream);
+int launch_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const float* scale_dev, uint8_t* q_out,
+                         float* amax_out, hipStream_t stream);
+int launch_scale_from_history(const float* hist, size_t len, int fmt, float* scale_out, hipStream_t stream);
+int launch_scale_n(const float* amax, size_t n, int fmt, float* scale_out, hipStream_t stream);
+int launch_amax_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, float* amax_out, hipStream_t stream);
+int launch_quantize_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt, const float* scale_dev,
+                         uint8_t* q_out, hipStream_t stream);
+int launch_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dtype, int fmt, const float* scale_dev,
+                              uint8_t* q_out, uint8_t* qt_out, hipStream_t stream);
 int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const float* scale_dev,
                       int out_dtype, void* out, hipStream_t stream);
 

@@ -76,7 +76,10 @@ __device__ __forceinline__ void wave_amax_commit(unsigned bits, float* amax_out)
         const unsigned o = (unsigned)__shfl_xor((int)bits, d, 64);
         bits = o > bits ? o : bits;
     }
-    if ((threadIdx.x & 63) == 0) atomicMax((unsigned*)amax_out, bits);
+    // most waves find the cell already large enough and skip the atomic
+    if ((threadIdx.x & 63) == 0 &&
+        bits > __hip_atomic_load((unsigned*)amax_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax((unsigned*)amax_out, bits);
 }
 
 }  // namespace fp8mm

@@ -67,6 +67,21 @@ def test_invalid_arguments_are_rejected_without_a_launch():
     assert L.fp8_gemm(p, 0, 1.0, p, 0, 1.0, p, 0, 4, 4, 0, None) == fp8.FP8_OK   # empty output
     assert L.fp8_gemm_dscale(p, 0, None, p, 0, p, p, 4, 4, 4, 0, None) == INV
     assert "scale pointer" in fp8.fp8_last_error()
+    assert L.fp8_gemm_ex(p, 0, 2, p, 0, 0, p, 4, 4, 4, 0, 1.0, 1.0, None, None, 0, None) == INV     # transA not 0/1
+    assert L.fp8_gemm_ex(p, 0, 0, p, 0, 0, p, 4, 4, 4, 0, 1.0, 1.0, p, None, 0, None) == INV        # one scale on device only
+    assert L.fp8_gemm_ex(p, 0, 0, p, 0, 0, p, 4, 4, 4, 0, 1.0, 1.0, None, None, 8, None) == INV     # unknown flag
+    fused = lambda **kw: L.fp8_gemm_fused(*[kw.get(k, d) for k, d in (
+        ("A", p), ("fmtA", 0), ("transA", 0), ("B", p), ("fmtB", 0), ("transB", 0), ("D", p), ("out_kind", 2),
+        ("M", 4), ("N", 4), ("K", 4), ("sA", p), ("nsA", 1), ("sB", p), ("nsB", 4), ("sD", None), ("amax", None),
+        ("flags", 0), ("stream", None))])
+    assert fused(out_kind=4) == INV
+    assert fused(nsA=3) == INV and "nsA" in fp8.fp8_last_error()
+    assert fused(nsB=2) == INV
+    assert fused(sA=None) == INV
+    assert fused(out_kind=1, sD=p) == INV                                        # output scale with a bf16 output
+    assert fused(amax=p + 2) == INV
+    assert fused(D=None) == INV
+    assert fused(M=0) == fp8.FP8_OK
 
 
 @pytest.mark.parametrize("fmt", [fp8.FP8_E4M3, fp8.FP8_E5M2])

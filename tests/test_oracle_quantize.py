@@ -132,3 +132,41 @@ def test_power_of_two_rescaling_of_the_input_changes_nothing(fmt):
         sc = oracle.scale_from_amax(oracle.amax(xc), fmt)
         assert sc == s / np.float32(c)
         assert np.array_equal(oracle.quantize(xc, fmt, sc), q)
+
+
+def test_per_row_helpers_against_numpy_and_the_flat_definitions():
+    """amax_rows is numpy's max |x| along axis 1; quantize_rows with equal factors is the flat cast;
+    rows are independent (changing one row's factor changes only that row); per-row factors with a
+    power-of-two ratio equal a flat cast of the pre-scaled rows (exact multiplication)."""
+    x = synth.normal(37 * 53, 9).reshape(37, 53)
+    x[5, 7] = -40.0
+    assert np.array_equal(oracle.amax_rows(x), np.max(np.abs(x), axis=1))
+    h = synth.to_bf16_bits(x.reshape(-1)).reshape(37, 53)
+    assert np.array_equal(oracle.amax_rows(h), np.max(np.abs(synth.bf16_bits_to_f32(h)), axis=1))
+    for fmt in FMTS:
+        s = oracle.scale_from_amax_n(oracle.amax_rows(x), fmt)
+        assert all(s[r] == oracle.scale_from_amax(np.max(np.abs(x[r])), fmt) for r in range(37))
+        flat = oracle.quantize(x, fmt, 3.0)
+        assert np.array_equal(oracle.quantize_rows(x, fmt, np.full(37, 3.0, np.float32)), flat)
+        sc = np.full(37, 3.0, np.float32)
+        sc[11] = 0.25
+        q = oracle.quantize_rows(x, fmt, sc)
+        assert np.array_equal(np.delete(q, 11, axis=0), np.delete(flat, 11, axis=0))
+        assert np.array_equal(q[11], oracle.quantize(x[11], fmt, 0.25))
+        p2 = np.ldexp(1.0, np.arange(37) % 9 - 4).astype(np.float32)
+        assert np.array_equal(oracle.quantize_rows(x, fmt, p2), oracle.quantize(x * p2[:, None], fmt, 1.0))
+        # the row maximum lands on the largest code of the format, nothing exceeds it
+        qs = oracle.quantize_rows(x, fmt, s)
+        assert np.all((qs & 0x7F).max(axis=1) == MAXCODE[fmt])
+    with pytest.raises(ValueError):
+        oracle.quantize_rows(x, E4M3, np.ones(36, np.float32))
+
+
+def test_scale_from_amax_history():
+    for fmt in FMTS:
+        h = np.array([0.5, 3.0, 2.0, 0.0], dtype=np.float32)
+        assert oracle.scale_from_amax_history(h, fmt) == np.float32(FMAX[fmt] / 3.0)
+        assert oracle.scale_from_amax_history(h[:1], fmt) == oracle.scale_from_amax(0.5, fmt)
+        assert oracle.scale_from_amax_history(np.zeros(0, np.float32), fmt) == 1.0
+        assert oracle.scale_from_amax_history(np.array([1.0, np.nan], np.float32), fmt) == 1.0
+        assert oracle.scale_from_amax_history(np.array([1.0, np.inf], np.float32), fmt) == 1.0
