@@ -124,6 +124,21 @@ int fp8_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const floa
                       uint8_t* q_out, float* amax_out, void* stream);
 
 /*
+ * fp8_quantize_sr -- the scaled cast with stochastic rounding in place of round-to-nearest
+ * (Section 2 names stochastic rounding among the rounding modes left to the implementation and
+ * does not define it; this definition is the library's).  y = fl32(x[i] * scale) of magnitude
+ * below the format's largest value lies between adjacent FP8 values lo <= |y| < hi; with
+ * T = floor(2^16 (|y| - lo) / (hi - lo)) the result is hi if T + r_i >= 2^16, else lo: hi with
+ * probability T / 2^16, values on the grid never move.  Larger magnitudes saturate; sign, NaN and
+ * inf as in fp8_quantize.  r_i = 16-bit field i % 8 (low half of word 0 first) of the output of
+ * Philox4x32-10 (Salmon et al., SC 2011) for the counter (i / 8, 0, 0) -- i / 8 as a 64-bit
+ * number in counter words 0 and 1 -- and the key (seed low word, seed high word): results depend
+ * on (seed, i) alone, not on the launch shape.  scale_dev, if not NULL, replaces scale.
+ */
+int fp8_quantize_sr(const void* x, size_t n, int in_dtype, int fmt, float scale,
+                    const float* scale_dev, uint64_t seed, uint8_t* q_out, void* stream);
+
+/*
  * fp8_scale_from_amax_history -- scale = fmt_max / max(amax_history[0 .. len-1]) by the rule
  * of fp8_scale_from_amax (a NaN entry propagates into the maximum; a zero, NaN or infinite
  * maximum, or len == 0, gives 1).  amax_history: device, len fp32 values.

@@ -60,6 +60,14 @@ def _load():
     lib.fp8o_gemm_rows.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_int,
                                    c.c_int64, c.c_int64, c.c_int64,
                                    c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
+    lib.fp8o_encode_sr.restype = c.c_uint8
+    lib.fp8o_encode_sr.argtypes = [c.c_int, c.c_float, c.c_uint32]
+    lib.fp8o_philox4x32.restype = None
+    lib.fp8o_philox4x32.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.fp8o_sr_bits.restype = c.c_uint32
+    lib.fp8o_sr_bits.argtypes = [c.c_uint64, c.c_uint64]
+    lib.fp8o_quantize_sr.restype = None
+    lib.fp8o_quantize_sr.argtypes = [c.c_void_p, c.c_size_t, c.c_int, c.c_int, c.c_float, c.c_uint64, c.c_void_p]
     lib.fp8o_num_threads.restype = c.c_int
     lib.fp8o_num_threads.argtypes = []
     _lib = lib
@@ -111,6 +119,30 @@ def quantize(x: np.ndarray, fmt: int, scale, saturating: bool = True) -> np.ndar
     q = np.empty(x.shape, dtype=np.uint8)
     _load().fp8o_quantize(_ptr(x), x.size, dt, fmt, float(np.float32(scale)),
                           int(saturating), _ptr(q))
+    return q
+
+
+def encode_sr(fmt: int, y, r16: int) -> int:
+    """Stochastic rounding of one fp32 value with the 16 random bits r16."""
+    return int(_load().fp8o_encode_sr(fmt, float(np.float32(y)), int(r16) & 0xFFFF))
+
+
+def philox4x32(ctr, key) -> np.ndarray:
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    _load().fp8o_philox4x32(_ptr(c), _ptr(k), _ptr(out))
+    return out
+
+
+def sr_bits(seed: int, i: int) -> int:
+    return int(_load().fp8o_sr_bits(int(seed), int(i)))
+
+
+def quantize_sr(x: np.ndarray, fmt: int, scale, seed: int) -> np.ndarray:
+    x, dt = _as_input(x)
+    q = np.empty(x.shape, dtype=np.uint8)
+    _load().fp8o_quantize_sr(_ptr(x), x.size, dt, fmt, float(np.float32(scale)), int(seed), _ptr(q))
     return q
 
 

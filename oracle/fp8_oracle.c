@@ -139,6 +139,76 @@ uint8_t fp8o_encode(int fmt, float y, int saturating)
     }
 }
 
+/*
+ * Stochastic rounding (Section 2 lists it as a rounding mode an implementation may choose; the
+ * paper gives no definition, this one is the reading of this repository).  A finite value of
+ * magnitude m below the largest finite value lies between adjacent FP8 values lo <= m < hi.  With
+ * t = (m - lo) / (hi - lo) and T = floor(t * 2^16), the result is hi if T + r >= 2^16 and lo
+ * otherwise, where r is a 16-bit random integer: hi is taken with probability T / 2^16, values
+ * on the grid never move.  Magnitudes at or above the largest finite value saturate; the sign
+ * and the special values are handled as in fp8o_encode.
+ */
+uint8_t fp8o_encode_sr(int fmt, float y, uint32_t r16)
+{
+    const int nfin = fmt_nfinite(fmt);
+    const uint8_t sign = signbit(y) ? 0x80 : 0x00;
+    const uint8_t max_code = (uint8_t)(nfin - 1);
+    double m, vlo, vhi, t;
+    int lo, hi;
+
+    if (isnan(y) || isinf(y)) return fp8o_encode(fmt, y, 1);
+    m = fabs((double)y);
+    if (m >= fp8o_decode(fmt, max_code)) return sign | max_code;
+    lo = 0;
+    hi = max_code;
+    while (hi - lo > 1) {
+        int mid = (lo + hi) / 2;
+        if (fp8o_decode(fmt, (uint8_t)mid) <= m) lo = mid; else hi = mid;
+    }
+    vlo = fp8o_decode(fmt, (uint8_t)lo);
+    vhi = fp8o_decode(fmt, (uint8_t)hi);
+    t = (m - vlo) / (vhi - vlo);            /* exact: the spacing is a power of two */
+    return sign | (uint8_t)((floor(t * 65536.0) + (double)(r16 & 0xFFFFu) >= 65536.0) ? hi : lo);
+}
+
+/*
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+ * SC 2011): ten rounds of two 32x32 -> 64 bit multiplications whose halves are crossed over and
+ * mixed with a key that is bumped by Weyl constants every round.
+ */
+void fp8o_philox4x32(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    int round;
+    for (round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 16 random bits of element i for a 64-bit seed: block i / 8 of the generator keyed by the
+ * seed, counter = (block, 0, 0) as a 128-bit number; 16-bit field i % 8 of its 128 output bits,
+ * low half of word 0 first. */
+uint32_t fp8o_sr_bits(uint64_t seed, uint64_t i)
+{
+    const uint64_t block = i / 8;
+    const uint32_t ctr[4] = {(uint32_t)block, (uint32_t)(block >> 32), 0u, 0u};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t w[4];
+    const unsigned f = (unsigned)(i % 8);
+    fp8o_philox4x32(ctr, key, w);
+    return (w[f / 2] >> (16 * (f % 2))) & 0xFFFFu;
+}
+
 /* bfloat16 is the upper half of a single-precision number: widening is exact. */
 static float bf16_to_f32(uint16_t h)
 {
@@ -226,6 +296,18 @@ void fp8o_dequantize(const uint8_t *q, size_t n, int fmt, float scale, double *o
     size_t i;
 #pragma omp parallel for
     for (i = 0; i < n; ++i) out[i] = fp8o_decode(fmt, q[i]) / (double)scale;
+}
+
+/* Scaled cast with stochastic rounding: q[i] = encode_sr(fl32(x[i] * scale), bits(seed, i)). */
+void fp8o_quantize_sr(const void *x, size_t n, int in_dtype, int fmt, float scale, uint64_t seed,
+                      uint8_t *q)
+{
+    size_t i;
+#pragma omp parallel for
+    for (i = 0; i < n; ++i) {
+        double p = (double)load_elem(x, i, in_dtype) * (double)scale;
+        q[i] = fp8o_encode_sr(fmt, (float)p, fp8o_sr_bits(seed, (uint64_t)i));
+    }
 }
 
 /*

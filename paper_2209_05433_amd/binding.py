@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so
 
 EXPORTS = (
     "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
-    "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax",
+    "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
     "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_last_error", "fp8_version",
@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
     L.fp8_gemm_fused.argtypes, L.fp8_gemm_fused.restype = [vp, i, i, vp, i, i, vp, i, i64, i64, i64, vp, i64, vp, i64, vp, vp, i, vp], i
+    L.fp8_quantize_sr.argtypes, L.fp8_quantize_sr.restype = [vp, sz, i, i, f, vp, c.c_uint64, vp, vp], i
     L.fp8_quantize_amax.argtypes, L.fp8_quantize_amax.restype = [vp, sz, i, i, vp, vp, vp, vp], i
     L.fp8_scale_from_amax_history.argtypes, L.fp8_scale_from_amax_history.restype = [vp, sz, i, vp, vp], i
     L.fp8_scale_from_amax_n.argtypes, L.fp8_scale_from_amax_n.restype = [vp, sz, i, vp, vp], i
@@ -298,3 +299,14 @@ def fp8_quantize_transpose(x, fmt: int, scale, q_out, qt_out, stream=None) -> No
                                         _f32_cells(scale, "scale", 1) if x.numel() else None,
                                         _dev(q_out, "q_out") if (q_out is not None and x.numel()) else None,
                                         _dev(qt_out, "qt_out") if x.numel() else None, _stream(stream)))
+
+
+def fp8_quantize_sr(x, fmt: int, scale, seed: int, q_out, stream=None) -> None:
+    """Stochastic-rounding cast; scale is a float or a one-element fp32 device tensor."""
+    if q_out.dtype != torch.uint8 or q_out.numel() != x.numel():
+        raise ValueError("q_out must be uint8 with as many elements as x")
+    dev = isinstance(scale, torch.Tensor)
+    _check(lib().fp8_quantize_sr(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
+                                 1.0 if dev else float(scale), _f32_cells(scale, "scale", 1) if dev else None,
+                                 int(seed) & 0xFFFFFFFFFFFFFFFF, _dev(q_out, "q_out") if x.numel() else None,
+                                 _stream(stream)))

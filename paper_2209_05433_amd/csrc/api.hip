@@ -158,6 +158,18 @@ int fp8_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const floa
     return launch_quantize_amax(x, n, in_dtype, fmt, scale_dev, q_out, amax_out, (hipStream_t)stream);
 }
 
+int fp8_quantize_sr(const void* x, size_t n, int in_dtype, int fmt, float scale, const float* scale_dev,
+                    uint64_t seed, uint8_t* q_out, void* stream)
+{
+    const char* who = "fp8_quantize_sr";
+    clear_error();
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (int e = check_tensor(who, x, in_dtype, n > 0)) return e;
+    if (n > 0 && !q_out) return fail(FP8_ERR_INVALID_ARG, "%s: q_out is NULL", who);
+    if (int e = check_f32_ptr(who, "scale_dev", scale_dev, false)) return e;
+    return launch_quantize_sr(x, n, in_dtype, fmt, scale, scale_dev, seed, q_out, (hipStream_t)stream);
+}
+
 int fp8_scale_from_amax_history(const float* amax_history, size_t len, int fmt, float* scale_out, void* stream)
 {
     const char* who = "fp8_scale_from_amax_history";

@@ -7,8 +7,12 @@
 //     element instead of 5);
 //   - the factor from a history of maxima;
 //   - per-row amax, per-row factors, per-row cast;
-//   - cast that also writes the transposed bytes.
-// The rounding itself is the routine of the plain cast (fp8_encode.hpp).
+//   - cast that also writes the transposed bytes;
+//   - cast with stochastic rounding (Section 2 names it as a rounding mode left to the
+//     implementation), random bits from a counter-based generator so that results depend on
+//     (seed, element index) alone.
+// Except for the stochastic mode the rounding itself is the routine of the plain cast
+// (fp8_encode.hpp).
 #include "cast_common.hpp"
 
 namespace fp8mm {
@@ -274,6 +278,111 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_scalar_kernel(con
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// cast with stochastic rounding.  For lo <= |y| < hi adjacent FP8 values, t = (|y| - lo)/(hi - lo),
+// T = floor(t * 2^16): the result is hi iff T + r >= 2^16, r = 16 random bits of the element.
+// In the bits of y: for results in the normal range T is the 16 bits below the kept mantissa and
+// the carry of T + r is added to the truncated code (a mantissa carry bumps the exponent as it
+// should); below the smallest normal value the grid is uniform, |y| / step is taken as a fixed-point
+// number with 16 fraction bits and r is added to it.
+// ------------------------------------------------------------------------------------------
+template <int FMT>
+__device__ __forceinline__ unsigned encode_sr_bits(float y, unsigned r16)
+{
+    constexpr int MB = FMT == FP8_E4M3 ? 3 : 2;
+    constexpr int BIAS = FMT == FP8_E4M3 ? 7 : 15;
+    constexpr unsigned DROP = 23 - MB;
+    constexpr unsigned REBIAS = (unsigned)(127 - BIAS) << 23;
+    constexpr unsigned MIN_NORMAL = (unsigned)(127 + 1 - BIAS) << 23;
+    constexpr unsigned TO_FIXED = (unsigned)(127 + 16 - (1 - BIAS - MB)) << 23;     // 2^16 / step
+    constexpr unsigned MAX_BITS = FMT == FP8_E4M3 ? 0x43E00000u : 0x47600000u;
+    constexpr unsigned MAX_CODE = FMT == FP8_E4M3 ? 0x7Eu : 0x7Bu;
+    constexpr unsigned INF_CODE = FMT == FP8_E4M3 ? 0x7Fu : 0x7Cu;
+    const unsigned u = as_u32(y);
+    const unsigned a = u & 0x7fffffffu;
+    const unsigned sign = (u >> 24) & 0x80u;
+    const unsigned T = (a >> (DROP - 16)) & 0xffffu;
+    const unsigned normal = ((a - REBIAS) >> DROP) + ((T + r16) >> 16);
+    const unsigned fixed = (unsigned)(as_f32(a < MIN_NORMAL ? a : 0u) * as_f32(TO_FIXED));   // truncates
+    const unsigned sub = (fixed + r16) >> 16;
+    unsigned code = a < MIN_NORMAL ? sub : normal;
+    code = a >= MAX_BITS ? MAX_CODE : code;
+    code = a >= 0x7f800000u ? INF_CODE : code;
+    code = a > 0x7f800000u ? 0x7Fu : code;
+    return sign | code;
+}
+
+// Philox4x32-10 (Salmon et al., SC 2011): counter (c0, c1, 0, 0), key (k0, k1).
+__device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned k0, unsigned k1, unsigned (&out)[4])
+{
+    unsigned c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Element e uses the 16-bit field e % 8 (low half of word 0 first) of generator block e / 8.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void quantize_sr_kernel(const void* __restrict__ x, size_t n, float scale,
+                                                              const float* __restrict__ scale_dev,
+                                                              unsigned seed_lo, unsigned seed_hi,
+                                                              uint8_t* __restrict__ q, bool vec)
+{
+    constexpr int V = DT == FP8_BF16 ? 2 : 4;
+    const float s = scale_dev ? *scale_dev : scale;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t done = 0;
+    if (vec) {
+        const u32x4* xv = (const u32x4*)x;
+        u32x4* qv = (u32x4*)q;
+        const size_t nitem = n / 16;
+        for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nitem; i += stride) {
+            u32x4 v[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) v[j] = __builtin_nontemporal_load(&xv[V * i + j]);
+            float y[16];
+            scale_item<DT>(v, s, y);
+            u32x4 o;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const size_t block = 2 * i + half;
+                unsigned w[4];
+                philox4x32_10((unsigned)block, (unsigned)(block >> 32), seed_lo, seed_hi, w);
+#pragma unroll
+                for (int d = 0; d < 2; ++d) {
+                    unsigned bytes = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int f = 4 * d + b;                       // field within the block
+                        const unsigned r = (w[f / 2] >> (16 * (f % 2))) & 0xffffu;
+                        bytes |= encode_sr_bits<FMT>(y[8 * half + f], r) << (8 * b);
+                    }
+                    o[2 * half + d] = bytes;
+                }
+            }
+            qv[i] = o;
+        }
+        done = nitem * 16;
+    }
+    for (size_t t = done + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
+        const size_t block = t / 8;
+        unsigned w[4];
+        philox4x32_10((unsigned)block, (unsigned)(block >> 32), seed_lo, seed_hi, w);
+        const unsigned f = (unsigned)(t % 8);
+        const unsigned r = (w[f / 2] >> (16 * (f % 2))) & 0xffffu;
+        q[t] = (uint8_t)encode_sr_bits<FMT>(load_scalar<DT>(x, t) * s, r);
+    }
+}
+
 #define FP8MM_DISPATCH_DT_FMT(KERNEL, grid, ...)                                                           \
     do {                                                                                                   \
         if (in_dtype == FP8_F32) {                                                                         \
@@ -297,6 +406,16 @@ int launch_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const f
     const dim3 grid(vec ? grid_for((n / 16 + 3) / 4, kCastBlocks) : grid_for(n, 2048));
     FP8MM_DISPATCH_DT_FMT(quantize_amax_kernel, grid, x, n, scale_dev, q_out, bits, vec);
     return check_launch("quantize_amax");
+}
+
+int launch_quantize_sr(const void* x, size_t n, int in_dtype, int fmt, float scale, const float* scale_dev,
+                       uint64_t seed, uint8_t* q_out, hipStream_t stream)
+{
+    if (n == 0) return FP8_OK;
+    const bool vec = aligned16(x) && aligned16(q_out);
+    const dim3 grid(vec ? grid_for(n / 16 + 1, kCastBlocks) : grid_for(n, 2048));
+    FP8MM_DISPATCH_DT_FMT(quantize_sr_kernel, grid, x, n, scale, scale_dev, (unsigned)seed, (unsigned)(seed >> 32), q_out, vec);
+    return check_launch("quantize_sr");
 }
 
 int launch_scale_from_history(const float* hist, size_t len, int fmt, float* scale_out, hipStream_t stream)

@@ -36,6 +36,8 @@ int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,
                     const float* scale_dev, bool saturate, uint8_t* q_out, hipStream_t stream);
 int launch_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const float* scale_dev, uint8_t* q_out,
                          float* amax_out, hipStream_t stream);
+int launch_quantize_sr(const void* x, size_t n, int in_dtype, int fmt, float scale, const float* scale_dev,
+                       uint64_t seed, uint8_t* q_out, hipStream_t stream);
 int launch_scale_from_history(const float* hist, size_t len, int fmt, float* scale_out, hipStream_t stream);
 int launch_scale_n(const float* amax, size_t n, int fmt, float* scale_out, hipStream_t stream);
 int launch_amax_rows(const void* x, int64_t rows, int64_t cols, int in_dtype, float* amax_out, hipStream_t stream);

@@ -162,3 +162,61 @@ def test_config2_size_single_pass_cast():
     want = oracle.quantize(x, E4M3, np.float32(0.1))
     got = q.cpu().numpy()
     assert np.array_equal(got, want), report_byte_mismatch(x, got, want)
+
+
+def sr_sweep_inputs(fmt):
+    """fp32 values over every binade the format sees (normal, subnormal, below the smallest
+    subnormal, above the maximum), both signs, with low mantissa bits set, plus grid points,
+    midpoints and specials."""
+    rng = np.random.default_rng(77 + fmt)
+    e = rng.integers(-30, 20, 400_000)
+    x = (rng.choice([-1.0, 1.0], e.size) * (1.0 + rng.random(e.size)) * 2.0 ** e).astype(np.float32)
+    vals = oracle.decode_all(fmt)
+    finite = vals[np.isfinite(vals)].astype(np.float32)
+    mids = ((finite[:-1].astype(np.float64) + finite[1:]) / 2).astype(np.float32)
+    extra = np.array([0.0, -0.0, np.nan, np.inf, -np.inf, 1e-45, -1e-45, 3e38, -3e38], dtype=np.float32)
+    bits = rng.integers(0, 2 ** 32, 100_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    return np.concatenate([x, finite, mids, np.nextafter(mids, np.float32(0)), extra, bits])
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_stochastic_rounding_cast(fmt):
+    x = sr_sweep_inputs(fmt)
+    n = x.size
+    for seed in (0, 0xDEADBEEFCAFEF00D):
+        q = torch.full((n,), 0xAA, dtype=torch.uint8, device="cuda")
+        fp8.fp8_quantize_sr(to_dev(x), fmt, 1.0, seed, q)
+        torch.cuda.synchronize()
+        want = oracle.quantize_sr(x, fmt, 1.0, seed)
+        got = q.cpu().numpy()
+        nan_in = np.isnan(x)
+        assert np.array_equal(got[~nan_in], want[~nan_in]), report_byte_mismatch(x.view(np.uint32)[~nan_in], got[~nan_in], want[~nan_in])
+        assert np.all((got[nan_in] & 0x7F) == (0x7F if fmt == E4M3 else 0x7F))
+    # bf16 input, device scale, a scale that is not a power of two; unaligned view (element path)
+    h = tensor(300_007, 5, "bf16", specials=True)
+    s = np.float32(13.7)
+    q = torch.empty(h.size, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_sr(to_dev(h), fmt, to_dev(np.array([s])), 99, q)
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy(), oracle.quantize_sr(h, fmt, s, 99))
+    q2 = torch.empty(h.size, dtype=torch.uint8, device="cuda")[3:]
+    fp8.fp8_quantize_sr(to_dev(h)[3:], fmt, float(s), 99, q2)
+    torch.cuda.synchronize()
+    assert np.array_equal(q2.cpu().numpy(), oracle.quantize_sr(h[3:], fmt, s, 99))
+
+
+def test_stochastic_rounding_is_unbiased_on_the_device():
+    n = 1 << 22
+    x = torch.full((n,), 0.3, device="cuda")
+    q = torch.empty(n, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_sr(x, E4M3, 3.7, 1234, q)
+    mean = fp8_mean(q, E4M3)
+    y = float(np.float32(0.3) * np.float32(3.7))
+    assert abs(mean - y) < 1e-3 * y          # RNE would be off by 1.2 % here (1.11 -> 1.125)
+
+
+def fp8_mean(q, fmt):
+    out = torch.empty(q.numel(), dtype=torch.float32, device="cuda")
+    fp8.fp8_dequantize(q, fmt, 1.0, out)
+    torch.cuda.synchronize()
+    return float(out.double().mean().item())
