@@ -1,7 +1,7 @@
 // GEMM dispatcher and the generic kernel for gfx950 (MI355X).
 //
-// Shapes and pointers that meet the tiled kernel's conditions (M, N multiples of 256, K a multiple
-// of 128, 16-byte aligned pointers) go to one of its instances; everything else is computed by the
+// Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 128, N a multiple of
+// 16, M too if A is stored K x M, 16-byte aligned pointers) go to one of its instances; everything else is computed by the
 // generic kernel below: any shape, any alignment, every storage order, the same epilogue
 // (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
 #include "gemm_common.hpp"
@@ -127,10 +127,14 @@ int launch_gemm(const GemmArgs& g)
     const bool aligned = aligned16(g.A) && aligned16(g.B) && aligned16(g.C) &&
                          (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
-    const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) && N < (1ll << 31) && K < (1ll << 31)
-                        && (M / TILE_M) * (N / TILE_N) < (1ll << 31);
-    const bool fast = !force_generic() && aligned && fits32 && M % TILE_M == 0 && N % TILE_N == 0 &&
-                      K % (2 * TILE_K) == 0;
+    const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
+                        K < (1ll << 31) && ((M + TILE_M - 1) / TILE_M) * ((N + TILE_N - 1) / TILE_N) < (1ll << 31);
+    // The tiled kernel works on 256 x 256 tiles and clips the last ones: loads of rows / columns
+    // beyond the edge are redirected to existing ones and their outputs are not stored.  What it
+    // needs: K in whole pairs of stages; rows of C and of an N-contiguous B that start on 16-byte
+    // boundaries (N % 16); the same for an M-contiguous A (M % 16).
+    const bool fast = !force_generic() && aligned && fits32 && K % (2 * TILE_K) == 0 && N % 16 == 0 &&
+                      (!g.transA || M % 16 == 0);
     if (fast) {
         typedef int (*tiled_fn)(const GemmArgs&);
         static const tiled_fn table[4][2] = {

@@ -1,36 +1,40 @@
-// FP8 x FP8 GEMM with fp32 accumulation and the fused unscale epilogue, for gfx950 (MI355X).
+// Tiled FP8 x FP8 GEMM with fp32 accumulation and the fused epilogue, for gfx950 (MI355X).
 //
-//   C[M x N] = alpha * A[M x K] * B[K x N],   alpha = 1 / (sA * sB)
+//   c[M x N] = (op(A)[M x K] x op(B)[K x N]) / (sA sB),   D = cast_out(c)
 //
-// A and B hold E4M3 / E5M2 bytes (arXiv 2209.05433, Table 1), both row-major; the products
-// are accumulated in fp32 by the matrix cores and the reciprocal of the two per-tensor scales
-// is applied once per output (Section 2), then the result is written as fp32 or bf16.
+// A and B hold E4M3 / E5M2 bytes (arXiv 2209.05433, Table 1), each in either storage order; the
+// products are accumulated in fp32 by the matrix cores and the reciprocals of the scaling factors
+// are applied once per output (Section 2); the result is written as fp32, bf16 or FP8.
 //
-// Fast kernel (M, N multiples of 256, K a multiple of 128, 16-byte aligned pointers):
+// Conditions (checked by the dispatcher): K a multiple of 128; N a multiple of 16, M too if A is
+// stored K x M; 16-byte aligned pointers.  M and N need not be multiples of the tile: loads of
+// rows / columns beyond the edge are redirected to existing ones, their outputs are not stored.
+//
 //   - one workgroup of 4 waves per 256 x 256 output tile, each wave owns 128 x 128 of it as
 //     4 x 4 blocks of v_mfma_f32_32x32x64_f8f6f4 (K = 64 per instruction, operand formats
 //     selected per operand, so the E5M2 x E4M3 mix costs nothing extra);
-//   - K is walked in stages of 64.  B comes as one 64 x 256 slab (16 KB) per stage in a ring of
-//     four; A as one 256 x 128 slab (32 KB) per pair of stages in a ring of three (160 KB of LDS in
-//     all), both filled by direct global->LDS loads issued three to four stages ahead of use.
-//     A rows are fetched 128 bytes at a time because the vector L1 keeps at most 64 requests to
-//     the L2 in flight and asks for whole 128-byte lines: 64-byte row pieces double its requests;
-//   - the MFMA wants, per lane, 32 consecutive-K bytes of one row (A) or one column (B).  A is
-//     K-contiguous in memory, so its fragments are plain 16-byte LDS reads.  B is N-contiguous;
-//     its fragments come from the transposing LDS read ds_read_b64_tr_b8, which hands each lane
-//     8 K-consecutive bytes of one column out of an 8 x 16 byte block;
-//   - both slabs are stored with an XOR swizzle of the 16-byte chunk index so that the
-//     fragment reads spread over the LDS banks; the swizzle is applied on the global side of
-//     the direct loads (LDS placement of a direct load is fixed: lane i writes 16 bytes at
-//     base + 16 i);
+//   - K is walked in stages of 64.  An operand that is contiguous along M / N in memory (B stored
+//     K x N, A stored K x M) comes as one 64 x 256 slab (16 KB) per stage in a ring of four; an
+//     operand that is contiguous along K (A stored M x K, B stored N x K) as one 256 x 128 slab
+//     (32 KB) per pair of stages in a ring of three (two for B if both are of this kind): 160 KB of
+//     LDS in all.  Slabs are filled by direct global->LDS loads issued two to four stages ahead of
+//     use.  K-contiguous rows are fetched 128 bytes at a time
+//     because the vector L1 keeps at most 64 requests to the L2 in flight and asks for whole
+//     128-byte lines: 64-byte row pieces double its requests;
+//   - the MFMA wants, per lane, 32 consecutive-K bytes of one row of op(A) / one column of op(B).
+//     From a K-contiguous slab these are plain 16-byte LDS reads; from the other kind they come
+//     through the transposing LDS read ds_read_b64_tr_b8, which hands each lane 8 K-consecutive
+//     bytes of one column out of an 8 x 16 byte block.  No transposed copy of an operand is made;
+//   - slabs are stored with an XOR swizzle of the 16-byte chunk index so that the fragment reads
+//     spread over the LDS banks; the swizzle is applied on the global side of the direct loads
+//     (LDS placement of a direct load is fixed: lane i writes 16 bytes at base + 16 i);
 //   - the instruction computes D[i][j] with operand 0 supplying i.  B fragments are operand 0,
 //     so every lane ends up with 4 consecutive N outputs of one row of C; the epilogue turns
 //     32 x 128 blocks around through LDS and stores whole 128-byte lines;
 //   - workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile map
 //     gives every XCD one contiguous run of a column-sweeping order in bands of 8 tile rows,
 //     so the 32 tiles an XCD works on at a time share 8 row slabs of A and 4 column slabs of
-//     B in its L2.
-//
+//     B in its L2;
 //   - the products are formed either by the FP8 instruction above (ACC_FP8) or, after an exact
 //     widening of the bytes to fp16 in registers, by v_mfma_f32_32x32x16_f16 (ACC_F16, the
 //     default): see the note at the ACC_* constants for why both exist.
@@ -138,9 +142,11 @@ struct Operand {
 };
 
 template <bool KC>
-__device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, unsigned ld, int r0, unsigned region,
-                                              int w, int l, int wsel)
+__device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, unsigned ld, int r0, int valid,
+                                              unsigned region, int w, int l, int wsel)
 {
+    // `valid` (1..256) rows / columns of the tile exist; loads of the others are redirected to an
+    // existing one (their products only reach outputs that are never stored).
     op.ld = ld;
     op.region = region;
     const int h = l >> 5;
@@ -149,7 +155,7 @@ __device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, 
 #pragma unroll
         for (int t = 0; t < 8; ++t) {                 // instruction ia fills rows 8 ia .. 8 ia + 7 (1 KB)
             const int row = (w * 8 + t) * 8 + (l >> 3);
-            op.off[t] = (unsigned)row * ld + (((l & 7) ^ swz_kc(row)) * 16);
+            op.off[t] = (unsigned)min(row, valid - 1) * ld + (((l & 7) ^ swz_kc(row)) * 16);
         }
         // lane = (r = l % 32, h = l / 32) reads K bytes 32h .. 32h+31 of row r of its stage:
         // chunks 4 par + 2h and + 1 of the 128-byte row (par = stage parity)
@@ -160,7 +166,8 @@ __device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, 
 #pragma unroll
         for (int t = 0; t < 4; ++t) {                 // instruction ib fills K-rows 4 ib .. 4 ib + 3 (1 KB)
             const int krow = (w * 4 + t) * 4 + (l >> 4);
-            op.off[t] = (unsigned)krow * ld + (((l & 15) ^ swz_mc(krow)) * 16);
+            const int chunk = (l & 15) ^ swz_mc(krow);           // 16 columns; `valid` is a multiple of 16 here
+            op.off[t] = (unsigned)krow * ld + min(chunk, (valid - 1) >> 4) * 16;
         }
 #pragma unroll
         for (int t = 4; t < 8; ++t) op.off[t] = 0;
@@ -212,7 +219,7 @@ __device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op
 // pass through LDS as fp32 (already multiplied by the output scale) and are rounded after it,
 // 16 consecutive columns per lane, by the same routine as in the cast kernel.
 template <int OUT, bool BVEC>
-__device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int N,
+__device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int M, int N,
                                          int wave_m0, int wave_n0, int w, int l)
 {
     constexpr bool FP8OUT = OUT == OUT_E4M3 || OUT == OUT_E5M2;
@@ -228,7 +235,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
         const double b = BVEC ? 1.0 : (double)scale_value(ep.sB_dev, ep.sB);
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-            const float a = ep.a_per_row ? ep.sA_dev[wave_m0 + mb * 32 + (l & 31)] : scale_value(ep.sA_dev, ep.sA);
+            const float a = ep.a_per_row ? ep.sA_dev[min(wave_m0 + mb * 32 + (l & 31), M - 1)] : scale_value(ep.sA_dev, ep.sA);
             ra[mb] = (float)(1.0 / ((double)a * b));
         }
     }
@@ -238,7 +245,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
         for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const v4f s = *(const v4f*)(ep.sB_dev + wave_n0 + nb * 32 + 8 * q + 4 * h);
+                const v4f s = *(const v4f*)(ep.sB_dev + min(wave_n0 + nb * 32 + 8 * q + 4 * h, N - 4));
                 cb[BVEC ? nb : 0][BVEC ? q : 0] = (v4f){1.0f / s.x, 1.0f / s.y, 1.0f / s.z, 1.0f / s.w};
             }
     }
@@ -261,8 +268,12 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
                     c0 *= s.x; c1 *= s.y; c2 *= s.z; c3 *= s.w;
                 }
                 if (ep.amax_out) {
-                    const unsigned m01 = max(as_u32(c0) & 0x7fffffffu, as_u32(c1) & 0x7fffffffu);
-                    const unsigned m23 = max(as_u32(c2) & 0x7fffffffu, as_u32(c3) & 0x7fffffffu);
+                    // outputs beyond the edges of C hold products of redirected loads: not counted
+                    // (N is a multiple of 16, so the four columns are inside or outside together)
+                    const bool inside = wave_m0 + mb * 32 + (l & 31) < M && wave_n0 + nb * 32 + 8 * q + 4 * h < N;
+                    const unsigned keep = inside ? 0x7fffffffu : 0u;
+                    const unsigned m01 = max(as_u32(c0) & keep, as_u32(c1) & keep);
+                    const unsigned m23 = max(as_u32(c2) & keep, as_u32(c3) & keep);
                     amax_bits = max(amax_bits, max(m01, m23));
                 }
                 uint8_t* dst = blk + (l & 31) * ROWB + (nb * 32 + 8 * q + 4 * h) * LSZ;
@@ -281,6 +292,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
         for (int i = 0; i < 32 / ROWS_PER_ST; ++i) {
             const int row = i * ROWS_PER_ST + st_row;
             uint8_t* out = c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col;
+            if (wave_m0 + mb * 32 + row >= M || wave_n0 + st_col / ESZ >= N) continue;   // beyond the edges of C
             if (FP8OUT) {
                 float y[16];
 #pragma unroll
@@ -316,22 +328,23 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int wm = w >> 1, wn = w & 1;
-    const TileMap tile = map_tile(blockIdx.x, M / BM, N / BN, group_m);
+    const TileMap tile = map_tile(blockIdx.x, (M + BM - 1) / BM, (N + BN - 1) / BN, group_m);
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
     const int KT = K / BK;
     const int h = l >> 5;
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
 
     Operand opA, opB;
-    operand_setup<A_KC>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, A_REGION, w, l, wm);
-    operand_setup<B_KC>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, B_REGION, w, l, wn);
+    operand_setup<A_KC>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, min(BM, M - m0), A_REGION, w, l, wm);
+    operand_setup<B_KC>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, min(BN, N - n0), B_REGION, w, l, wn);
 
     // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
     // the steps -5 .. -1).  Step s issues, in this order:
-    //   for a K-contiguous operand, in parts 0..3: if s is odd the first four loads of the slab of
-    //                stage pair (s+1)/2 + ring - 1 (into the slot that stage s frees), if s is
-    //                even the other four loads of pair s/2 + ring - 1;
+    //   for a K-contiguous operand, if s is odd: the slab of stage pair (s+1)/2 + ring - 1 into
+    //                the slot that stage s frees (8 loads per wave, two in each of parts 0..3);
     //   for an MN-contiguous operand the slab of stage s + 4 (4 loads per wave, parts 4..7).
+    // (Splitting the pair slab over the odd and the even step, for the same number of loads in
+    // every step, measured 2 % slower in the FP8 mode.)
     // If both operands are K-contiguous, B's ring holds two pairs only and its loads have less
     // than two steps to arrive; they must not queue behind A's.  Then the odd steps issue B alone
     // and the even step s issues A's pair s/2 + 2, one load per part, into the slot of the pair
@@ -342,8 +355,8 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     auto count_step = [&](int s) {
         int n = 0;
         if (A_KC && B_KC) return ((s & 1) ? pair_valid(kc_pair_of(s, B_RING)) : pair_valid(s / 2 + A_RING - 1)) ? 8 : 0;
-        if (A_KC && pair_valid((s & 1) ? kc_pair_of(s, A_RING) : s / 2 + A_RING - 1)) n += 4;
-        if (B_KC && pair_valid((s & 1) ? kc_pair_of(s, B_RING) : s / 2 + B_RING - 1)) n += 4;
+        if (A_KC && (s & 1) && pair_valid(kc_pair_of(s, A_RING))) n += 8;
+        if (B_KC && (s & 1) && pair_valid(kc_pair_of(s, B_RING))) n += 8;
         if (!A_KC && stage_valid(s + 4)) n += 4;
         if (!B_KC && stage_valid(s + 4)) n += 4;
         return n;
@@ -390,10 +403,10 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                 if (pair_valid(p)) issue_kc(opA, p, sa, j);
             }
         } else if (j < 4) {
-            // the first half of a pair slab in the odd step that frees its slot, the second half
-            // in the even step after it: every step issues the same number of loads
-            if (A_KC) { const int p = odd ? kc_pair_of(s, A_RING) : s / 2 + A_RING - 1; if (pair_valid(p)) issue_kc(opA, p, sa, odd ? j : 4 + j); }
-            if (B_KC) { const int p = odd ? kc_pair_of(s, B_RING) : s / 2 + B_RING - 1; if (pair_valid(p)) issue_kc(opB, p, sb, odd ? j : 4 + j); }
+            if (odd) {
+                if (A_KC) { const int p = kc_pair_of(s, A_RING); if (pair_valid(p)) { issue_kc(opA, p, sa, 2 * j); issue_kc(opA, p, sa, 2 * j + 1); } }
+                if (B_KC) { const int p = kc_pair_of(s, B_RING); if (pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); } }
+            }
         } else if (stage_valid(s + 4)) {
             if (!A_KC) issue_mc(opA, s + 4, j - 4);
             if (!B_KC) issue_mc(opB, s + 4, j - 4);
@@ -467,8 +480,8 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[4],
                       v8i (&af_n)[4], v8i (&bf_n)[4]) {
         // slot that A's loads of this step go to
-        const int sa_ld = (A_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
-        const int sb_ld = (B_KC && !A_KC && !odd) ? (sb == 0 ? B_RING - 1 : sb - 1) : sb;
+        const int sa_ld = (A_KC && B_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
+        const int sb_ld = sb;
         if (kt + 8 < KT) {
             if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
         } else {
@@ -517,17 +530,17 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const int wave_m0 = m0 + wm * 128, wave_n0 = n0 + wn * 128;
     if (ep.b_per_col) {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, true>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
         }
     } else {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, false>(acc, smem, ep, C, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
         }
     }
 }
@@ -553,7 +566,7 @@ int launch_fast(const GemmArgs& g)
             return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
         attr_set = true;
     }
-    const int tiles = (int)((g.M / BM) * (g.N / BN));
+    const int tiles = (int)(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN));
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
                        (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting());
     return check_launch("gemm (tiled kernel)");

@@ -285,3 +285,66 @@ def test_config4_shape_fp8_output_full_size():
                                 min_exact=0.999 if mode == "f16" else 0.80)
         check_wide(C[ti, tj], S, T, sA, sB, fp8.FP8_OUT_BF16, mode, "config 4 bf16 out via fused " + mode)
         print("config 4 shape, E4M3 output (%s): %.4f of sampled bytes equal the oracle's" % (mode, exact), flush=True)
+
+
+RAGGED = [(300, 272, 256), (8, 16, 128), (1, 1008, 384), (1000, 48, 128), (513, 528, 256), (255, 256, 128)]
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_edge_tiles_of_the_tiled_kernel(transA, transB, mode):
+    """M and N that are not multiples of the 256 x 256 tile (N a multiple of 16, M too if A is stored
+    K x M) run in the tiled kernel with clipped edge tiles: every output kind, per-channel factors
+    and the output amax must come out as for whole tiles, and nothing may be written past the edges."""
+    rng = np.random.default_rng(400 + 2 * transA + transB)
+    for (M, N, K) in RAGGED:
+        if transA and M % 16:
+            M = (M + 15) // 16 * 16
+        A = random_codes(rng, (M, K), E4M3)
+        B = random_codes(rng, (K, N), E5M2, 0x6F)
+        S, T = oracle.gemm_rows(A, E4M3, B, E5M2)
+        sA = rng.uniform(0.5, 4.0, M).astype(np.float32)
+        sB = rng.uniform(0.5, 4.0, N).astype(np.float32)
+        dA = to_dev(np.ascontiguousarray(A.T) if transA else A)
+        dB = to_dev(np.ascontiguousarray(B.T) if transB else B)
+        c_ref, b = reference(S, T, sA, sB, mode)
+        for out_kind in (fp8.FP8_OUT_F32, fp8.FP8_OUT_BF16, fp8.FP8_OUT_E4M3):
+            # the output sits inside a larger buffer whose surroundings must stay untouched
+            esz = {fp8.FP8_OUT_F32: 4, fp8.FP8_OUT_BF16: 2, fp8.FP8_OUT_E4M3: 1}[out_kind]
+            pad = 4096 // esz
+            buf = torch.zeros(2 * pad + M * N, dtype=OUT_T[out_kind], device="cuda")
+            buf.fill_(7)
+            D = buf[pad:pad + M * N].view(M, N)
+            amax = torch.full((1,), -1.0, device="cuda")
+            sD = None
+            if out_kind == fp8.FP8_OUT_E4M3:
+                sD = dev_f32(np.float32(448.0 / np.max(np.abs(c_ref))))
+            fp8.fp8_gemm_fused(dA, E4M3, transA, dB, E5M2, transB, D, out_kind, dev_f32(sA), dev_f32(sB), sD, amax,
+                               flags_of(mode))
+            torch.cuda.synchronize()
+            what = "edge tiles %s layout %d%d out %d %s" % ((M, N, K), transA, transB, out_kind, mode)
+            assert bool((buf[:pad] == 7).all()) and bool((buf[pad + M * N:] == 7).all()), what + ": wrote outside D"
+            if out_kind == fp8.FP8_OUT_E4M3:
+                check_fp8_bytes(D.cpu().numpy(), c_ref, b, np.float32(sD.item()), E4M3, what,
+                                min_exact=0.99 if mode == "f16" else 0.80)
+            else:
+                check_wide(D, S, T, sA, sB, out_kind, mode, what)
+            check_amax(np.float32(amax.item()), c_ref, b, what)
+
+
+def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers():
+    import os
+    rng = np.random.default_rng(9)
+    for (M, N, K) in RAGGED:
+        A, B = int_codes(rng, (M, K)), int_codes(rng, (K, N))
+        S, _ = oracle.gemm_rows(A, E4M3, B, E4M3)
+        for mode in MODES:
+            D, amax = run_fused(A, E4M3, B, E4M3, fp8.FP8_OUT_F32, np.float32(0.5), np.float32(4.0), want_amax=True, mode=mode)
+            assert np.array_equal(out_to_f64(D), S / 2.0), (M, N, K, mode)
+            assert float(amax) == np.max(np.abs(S / 2.0))
+        os.environ["FP8MM_GEMM"] = "generic"
+        try:
+            G, _ = run_fused(A, E4M3, B, E4M3, fp8.FP8_OUT_F32, np.float32(0.5), np.float32(4.0))
+        finally:
+            del os.environ["FP8MM_GEMM"]
+        assert np.array_equal(out_to_f64(G), S / 2.0)
