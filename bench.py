@@ -170,6 +170,7 @@ def main():
                          "unit": "TFLOP/s", "frac": round(flops / gemm8_ms * 1e-9 / PEAK_FP8_TFLOPS, 4)},
             "note": "meets 2^-10 * sum|ab| (hardware adder window), not the 2^-20 bound of the default path",
         }
+        result["gemm_variants"] = gemm_variants(fp8, torch, qA, qB, scale, fmtA, fmtB, M, N, K, out_dtype, flops, args)
         del dA, dB, qA, qB, C
         torch.cuda.empty_cache()
         result["quantize_only"] = quantize_only(fp8, synth, torch, np, args)
@@ -178,6 +179,49 @@ def main():
         result["cpu_baseline"] = cpu_baseline(A_bits, B_bits, M, N, K, fmtA, fmtB, flops)
 
     print(json.dumps(result))
+
+
+def _event_ms(torch, fn, iters, warm=2):
+    """Average duration of fn over iters launches, from events on torch's current stream."""
+    stream = torch.cuda.current_stream()
+    for _ in range(warm):
+        fn()
+    e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    torch.cuda.synchronize()
+    for a, b in e:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in e) / iters
+
+
+def gemm_variants(fp8, torch, qA, qB, scale, fmtA, fmtB, M, N, K, out_dtype, flops, args):
+    """The same product through the other entry points: operands given transposed (the storage orders
+    of the dgrad / wgrad GEMMs of a linear layer), FP8 output with output scale and amax, per-channel
+    factors.  TFLOP/s of the GEMM launch alone."""
+    iters = max(3, args.steps // 4)
+    out = {}
+    qAt, qBt = qA.t().contiguous(), qB.t().contiguous()
+    C = torch.empty((M, N), dtype=out_dtype, device="cuda")
+    for tA, tB, a, b in ((0, 1, qA, qBt), (1, 0, qAt, qB), (1, 1, qAt, qBt)):
+        for flags, mode in ((0, "fp16_instr"), (fp8.FP8_GEMM_MFMA8, "fp8_instr")):
+            ms = _event_ms(torch, lambda: fp8.fp8_gemm_ex(a, fmtA, tA, b, fmtB, tB, C, scale[0:1], scale[1:2], flags), iters)
+            out["gemm_ex_transA%d_transB%d_%s" % (tA, tB, mode)] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms * 1e-9, 1)}
+    del qAt, qBt
+    D = torch.empty((M, N), dtype=torch.uint8, device="cuda")
+    amax = torch.zeros(1, device="cuda")
+    sD = torch.ones(1, device="cuda")
+    sAv = torch.ones(M, device="cuda") * scale[0]
+    sBv = torch.ones(N, device="cuda") * scale[1]
+    for flags, mode in ((0, "fp16_instr"), (fp8.FP8_GEMM_MFMA8, "fp8_instr")):
+        ms = _event_ms(torch, lambda: fp8.fp8_gemm_fused(qA, fmtA, 0, qB, fmtB, 0, D, fp8.FP8_OUT_E4M3, scale[0:1], scale[1:2],
+                                                         sD, amax, flags), iters)
+        out["gemm_fused_e4m3_out_amax_%s" % mode] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms * 1e-9, 1)}
+        ms = _event_ms(torch, lambda: fp8.fp8_gemm_fused(qA, fmtA, 0, qB, fmtB, 0, C, fp8.FP8_OUT_BF16 if C.dtype == torch.bfloat16 else fp8.FP8_OUT_F32,
+                                                         sAv, sBv, None, None, flags), iters)
+        out["gemm_fused_per_row_per_col_%s" % mode] = {"ms": round(ms, 4), "TFLOP/s": round(flops / ms * 1e-9, 1)}
+    return out
 
 
 def quantize_only(fp8, synth, torch, np, args):
@@ -212,6 +256,21 @@ def quantize_only(fp8, synth, torch, np, args):
         ms = t(lambda: fp8.fp8_quantize_dscale(x, fmt, scale, q), iters)
         out[name] = {"us": round(ms * 1e3, 1), "GB/s": round(3.0 * n / ms * 1e-6, 1),
                      "frac_of_hbm_peak": round(3.0 * n / ms * 1e-6 / PEAK_HBM_GBS, 4)}
+
+    # variants of the cast (algorithmic bytes per element: bf16 in, bytes out)
+    def rate(name, ms, bytes_per_elem):
+        out[name] = {"us": round(ms * 1e3, 1), "GB/s": round(bytes_per_elem * n / ms * 1e-6, 1),
+                     "frac_of_hbm_peak": round(bytes_per_elem * n / ms * 1e-6 / PEAK_HBM_GBS, 4)}
+    rate("cast_amax_single_pass_e4m3", t(lambda: fp8.fp8_quantize_amax(x, 0, scale, q, amax), iters), 3.0)
+    rate("cast_stochastic_e4m3", t(lambda: fp8.fp8_quantize_sr(x, 0, scale, 1234, q), iters), 3.0)
+    rows, cols = 1 << 14, 1 << 14
+    xm, qm = x.view(rows, cols), q.view(rows, cols)
+    qt = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
+    rate("cast_transpose_e4m3_16384x16384_both_orders", t(lambda: fp8.fp8_quantize_transpose(xm, 0, scale, qm, qt), iters), 4.0)
+    del qt
+    ar, sr = torch.zeros(rows, device="cuda"), torch.ones(rows, device="cuda")
+    rate("amax_rows_16384x16384", t(lambda: fp8.fp8_amax_rows(xm, ar), iters), 2.0)
+    rate("cast_rows_e4m3_16384x16384", t(lambda: fp8.fp8_quantize_rows(xm, 0, sr, qm), iters), 3.0)
     return out
 
 

@@ -9,7 +9,7 @@ namespace fp8mm {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kAmaxBlocks = 256 * 2;      // read-only stream: 2 workgroups per compute unit measured best
+constexpr int kAmaxBlocks = 256 * 4;      // read-only stream: 32 KB chunks dealt to this many workgroups measured best
 constexpr int kCastBlocks = 256 * 64;     // read+write stream: many short contiguous chunks measured best
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));

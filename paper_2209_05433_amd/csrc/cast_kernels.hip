@@ -14,6 +14,11 @@ namespace fp8mm {
 namespace {
 
 // Vector path: x is 16-byte aligned.  nvec full vectors, then n - nvec*per_vec tail elements.
+// Every workgroup takes whole chunks of 32 KB (8 vectors per lane, all loaded before the first
+// compare), four workgroups per compute unit; one atomic per workgroup at the end (with one chunk
+// per workgroup the thousands of atomics on one cell cost a quarter of the run time).
+constexpr int kAmaxChunkVecs = kThreads * 8;
+
 template <int DT>
 __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restrict__ x, size_t n,
                                                            unsigned* __restrict__ out_bits)
@@ -21,31 +26,32 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
     constexpr int PV = Elem<DT>::per_vec;
     const u32x4* xv = (const u32x4*)x;
     const size_t nvec = n / PV;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-    unsigned r0 = 0, r1 = 0, r2 = 0, r3 = 0;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {
-        const u32x4 a = __builtin_nontemporal_load(&xv[i]), b = __builtin_nontemporal_load(&xv[i + stride]);
-        const u32x4 c = __builtin_nontemporal_load(&xv[i + 2 * stride]), d = __builtin_nontemporal_load(&xv[i + 3 * stride]);
-        r0 = vec_mag_max<DT>(a, r0);
-        r1 = vec_mag_max<DT>(b, r1);
-        r2 = vec_mag_max<DT>(c, r2);
-        r3 = vec_mag_max<DT>(d, r3);
+    const size_t nchunk = nvec / kAmaxChunkVecs;
+    unsigned run[4] = {0u, 0u, 0u, 0u};
+    for (size_t c = blockIdx.x; c < nchunk; c += gridDim.x) {
+        const u32x4* p = xv + c * kAmaxChunkVecs + threadIdx.x;
+        u32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(p + j * kThreads);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) run[j & 3] = vec_mag_max<DT>(v[j], run[j & 3]);
     }
-    for (; i < nvec; i += stride) r0 = vec_mag_max<DT>(__builtin_nontemporal_load(&xv[i]), r0);
+    // vectors after the last whole chunk, then the tail elements: workgroup 0
+    if (blockIdx.x == 0) {
+        for (size_t i = nchunk * kAmaxChunkVecs + threadIdx.x; i < nvec; i += kThreads)
+            run[0] = vec_mag_max<DT>(__builtin_nontemporal_load(&xv[i]), run[0]);
+    }
     unsigned r;
     if (DT == FP8_F32) {
-        r0 = r0 > r1 ? r0 : r1;
-        r2 = r2 > r3 ? r2 : r3;
-        r = r0 > r2 ? r0 : r2;
+        const unsigned a = run[0] > run[1] ? run[0] : run[1], b = run[2] > run[3] ? run[2] : run[3];
+        r = a > b ? a : b;
     } else {
         u16x2 p = __builtin_elementwise_max(
-            __builtin_elementwise_max(__builtin_bit_cast(u16x2, r0), __builtin_bit_cast(u16x2, r1)),
-            __builtin_elementwise_max(__builtin_bit_cast(u16x2, r2), __builtin_bit_cast(u16x2, r3)));
+            __builtin_elementwise_max(__builtin_bit_cast(u16x2, run[0]), __builtin_bit_cast(u16x2, run[1])),
+            __builtin_elementwise_max(__builtin_bit_cast(u16x2, run[2]), __builtin_bit_cast(u16x2, run[3])));
         unsigned short m = p.x > p.y ? p.x : p.y;
         r = (unsigned)m << 16;
     }
-    // tail elements: first threads of block 0
     if (blockIdx.x == 0) {
         size_t t = nvec * PV + threadIdx.x;
         if (t < n) {
@@ -54,7 +60,8 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
         }
     }
     r = block_max_u32(r);
-    if (threadIdx.x == 0) atomicMax(out_bits, r);
+    // most workgroups find the cell already large enough and skip the atomic
+    if (threadIdx.x == 0 && r > __hip_atomic_load(out_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out_bits, r);
 }
 
 // Any alignment the element type allows: one element per lane per step.
@@ -153,7 +160,8 @@ int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStrea
     if (n == 0) return check_launch("amax init");
     if (aligned16(x)) {
         const size_t per_vec = in_dtype == FP8_F32 ? 4 : 8;
-        const int grid = grid_for((n / per_vec + 3) / 4, kAmaxBlocks);
+        const size_t nchunk = n / per_vec / kAmaxChunkVecs;
+        const int grid = (int)(nchunk < 1 ? 1 : nchunk > (size_t)kAmaxBlocks ? (size_t)kAmaxBlocks : nchunk);
         if (in_dtype == FP8_F32)
             hipLaunchKernelGGL(amax_vec_kernel<FP8_F32>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
         else

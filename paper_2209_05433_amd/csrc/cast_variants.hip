@@ -211,7 +211,19 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
     constexpr int PASSES = TT / RPP;
     __shared__ __attribute__((aligned(16))) uint8_t tile[TT * TT_PITCH];
     const float s = *scale_dev;
-    const int64_t r0 = (int64_t)blockIdx.y * TT, c0 = (int64_t)blockIdx.x * TT;
+    // Workgroup id -> tile.  The few hundred workgroups in flight at a time cover a square of
+    // 16 x 16 tiles, so that the reads of x, the writes of q and the writes of q^T each touch runs
+    // of 2 KB or more of consecutive addresses close together in time (with a row-by-row order the
+    // q^T rows would get 128 bytes each per pass over a row of tiles).
+    constexpr int SQ = 16;
+    const int tiles_r = (int)((rows + TT - 1) / TT), tiles_c = (int)((cols + TT - 1) / TT);
+    const int band = blockIdx.x / (SQ * tiles_c);                  // band of SQ tile rows
+    const int band_rows = min(SQ, tiles_r - band * SQ);
+    const int in_band = blockIdx.x - band * SQ * tiles_c;
+    const int sq = in_band / (band_rows * SQ);                      // square within the band (all but the last are SQ wide)
+    const int sq_cols = min(SQ, tiles_c - sq * SQ);
+    const int in_sq = in_band - sq * band_rows * SQ;
+    const int64_t r0 = (int64_t)(band * SQ + in_sq / sq_cols) * TT, c0 = (int64_t)(sq * SQ + in_sq % sq_cols) * TT;
     const int tid = threadIdx.x;
     const int lr = tid / LPR, lc = (tid % LPR) * EPL;    // lane's row within a pass, first column
 
@@ -403,7 +415,7 @@ int launch_quantize_amax(const void* x, size_t n, int in_dtype, int fmt, const f
     hipLaunchKernelGGL(store_u32_kernel, dim3(1), dim3(1), 0, stream, bits, 0u);
     if (n == 0) return check_launch("quantize_amax init");
     const bool vec = aligned16(x) && aligned16(q_out);
-    const dim3 grid(vec ? grid_for((n / 16 + 3) / 4, kCastBlocks) : grid_for(n, 2048));
+    const dim3 grid(vec ? grid_for((n / 16 + 3) / 4, 512) : grid_for(n, 2048));   // 512 measured best (one atomic each)
     FP8MM_DISPATCH_DT_FMT(quantize_amax_kernel, grid, x, n, scale_dev, q_out, bits, vec);
     return check_launch("quantize_amax");
 }
@@ -458,9 +470,9 @@ int launch_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_
     if (rows == 0 || cols == 0) return FP8_OK;
     const int64_t tiles_r = (rows + TT - 1) / TT, tiles_c = (cols + TT - 1) / TT;
     const bool vec = aligned16(x) && aligned16(qt_out) && (!q_out || aligned16(q_out)) && rows % 16 == 0 && cols % 16 == 0 &&
-                     tiles_r < 65536 && tiles_c < (1ll << 31);
+                     tiles_r * tiles_c < (1ll << 31);
     if (vec) {
-        const dim3 grid((unsigned)tiles_c, (unsigned)tiles_r);
+        const dim3 grid((unsigned)(tiles_r * tiles_c));
         FP8MM_DISPATCH_DT_FMT(quantize_transpose_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);
     } else {
         const dim3 grid(grid_for((size_t)rows * (size_t)cols, 4096));
