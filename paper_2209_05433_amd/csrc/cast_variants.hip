@@ -180,8 +180,8 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const void* __r
 
 // ------------------------------------------------------------------------------------------
 // cast + transpose.  One workgroup per 128 x 128 tile of x.  A lane converts 8 (bf16) or 4 (fp32)
-// consecutive elements of a row: their bytes go straight to q (a wave instruction covers whole
-// 128-byte rows of the tile) and into an LDS copy of the tile.  The transposed tile leaves through
+// consecutive elements of a row into an LDS copy of the tile; q is stored from there 16 bytes per
+// lane (a wave instruction covers 8 whole 128-byte rows of the tile).  The transposed tile leaves through
 // the transposing LDS read of gfx950 (ds_read_b64_tr_b8: 16 lanes read an 8 x 16 byte block and
 // each receives one column of it), two per lane = 16 consecutive bytes of a row of q^T.
 // ------------------------------------------------------------------------------------------
@@ -211,19 +211,9 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
     constexpr int PASSES = TT / RPP;
     __shared__ __attribute__((aligned(16))) uint8_t tile[TT * TT_PITCH];
     const float s = *scale_dev;
-    // Workgroup id -> tile.  The few hundred workgroups in flight at a time cover a square of
-    // 16 x 16 tiles, so that the reads of x, the writes of q and the writes of q^T each touch runs
-    // of 2 KB or more of consecutive addresses close together in time (with a row-by-row order the
-    // q^T rows would get 128 bytes each per pass over a row of tiles).
-    constexpr int SQ = 16;
-    const int tiles_r = (int)((rows + TT - 1) / TT), tiles_c = (int)((cols + TT - 1) / TT);
-    const int band = blockIdx.x / (SQ * tiles_c);                  // band of SQ tile rows
-    const int band_rows = min(SQ, tiles_r - band * SQ);
-    const int in_band = blockIdx.x - band * SQ * tiles_c;
-    const int sq = in_band / (band_rows * SQ);                      // square within the band (all but the last are SQ wide)
-    const int sq_cols = min(SQ, tiles_c - sq * SQ);
-    const int in_sq = in_band - sq * band_rows * SQ;
-    const int64_t r0 = (int64_t)(band * SQ + in_sq / sq_cols) * TT, c0 = (int64_t)(sq * SQ + in_sq % sq_cols) * TT;
+    // tile order: along the rows of x (measured: square super-tiles of 4 .. 32 tiles change the rate by
+    // a few per cent in either direction depending on the shape)
+    const int64_t r0 = (int64_t)blockIdx.y * TT, c0 = (int64_t)blockIdx.x * TT;
     const int tid = threadIdx.x;
     const int lr = tid / LPR, lc = (tid % LPR) * EPL;    // lane's row within a pass, first column
 
@@ -239,7 +229,6 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int tr = p * RPP + lr;
-        const int64_t r = r0 + tr, c = c0 + lc;
         unsigned b0, b1 = 0;
         if (DT == FP8_BF16) {
             b0 = encode4<FMT>(as_f32(v[p].x << 16) * s, as_f32(v[p].x & 0xffff0000u) * s,
@@ -247,14 +236,22 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
             b1 = encode4<FMT>(as_f32(v[p].z << 16) * s, as_f32(v[p].z & 0xffff0000u) * s,
                               as_f32(v[p].w << 16) * s, as_f32(v[p].w & 0xffff0000u) * s);
             *LDS_PTR(v2i, tile + tr * TT_PITCH + lc) = (v2i){(int)b0, (int)b1};
-            if (q && r < rows && c < cols) *(v2i*)(q + (size_t)r * (size_t)cols + (size_t)c) = (v2i){(int)b0, (int)b1};
         } else {
             b0 = encode4<FMT>(as_f32(v[p].x) * s, as_f32(v[p].y) * s, as_f32(v[p].z) * s, as_f32(v[p].w) * s);
             *LDS_PTR(unsigned, tile + tr * TT_PITCH + lc) = b0;
-            if (q && r < rows && c < cols) *(unsigned*)(q + (size_t)r * (size_t)cols + (size_t)c) = b0;
         }
     }
     __syncthreads();
+    // q: 16 bytes per lane, 8 lanes per 128-byte tile row, 32 rows per pass of the workgroup
+    if (q) {
+#pragma unroll
+        for (int p = 0; p < TT / 32; ++p) {
+            const int tr = p * 32 + (tid >> 3), tc = (tid & 7) * 16;
+            const int64_t r = r0 + tr, c = c0 + tc;
+            if (r < rows && c < cols)
+                *(u32x4*)(q + (size_t)r * (size_t)cols + (size_t)c) = *LDS_PTR(u32x4, tile + tr * TT_PITCH + tc);
+        }
+    }
     // q^T: tile column tc (a row of q^T), 16 consecutive tile rows per lane.  A wave instruction
     // covers 16 columns x 64 rows; wave w owns the columns 32 w .. 32 w + 31.
     const int w = tid >> 6, l = tid & 63;
@@ -470,9 +467,9 @@ int launch_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_
     if (rows == 0 || cols == 0) return FP8_OK;
     const int64_t tiles_r = (rows + TT - 1) / TT, tiles_c = (cols + TT - 1) / TT;
     const bool vec = aligned16(x) && aligned16(qt_out) && (!q_out || aligned16(q_out)) && rows % 16 == 0 && cols % 16 == 0 &&
-                     tiles_r * tiles_c < (1ll << 31);
+                     tiles_r < 65536 && tiles_c < (1ll << 31);
     if (vec) {
-        const dim3 grid((unsigned)(tiles_r * tiles_c));
+        const dim3 grid((unsigned)tiles_c, (unsigned)tiles_r);
         FP8MM_DISPATCH_DT_FMT(quantize_transpose_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);
     } else {
         const dim3 grid(grid_for((size_t)rows * (size_t)cols, 4096));
