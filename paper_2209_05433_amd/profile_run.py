@@ -4,6 +4,7 @@ few times, with random FP8 bytes / bf16 values already resident in HBM.
 
     python3 -m paper_2209_05433_amd.profile_run --workload ffn_up_175b --mode f16 --iters 3
     python3 -m paper_2209_05433_amd.profile_run --workload quantize_only --iters 3
+    python3 -m paper_2209_05433_amd.profile_run --workload cast_variants --iters 3
 """
 from __future__ import annotations
 
@@ -27,7 +28,7 @@ def random_codes(shape, top=0x5F):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="ffn_up_175b", choices=sorted(SHAPES) + ["quantize_only"])
+    ap.add_argument("--workload", default="ffn_up_175b", choices=sorted(SHAPES) + ["quantize_only", "cast_variants"])
     ap.add_argument("--mode", default="f16", choices=["f16", "mfma8"])
     ap.add_argument("--iters", type=int, default=3)
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy")
@@ -54,6 +55,20 @@ def main():
             for fmt in (fp8.FP8_E4M3, fp8.FP8_E5M2):
                 fp8.fp8_scale_from_amax(amax, fmt, scale)
                 fp8.fp8_quantize_dscale(x, fmt, scale, q)
+    elif args.workload == "cast_variants":
+        rows = cols = 1 << 14
+        x = torch.randn(rows * cols, device="cuda").to(torch.bfloat16).view(rows, cols)
+        q = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+        qt = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
+        amax = torch.zeros(1, device="cuda")
+        scale = torch.ones(1, device="cuda")
+        row_amax, row_scale = torch.zeros(rows, device="cuda"), torch.ones(rows, device="cuda")
+        for _ in range(args.iters):
+            fp8.fp8_quantize_amax(x.view(-1), fp8.FP8_E4M3, scale, q.view(-1), amax)
+            fp8.fp8_quantize_sr(x.view(-1), fp8.FP8_E4M3, scale, 1234, q.view(-1))
+            fp8.fp8_quantize_transpose(x, fp8.FP8_E4M3, scale, q, qt)
+            fp8.fp8_amax_rows(x, row_amax)
+            fp8.fp8_quantize_rows(x, fp8.FP8_E4M3, row_scale, q)
     else:
         M, N, K, fmtA, out = SHAPES[args.workload]
         if args.mnk:
