@@ -43,6 +43,7 @@ struct GemmArgs {
     int fmtA, fmtB;
     bool transA, transB;          // A stored K x M / B stored N x K
     int acc;                      // ACC_*
+    int tile_n;                   // width of the tiled kernel's tile: 256, or 128 (chosen by the dispatcher)
     EpilogueArgs ep;
     hipStream_t stream;
 };

@@ -12,7 +12,8 @@
 //
 //   - one workgroup of 4 waves per 256 x 256 output tile, each wave owns 128 x 128 of it as
 //     4 x 4 blocks of v_mfma_f32_32x32x64_f8f6f4 (K = 64 per instruction, operand formats
-//     selected per operand, so the E5M2 x E4M3 mix costs nothing extra);
+//     selected per operand, so the E5M2 x E4M3 mix costs nothing extra); a 256 x 128 variant
+//     (each wave 128 x 64) serves problems with too few wide tiles to fill the chip;
 //   - K is walked in stages of 64.  An operand that is contiguous along M / N in memory (B stored
 //     K x N, A stored K x M) comes as one 64 x 256 slab (16 KB) per stage in a ring of four; an
 //     operand that is contiguous along K (A stored M x K, B stored N x K) as one 256 x 128 slab
@@ -60,14 +61,16 @@ typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 // ------------------------------------------------------------------------------------------
 // Fast kernel
 // ------------------------------------------------------------------------------------------
-constexpr int BM = 256, BN = 256, BK = 64;
-// An operand tile is staged in one of two ways, depending on how the operand lies in memory:
-//   K-contiguous  (A row-major M x K; B given as N x K): one 256 x 128 slab (32 KB) per PAIR of
-//                 stages, fragments by 16-byte LDS reads;
-//   MN-contiguous (B row-major K x N; A given as K x M): one 64 x 256 slab (16 KB) per stage,
-//                 ring of four, fragments by the transposing 8-byte LDS read.
-constexpr int KC_SLAB = 256 * 128;           // 32 KB
-constexpr int MC_SLAB = 64 * 256;            // 16 KB
+constexpr int BM = 256, BK = 64;
+// The tile is 256 rows of op(A) by 64 NB columns of op(B), NB = 4 or 2 (template parameter): two
+// waves side by side along N, each NB blocks of 32 columns wide.  The narrow tile is for problems
+// whose 256 x 256 tiles would leave much of the last round of workgroups empty.
+// An operand tile of EXT rows / columns (256, or 128 for the narrow B) is staged in one of two ways,
+// depending on how the operand lies in memory:
+//   K-contiguous  (A row-major M x K; B given as N x K): one EXT x 128 slab per PAIR of stages,
+//                 fragments by 16-byte LDS reads;
+//   MN-contiguous (B row-major K x N; A given as K x M): one 64 x EXT slab per stage, ring of
+//                 four, fragments by the transposing 8-byte LDS read.
 constexpr int MC_SLOTS = 4;
 constexpr int FAST_LDS = 160 * 1024;         // all of the LDS of a compute unit
 constexpr int FAST_THREADS = 256;
@@ -75,7 +78,7 @@ constexpr int GROUP_M = 8;                   // tile rows per band of the tile o
 constexpr int NUM_XCD = 8;
 
 // Chunk swizzles.  K-contiguous slab: rows of 128 B = 8 chunks; MN-contiguous slab: rows of
-// 256 B = 16 chunks.  Measured on gfx950: with these a 16-byte fragment read costs 5 clocks per
+// EXT bytes = 16 or 8 chunks (the swizzle value is reduced to the chunk count).  Measured on gfx950: with these a 16-byte fragment read costs 5 clocks per
 // wave instruction (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read
 // 7.3 clocks.
 __device__ __forceinline__ int swz_kc(int row) { return (row >> 1) & 7; }
@@ -130,52 +133,56 @@ __device__ __forceinline__ v8h widen8(int lo, int hi)
     return (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
 }
 
-// One operand of the tile as the kernel sees it.  r = row of A / column of B inside the 256-wide
+// One operand of the tile as the kernel sees it.  r = row of A / column of B inside the EXT-wide
 // tile, k = position along K:
 //   KC: element (r, k) at tile + r * ld + k;   MC: element (r, k) at tile + k * ld + r.
 struct Operand {
     const uint8_t* tile;     // first byte of the tile's rows (KC) or columns (MC)
     unsigned ld;             // leading dimension in bytes
-    unsigned off[8];         // per-lane offsets of this wave's direct loads (8 used by KC, 4 by MC)
+    unsigned off[8];         // per-lane offsets of this wave's direct loads (EXT/32 used by KC, EXT/64 by MC)
     unsigned region;         // LDS byte offset of the operand's ring
     unsigned rd;             // per-lane LDS offset of its first fragment read (region included)
 };
 
-template <bool KC>
+template <bool KC, int EXT>
 __device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, unsigned ld, int r0, int valid,
                                               unsigned region, int w, int l, int wsel)
 {
-    // `valid` (1..256) rows / columns of the tile exist; loads of the others are redirected to an
+    // `valid` (1..EXT) rows / columns of the tile exist; loads of the others are redirected to an
     // existing one (their products only reach outputs that are never stored).
     op.ld = ld;
     op.region = region;
     const int h = l >> 5;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) op.off[t] = 0;
     if (KC) {
+        constexpr int LW = EXT / 32;                  // loads per wave per slab; each fills 8 rows (1 KB)
         op.tile = base + (size_t)r0 * ld;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {                 // instruction ia fills rows 8 ia .. 8 ia + 7 (1 KB)
-            const int row = (w * 8 + t) * 8 + (l >> 3);
+        for (int t = 0; t < LW; ++t) {
+            const int row = (w * LW + t) * 8 + (l >> 3);
             op.off[t] = (unsigned)min(row, valid - 1) * ld + (((l & 7) ^ swz_kc(row)) * 16);
         }
         // lane = (r = l % 32, h = l / 32) reads K bytes 32h .. 32h+31 of row r of its stage:
         // chunks 4 par + 2h and + 1 of the 128-byte row (par = stage parity)
-        const int row = wsel * 128 + (l & 31);
+        const int row = wsel * (EXT / 2) + (l & 31);
         op.rd = region + row * 128 + (((2 * h) ^ swz_kc(row)) * 16);
     } else {
+        constexpr int CH = EXT / 16;                  // 16-byte chunks per K-row
+        constexpr int KR = 1024 / EXT;                // K-rows filled by one load instruction (1 KB)
+        constexpr int LW = 64 / KR / 4;               // loads per wave per slab
         op.tile = base + r0;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {                 // instruction ib fills K-rows 4 ib .. 4 ib + 3 (1 KB)
-            const int krow = (w * 4 + t) * 4 + (l >> 4);
-            const int chunk = (l & 15) ^ swz_mc(krow);           // 16 columns; `valid` is a multiple of 16 here
+        for (int t = 0; t < LW; ++t) {
+            const int krow = (w * LW + t) * KR + l / CH;
+            const int chunk = (l % CH) ^ (swz_mc(krow) & (CH - 1));   // 16 columns; `valid` is a multiple of 16 here
             op.off[t] = (unsigned)krow * ld + min(chunk, (valid - 1) >> 4) * 16;
         }
-#pragma unroll
-        for (int t = 4; t < 8; ++t) op.off[t] = 0;
         // lane = (r = l % 32, h): column r, K bytes 32h .. 32h+31, gathered by four transposing
         // reads of 8 K-rows x 16 columns per 16-lane group; lanes 2q and 2q+1 address K-row q
         const int t16 = l & 15, gq = (l >> 4) & 1;
         const int krow = 32 * h + (t16 >> 1);
-        op.rd = region + krow * 256 + (((wsel * 8 + gq) ^ swz_mc(krow)) * 16) + (t16 & 1) * 8;
+        op.rd = region + krow * EXT + (((wsel * (CH / 2) + gq) ^ (swz_mc(krow) & (CH - 1))) * 16) + (t16 & 1) * 8;
     }
 }
 
@@ -188,45 +195,46 @@ __device__ __forceinline__ void direct_load(const uint8_t* base, unsigned off, u
                  :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
 }
 
-// Part j (0..7) of the fragment reads of stage kt: 16 bytes per lane of block j/2 (half j%2 of
-// the lane's 32 bytes) of one operand, as one 16-byte read (KC) or two transposing reads (MC).
-template <bool KC>
-__device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op, int kt, int kc_slot, int j,
-                                          v8i (&f)[4])
+// Read-part rp of the fragment reads of stage kt for one operand: 16 bytes per lane of block rp/2
+// (half rp%2 of the lane's 32 bytes), as one 16-byte read (KC) or two transposing reads (MC).
+template <bool KC, int EXT>
+__device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op, int kt, int kc_slot, int rp,
+                                          v8i* f)
 {
-    const int blk = j >> 1, half = j & 1;
+    const int blk = rp >> 1, half = rp & 1;
     if (KC) {
-        const unsigned addr = (op.rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + kc_slot * KC_SLAB + blk * 32 * 128;
+        const unsigned addr = (op.rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + kc_slot * (EXT * 128) + blk * 32 * 128;
         const v4i a = *LDS_PTR(v4i, smem + addr);
         f[blk][4 * half + 0] = a.x; f[blk][4 * half + 1] = a.y; f[blk][4 * half + 2] = a.z; f[blk][4 * half + 3] = a.w;
     } else {
-        const unsigned base = (unsigned)(kt & (MC_SLOTS - 1)) * MC_SLAB + (op.rd ^ (unsigned)(blk * 32));
+        const unsigned base = (unsigned)(kt & (MC_SLOTS - 1)) * (64 * EXT) + (op.rd ^ (unsigned)(blk * 32));
 #pragma unroll
         for (int s = 2 * half; s < 2 * half + 2; ++s) {
-            const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * 256));
+            const v2i p = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, smem + base + s * 8 * EXT));
             f[blk][2 * s] = p.x; f[blk][2 * s + 1] = p.y;
         }
     }
 }
 
-// The epilogue of one wave: its 128 x 128 sub-tile of accumulators -> memory.
+// The epilogue of one wave: its 128 x 32 NB sub-tile of accumulators -> memory.
 //   c = acc * ra(row) [* cb(column)]: the reciprocal scales, applied once per output;
 //   amax of |c| (if asked for); conversion to the output kind; whole-line stores.
 // A lane holds 4 consecutive N of one C row per accumulator quad; written straight out that would
-// be small pieces scattered over 32 rows per instruction.  Instead the wave turns each 32 x 128
+// be small pieces scattered over 32 rows per instruction.  Instead the wave turns each 32 x 32 NB
 // block around through its own piece of the (now idle) LDS and stores it with 16 bytes per lane
-// along N: whole 128-byte lines.  fp32 and bf16 outputs are converted before the turn; FP8 outputs
+// along N: whole 128-byte lines (64-byte halves for FP8 outputs of the narrow tile).  fp32 and bf16 outputs are converted before the turn; FP8 outputs
 // pass through LDS as fp32 (already multiplied by the output scale) and are rounded after it,
 // 16 consecutive columns per lane, by the same routine as in the cast kernel.
-template <int OUT, bool BVEC>
-__device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int M, int N,
+template <int OUT, bool BVEC, int NB>
+__device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int M, int N,
                                          int wave_m0, int wave_n0, int w, int l)
 {
     constexpr bool FP8OUT = OUT == OUT_E4M3 || OUT == OUT_E5M2;
     constexpr int ESZ = OUT == OUT_F32 ? 4 : OUT == OUT_BF16 ? 2 : 1;     // bytes per output in memory
     constexpr int LSZ = FP8OUT ? 4 : ESZ;                                 // bytes per output in LDS
-    constexpr int ROWB = 128 * LSZ + 16;                                  // padded LDS row of the wave's block
-    constexpr int ROWS_PER_ST = 1024 / (128 * ESZ);                       // C rows covered by one store instruction
+    constexpr int WN = 32 * NB;                                           // columns of the wave's sub-tile
+    constexpr int ROWB = WN * LSZ + 16;                                   // padded LDS row of the wave's block
+    constexpr int ROWS_PER_ST = 1024 / (WN * ESZ);                        // C rows covered by one store instruction
     const int h = l >> 5;
 
     // reciprocal scales: per row in ra (with the per-tensor sB folded in), per column in cb
@@ -239,10 +247,10 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
             ra[mb] = (float)(1.0 / ((double)a * b));
         }
     }
-    v4f cb[BVEC ? 4 : 1][BVEC ? 4 : 1];
+    v4f cb[BVEC ? NB : 1][BVEC ? 4 : 1];
     if (BVEC) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const v4f s = *(const v4f*)(ep.sB_dev + min(wave_n0 + nb * 32 + 8 * q + 4 * h, N - 4));
@@ -258,7 +266,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 float c0 = acc[nb][mb][4 * q + 0] * ra[mb], c1 = acc[nb][mb][4 * q + 1] * ra[mb];
@@ -309,19 +317,23 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[4][4], uint8_t* smem, const
     if (ep.amax_out) wave_amax_commit(amax_bits, ep.amax_out);
 }
 
-// A_KC / B_KC: how the operand lies in memory (see Operand).  LDS: an MN-contiguous operand takes
-// 64 KB (ring of four stages); a K-contiguous one 96 KB (ring of three stage pairs), or 64 KB
-// (ring of two pairs) for B when both operands are K-contiguous.
-template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC>
+// A_KC / B_KC: how the operand lies in memory (see Operand); NB: width of the tile in blocks of 32
+// columns per wave.  LDS: an MN-contiguous operand takes a ring of four stage slabs; a K-contiguous
+// one a ring of three stage-pair slabs, or of two for B when both operands are K-contiguous.
+template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
     int M, int N, int K, EpilogueArgs ep, int group_m)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    constexpr int BN = 64 * NB;                             // tile width
+    constexpr int P = 2 * NB;                               // parts a stage is cut into
     constexpr int A_RING = 3;                               // stage pairs in A's ring (if A_KC)
     constexpr int B_RING = A_KC ? 2 : 3;                    // stage pairs in B's ring (if B_KC)
     constexpr bool HAS_MC = !A_KC || !B_KC;
-    // LDS map: the 64 KB operand (MN-contiguous, or B when both are K-contiguous) first.
+    // direct loads per wave: per pair slab (K-contiguous) / per stage slab (MN-contiguous)
+    constexpr int A_KC_LOADS = 8, A_MC_LOADS = 4, B_KC_LOADS = 2 * NB, B_MC_LOADS = NB;
+    // LDS map: the operand with the smaller ring (MN-contiguous, or B when both are K-contiguous) first.
     constexpr unsigned A_REGION = A_KC ? 65536u : 0u;
     constexpr unsigned B_REGION = A_KC ? 0u : 65536u;
 
@@ -331,103 +343,135 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const TileMap tile = map_tile(blockIdx.x, (M + BM - 1) / BM, (N + BN - 1) / BN, group_m);
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
     const int KT = K / BK;
-    const int h = l >> 5;
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
 
     Operand opA, opB;
-    operand_setup<A_KC>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, min(BM, M - m0), A_REGION, w, l, wm);
-    operand_setup<B_KC>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, min(BN, N - n0), B_REGION, w, l, wn);
+    operand_setup<A_KC, BM>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, min(BM, M - m0), A_REGION, w, l, wm);
+    operand_setup<B_KC, BN>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, min(BN, N - n0), B_REGION, w, l, wn);
 
     // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
     // the steps -5 .. -1).  Step s issues, in this order:
     //   for a K-contiguous operand, if s is odd: the slab of stage pair (s+1)/2 + ring - 1 into
-    //                the slot that stage s frees (8 loads per wave, two in each of parts 0..3);
-    //   for an MN-contiguous operand the slab of stage s + 4 (4 loads per wave, parts 4..7).
+    //                the slot that stage s frees, spread over the first half of the parts;
+    //   for an MN-contiguous operand the slab of stage s + 4, spread over the second half.
     // (Splitting the pair slab over the odd and the even step, for the same number of loads in
     // every step, measured 2 % slower in the FP8 mode.)
     // If both operands are K-contiguous, B's ring holds two pairs only and its loads have less
     // than two steps to arrive; they must not queue behind A's.  Then the odd steps issue B alone
-    // and the even step s issues A's pair s/2 + 2, one load per part, into the slot of the pair
+    // and the even step s issues A's pair s/2 + 2, spread over all parts, into the slot of the pair
     // that ended a step ago (three steps of lead are left).
     auto kc_pair_of = [](int s, int ring) { return (s + 1) / 2 + ring - 1; };     // s odd (may be negative)
     auto pair_valid = [&](int p) { return p >= 0 && 2 * p < KT; };
     auto stage_valid = [&](int st) { return st >= 0 && st < KT; };
     auto count_step = [&](int s) {
         int n = 0;
-        if (A_KC && B_KC) return ((s & 1) ? pair_valid(kc_pair_of(s, B_RING)) : pair_valid(s / 2 + A_RING - 1)) ? 8 : 0;
-        if (A_KC && (s & 1) && pair_valid(kc_pair_of(s, A_RING))) n += 8;
-        if (B_KC && (s & 1) && pair_valid(kc_pair_of(s, B_RING))) n += 8;
-        if (!A_KC && stage_valid(s + 4)) n += 4;
-        if (!B_KC && stage_valid(s + 4)) n += 4;
+        if (A_KC && B_KC)
+            return (s & 1) ? (pair_valid(kc_pair_of(s, B_RING)) ? B_KC_LOADS : 0) : (pair_valid(s / 2 + A_RING - 1) ? A_KC_LOADS : 0);
+        if (A_KC && (s & 1) && pair_valid(kc_pair_of(s, A_RING))) n += A_KC_LOADS;
+        if (B_KC && (s & 1) && pair_valid(kc_pair_of(s, B_RING))) n += B_KC_LOADS;
+        if (!A_KC && stage_valid(s + 4)) n += A_MC_LOADS;
+        if (!B_KC && stage_valid(s + 4)) n += B_MC_LOADS;
         return n;
     };
     // Loads complete in order.  Stage t is complete once the last load issued for it is: that is
     // the last load of step t - 4 if an operand is MN-contiguous, else of the step that issued
     // B's pair t/2.  `upto` = last step whose loads have been issued when the wait is placed.
     // When a step waits for the stage after its own and every step of the window issues its full
-    // set, the count depends on the parity of the step alone and is a compile-time constant.
-    constexpr int KC_OPS = (A_KC ? 1 : 0) + (B_KC ? 1 : 0);
-    constexpr int STEADY_EVEN = HAS_MC ? 8 * KC_OPS + 8 * (2 - KC_OPS) : 16;   // the wait at the start of an even step
-    constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : 8;
+    // set, the count depends on the parity of the step alone and is a compile-time constant: with
+    // an MN-contiguous operand the window is one odd and one even step; with two K-contiguous
+    // operands it is A's even step and B's odd step before an even step, A's even step before an odd one.
+    constexpr int STEADY_EVEN = HAS_MC ? (A_KC ? A_KC_LOADS : 2 * A_MC_LOADS) + (B_KC ? B_KC_LOADS : 2 * B_MC_LOADS)
+                                       : A_KC_LOADS + B_KC_LOADS;
+    constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : A_KC_LOADS;
     auto wait_stage = [&](int t, int upto) {
         const int s_need = HAS_MC ? t - 4 : 2 * (t / 2) - 2 * B_RING + 1;
         int allowed = 0;
         for (int s = s_need + 1; s <= upto; ++s) allowed += count_step(s);
-        switch (allowed) {
-            case 0: wait_vmcnt<0>(); break;   case 4: wait_vmcnt<4>(); break;
-            case 8: wait_vmcnt<8>(); break;   case 12: wait_vmcnt<12>(); break;
-            case 16: wait_vmcnt<16>(); break; case 20: wait_vmcnt<20>(); break;
-            case 24: wait_vmcnt<24>(); break; case 28: wait_vmcnt<28>(); break;
-            case 32: wait_vmcnt<32>(); break; case 36: wait_vmcnt<36>(); break;
+        switch (allowed >> 1) {                   // every count is even
+            case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<2>(); break;   case 2: wait_vmcnt<4>(); break;
+            case 3: wait_vmcnt<6>(); break;   case 4: wait_vmcnt<8>(); break;   case 5: wait_vmcnt<10>(); break;
+            case 6: wait_vmcnt<12>(); break;  case 7: wait_vmcnt<14>(); break;  case 8: wait_vmcnt<16>(); break;
+            case 9: wait_vmcnt<18>(); break;  case 10: wait_vmcnt<20>(); break; case 11: wait_vmcnt<22>(); break;
+            case 12: wait_vmcnt<24>(); break; case 13: wait_vmcnt<26>(); break; case 14: wait_vmcnt<28>(); break;
+            case 15: wait_vmcnt<30>(); break; case 16: wait_vmcnt<32>(); break; case 17: wait_vmcnt<34>(); break;
+            case 18: wait_vmcnt<36>(); break; case 19: wait_vmcnt<38>(); break; case 20: wait_vmcnt<40>(); break;
             default: wait_vmcnt<0>(); break;
         }
     };
-    auto issue_kc = [&](const Operand& op, int pair, int slot, int t) {
+    // load t of this wave for a pair slab (loads-per-wave lw: the slab takes 4 lw KB) / a stage slab
+    auto issue_kc = [&](const Operand& op, int lw, int pair, int slot, int t) {
         direct_load(op.tile + (size_t)pair * 2 * BK, op.off[t],
-                    lds0 + op.region + slot * KC_SLAB + w * 8192 + t * 1024);
+                    lds0 + op.region + slot * (lw * 4096) + w * (lw * 1024) + t * 1024);
     };
-    auto issue_mc = [&](const Operand& op, int st, int t) {
+    auto issue_mc = [&](const Operand& op, int lw, int st, int t) {
         direct_load(op.tile + (size_t)st * BK * op.ld, op.off[t],
-                    lds0 + op.region + (st & (MC_SLOTS - 1)) * MC_SLAB + w * 4096 + t * 1024);
+                    lds0 + op.region + (st & (MC_SLOTS - 1)) * (lw * 4096) + w * (lw * 1024) + t * 1024);
     };
     // the loads of step s that fall into part j; sa, sb = ring slots the K-contiguous slabs of
     // this step go to (the slots of the pair that stage s ends; for A in an even step when both
     // operands are K-contiguous: of the pair before the one stage s begins)
     auto issue_part = [&](int s, bool odd, int j, int sa, int sb) {
+        constexpr int H = P / 2;
         if (A_KC && B_KC) {
             if (odd) {
                 const int p = kc_pair_of(s, B_RING);
-                if (j < 4 && pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); }
+                if (j < H && pair_valid(p)) {
+#pragma unroll
+                    for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
+                }
             } else {
                 const int p = s / 2 + A_RING - 1;
-                if (pair_valid(p)) issue_kc(opA, p, sa, j);
+                if (pair_valid(p)) {
+#pragma unroll
+                    for (int t = j * (A_KC_LOADS / P); t < (j + 1) * (A_KC_LOADS / P); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
+                }
             }
-        } else if (j < 4) {
+        } else if (j < H) {
             if (odd) {
-                if (A_KC) { const int p = kc_pair_of(s, A_RING); if (pair_valid(p)) { issue_kc(opA, p, sa, 2 * j); issue_kc(opA, p, sa, 2 * j + 1); } }
-                if (B_KC) { const int p = kc_pair_of(s, B_RING); if (pair_valid(p)) { issue_kc(opB, p, sb, 2 * j); issue_kc(opB, p, sb, 2 * j + 1); } }
+                if (A_KC) {
+                    const int p = kc_pair_of(s, A_RING);
+                    if (pair_valid(p)) {
+#pragma unroll
+                        for (int t = j * (A_KC_LOADS / H); t < (j + 1) * (A_KC_LOADS / H); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
+                    }
+                }
+                if (B_KC) {
+                    const int p = kc_pair_of(s, B_RING);
+                    if (pair_valid(p)) {
+#pragma unroll
+                        for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
+                    }
+                }
             }
         } else if (stage_valid(s + 4)) {
-            if (!A_KC) issue_mc(opA, s + 4, j - 4);
-            if (!B_KC) issue_mc(opB, s + 4, j - 4);
+            const int jj = j - H;
+            if (!A_KC) {
+#pragma unroll
+                for (int t = jj * (A_MC_LOADS / H); t < (jj + 1) * (A_MC_LOADS / H); ++t) issue_mc(opA, A_MC_LOADS, s + 4, t);
+            }
+            if (!B_KC) {
+#pragma unroll
+                for (int t = jj * (B_MC_LOADS / H); t < (jj + 1) * (B_MC_LOADS / H); ++t) issue_mc(opB, B_MC_LOADS, s + 4, t);
+            }
         }
     };
 
-    v16f acc[4][4];
+    v16f acc[NB][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NB; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // The block products of a stage, in 8 parts.
-    //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64); part j = blocks 2j, 2j+1.
+    // The block products of a stage, in P parts.
+    //   ACC_FP8: one v_mfma_f32_32x32x64_f8f6f4 per block (K = 64); part j = B block j/2 against
+    //            the A blocks 2(j%2) and 2(j%2)+1.
     //   ACC_F16: the FP8 bytes are widened exactly to fp16 in registers and each block takes four
-    //            v_mfma_f32_32x32x16_f16 (K = 16, 8 of the lane's 32 bytes each); part j = K
-    //            sub-step j/2, B blocks 2(j%2) and 2(j%2)+1 against the four A blocks.
+    //            v_mfma_f32_32x32x16_f16 (K = 16, 8 of the lane's 32 bytes each); a part is two B
+    //            blocks of one K sub-step against the four A blocks.
     v8h a16[4];
-    auto compute_part = [&](int j, v8i (&af)[4], v8i (&bf)[4]) {
+    auto compute_part = [&](int j, v8i (&af)[4], v8i (&bf)[NB]) {
         if (ACC == ACC_FP8) {
             const int nb = j >> 1;
 #pragma unroll
@@ -435,13 +479,14 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                 acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                     bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
         } else {
-            const int s = j >> 1;
-            if ((j & 1) == 0) {
+            constexpr int PPS = NB / 2;               // parts per K sub-step
+            const int s = j / PPS, nb0 = 2 * (j % PPS);
+            if (j % PPS == 0) {
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb) a16[mb] = widen8<FMT_A>(af[mb][2 * s], af[mb][2 * s + 1]);
             }
 #pragma unroll
-            for (int nb = 2 * (j & 1); nb < 2 * (j & 1) + 2; ++nb) {
+            for (int nb = nb0; nb < nb0 + 2; ++nb) {
                 const v8h b16 = widen8<FMT_B>(bf[nb][2 * s], bf[nb][2 * s + 1]);
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)
@@ -449,7 +494,9 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             }
         }
     };
-    constexpr int READS_PER_PART = (A_KC ? 1 : 2) + (B_KC ? 1 : 2);
+    // fragment reads of the next stage that go out in one part: 8 / P read-parts of A, one of B
+    constexpr int A_RP = 8 / P;
+    constexpr int READS_PER_PART = A_RP * (A_KC ? 1 : 2) + (B_KC ? 1 : 2);
     auto sched_part = [&]() {
         if (ACC == ACC_FP8) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                        // MFMA
@@ -460,25 +507,27 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
-                if (i % 2 == 0 && i / 2 < READS_PER_PART) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                    // widening
+                if (NB == 4 ? (i % 2 == 0 && i / 2 < READS_PER_PART) : i < READS_PER_PART)
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, NB == 4 ? 2 : 3, 0);      // widening
             }
         }
     };
-    auto read_both = [&](int kt, int j, int sa, int sb, v8i (&af)[4], v8i (&bf)[4]) {
-        read_part<A_KC>(smem, opA, kt, sa, j, af);
-        read_part<B_KC>(smem, opB, kt, sb, j, bf);
+    auto read_both = [&](int kt, int j, int sa, int sb, v8i (&af)[4], v8i (&bf)[NB]) {
+#pragma unroll
+        for (int r = 0; r < A_RP; ++r) read_part<A_KC, BM>(smem, opA, kt, sa, j * A_RP + r, af);
+        read_part<B_KC, BN>(smem, opB, kt, sb, j, bf);
     };
 
     // One K stage kt (not the last).  The frags of stage kt are in (af, bf); their LDS reads were
-    // issued a stage ago.  First stage kt+1 is made visible.  Then, in 8 parts, the direct loads of
+    // issued a stage ago.  First stage kt+1 is made visible.  Then, in P parts, the direct loads of
     // step kt are issued (into the slots that stage kt, whose frags are in registers, has freed),
-    // an eighth of the MFMAs of stage kt runs, and the fragment reads of stage kt+1 go out into
+    // a share of the MFMAs of stage kt runs, and the fragment reads of stage kt+1 go out into
     // (af_n, bf_n).  Spreading matters: the four waves run in step, and a wave that issues its
     // loads in one burst waits for the address unit before it reaches its first MFMA.
     // (sa, sb) = ring slots of the pair of stage kt, (sa_n, sb_n) = of the pair of stage kt+1.
-    auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[4],
-                      v8i (&af_n)[4], v8i (&bf_n)[4]) {
+    auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[NB],
+                      v8i (&af_n)[4], v8i (&bf_n)[NB]) {
         // slot that A's loads of this step go to
         const int sa_ld = (A_KC && B_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
         const int sb_ld = sb;
@@ -490,7 +539,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < P; ++j) {
             issue_part(kt, odd, j, sa_ld, sb_ld);
             read_both(kt + 1, j, sa_n, sb_n, af_n, bf_n);
             compute_part(j, af, bf);
@@ -500,18 +549,18 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 
     // Prologue: steps -5 .. -1 of the same schedule, then stage 0 visible and its frags read.
     // KT is even and >= 2.
-    v8i af0[4], bf0[4], af1[4], bf1[4];
+    v8i af0[4], bf0[NB], af1[4], bf1[NB];
     for (int s = -5; s < 0; ++s) {
         // a pair issued by a step s < 0 has an index below the ring size: slot = pair
         const int sa = !A_KC ? 0 : (s & 1) ? (s + 1) / 2 + A_RING - 1 : s / 2 + A_RING - 1;
         const int sb = !B_KC ? 0 : (s & 1) ? (s + 1) / 2 + B_RING - 1 : s / 2 + B_RING - 1;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) issue_part(s, s & 1, j, sa, sb);
+        for (int j = 0; j < P; ++j) issue_part(s, s & 1, j, sa, sb);
     }
     wait_stage(0, -1);
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) read_both(0, j, 0, 0, af0, bf0);
+    for (int j = 0; j < P; ++j) read_both(0, j, 0, 0, af0, bf0);
     int sa = 0, sb = 0;                       // ring slots of the current stage pair
     for (int kt = 0; kt < KT - 2; kt += 2) {
         const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
@@ -522,25 +571,25 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     }
     k_step(KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) compute_part(j, af1, bf1);
+    for (int j = 0; j < P; ++j) compute_part(j, af1, bf1);
 
     // ---- epilogue (wave-uniform choice of the output kind and of the scale granularity) --------
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();                           // every wave is done with the operand slabs
-    const int wave_m0 = m0 + wm * 128, wave_n0 = n0 + wn * 128;
+    const int wave_m0 = m0 + wm * 128, wave_n0 = n0 + wn * (32 * NB);
     if (ep.b_per_col) {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, true>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
         }
     } else {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, false>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_BF16: epilogue<OUT_BF16, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            default: epilogue<OUT_E5M2, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
         }
     }
 }
@@ -555,17 +604,18 @@ int group_m_setting()
     return v > 0 ? v : GROUP_M;
 }
 
-template <int FA, int FB, int ACC, bool A_KC, bool B_KC>
+template <int FA, int FB, int ACC, bool A_KC, bool B_KC, int NB>
 int launch_fast(const GemmArgs& g)
 {
     static bool attr_set = false;
-    auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC>;
+    auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC, NB>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
         if (e != hipSuccess)
             return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
         attr_set = true;
     }
+    constexpr int BN = 64 * NB;
     const int tiles = (int)(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN));
     hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
                        (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting());
@@ -578,16 +628,22 @@ int launch_fast(const GemmArgs& g)
 #error "compile with -DFP8MM_LAYOUT=0..3 (2 * transA + transB) and -DFP8MM_ACC=0|1"
 #endif
 
-int FP8MM_TILED_NAME(FP8MM_LAYOUT, FP8MM_ACC)(const GemmArgs& g)
+template <int NB>
+static int launch_formats(const GemmArgs& g)
 {
     constexpr bool A_KC = (FP8MM_LAYOUT & 2) == 0;   // A row-major M x K is K-contiguous
     constexpr bool B_KC = (FP8MM_LAYOUT & 1) != 0;   // B stored N x K is K-contiguous
     constexpr int ACC = FP8MM_ACC;
     if (g.fmtA == FP8_E4M3)
-        return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC>(g)
-                                  : launch_fast<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC>(g);
-    return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E5M2, FP8_E4M3, ACC, A_KC, B_KC>(g)
-                              : launch_fast<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC>(g);
+        return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC, NB>(g)
+                                  : launch_fast<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC, NB>(g);
+    return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E5M2, FP8_E4M3, ACC, A_KC, B_KC, NB>(g)
+                              : launch_fast<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC, NB>(g);
+}
+
+int FP8MM_TILED_NAME(FP8MM_LAYOUT, FP8MM_ACC)(const GemmArgs& g)
+{
+    return g.tile_n == 128 ? launch_formats<2>(g) : launch_formats<4>(g);
 }
 
 }  // namespace fp8mm

@@ -363,9 +363,17 @@ def test_fp8_instruction_adder_window_is_what_the_header_says():
 
 # ---- operand storage orders (forward with out x in weights, dgrad, wgrad) ---------------------------
 
+@pytest.fixture(params=["256", "128"])
+def tile_n(request):
+    """Both tile widths of the tiled kernel, whatever the dispatcher would choose."""
+    os.environ["FP8MM_TILE_N"] = request.param
+    yield request.param
+    del os.environ["FP8MM_TILE_N"]
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-def test_operand_layouts(transA, transB, mode):
+def test_operand_layouts(transA, transB, mode, tile_n):
     """C = op(A) op(B) with either operand given transposed; tiled kernel shape and a ragged one."""
     rng = np.random.default_rng(50 + 2 * transA + transB)
     for (M, N, K) in [(512, 256, 640), (256, 512, 128), (100, 36, 72)]:
@@ -391,7 +399,7 @@ def test_operand_layouts(transA, transB, mode):
 
 
 @pytest.mark.parametrize("transA,transB", [(0, 1), (1, 0), (1, 1)])
-def test_operand_layouts_exact_integers_long_k(transA, transB):
+def test_operand_layouts_exact_integers_long_k(transA, transB, tile_n):
     """Exact-integer operands over many stages (odd and even stage pairs, ring wrap-around)."""
     M, N, K = 256, 256, 128 * 13
     rng = np.random.default_rng(9 + transA)

@@ -290,9 +290,18 @@ def test_config4_shape_fp8_output_full_size():
 RAGGED = [(300, 272, 256), (8, 16, 128), (1, 1008, 384), (1000, 48, 128), (513, 528, 256), (255, 256, 128)]
 
 
+@pytest.fixture(params=["256", "128"])
+def tile_n(request):
+    """Both tile widths of the tiled kernel, whatever the dispatcher would choose."""
+    import os
+    os.environ["FP8MM_TILE_N"] = request.param
+    yield request.param
+    del os.environ["FP8MM_TILE_N"]
+
+
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-def test_edge_tiles_of_the_tiled_kernel(transA, transB, mode):
+def test_edge_tiles_of_the_tiled_kernel(transA, transB, mode, tile_n):
     """M and N that are not multiples of the 256 x 256 tile (N a multiple of 16, M too if A is stored
     K x M) run in the tiled kernel with clipped edge tiles: every output kind, per-channel factors
     and the output amax must come out as for whole tiles, and nothing may be written past the edges."""
@@ -332,7 +341,7 @@ def test_edge_tiles_of_the_tiled_kernel(transA, transB, mode):
             check_amax(np.float32(amax.item()), c_ref, b, what)
 
 
-def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers():
+def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers(tile_n):
     import os
     rng = np.random.default_rng(9)
     for (M, N, K) in RAGGED:
