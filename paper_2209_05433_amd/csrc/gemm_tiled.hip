@@ -43,6 +43,8 @@
 // This file is compiled once per (storage orders, accumulation mode): -DFP8MM_LAYOUT, -DFP8MM_ACC.
 #include "gemm_common.hpp"
 
+#include <type_traits>
+
 namespace fp8mm {
 namespace {
 
@@ -195,13 +197,12 @@ __device__ __forceinline__ void direct_load(const uint8_t* base, unsigned off, u
                  :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
 }
 
-// Read-part rp of the fragment reads of stage kt for one operand: 16 bytes per lane of block rp/2
-// (half rp%2 of the lane's 32 bytes), as one 16-byte read (KC) or two transposing reads (MC).
+// One read-part of the fragment reads of stage kt for one operand: 16 bytes per lane of block blk
+// (half 0 or 1 of the lane's 32 bytes), as one 16-byte read (KC) or two transposing reads (MC).
 template <bool KC, int EXT>
-__device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op, int kt, int kc_slot, int rp,
+__device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op, int kt, int kc_slot, int blk, int half,
                                           v8i* f)
 {
-    const int blk = rp >> 1, half = rp & 1;
     if (KC) {
         const unsigned addr = (op.rd ^ (unsigned)((kt & 1) * 64 + half * 16)) + kc_slot * (EXT * 128) + blk * 32 * 128;
         const v4i a = *LDS_PTR(v4i, smem + addr);
@@ -410,18 +411,22 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // the loads of step s that fall into part j; sa, sb = ring slots the K-contiguous slabs of
     // this step go to (the slots of the pair that stage s ends; for A in an even step when both
     // operands are K-contiguous: of the pair before the one stage s begins)
-    auto issue_part = [&](int s, bool odd, int j, int sa, int sb) {
+    // FULL (compile-time): the caller guarantees that every load of the step exists, and no test is
+    // made.  The tests are branches, and a branch ends the region within which the compiler may
+    // move the conversions of one part under the MFMAs of the part before.
+    auto issue_part = [&](auto full_tag, int s, bool odd, int j, int sa, int sb) {
+        constexpr bool FULL = decltype(full_tag)::value;
         constexpr int H = P / 2;
         if (A_KC && B_KC) {
             if (odd) {
                 const int p = kc_pair_of(s, B_RING);
-                if (j < H && pair_valid(p)) {
+                if (j < H && (FULL || pair_valid(p))) {
 #pragma unroll
                     for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
                 }
             } else {
                 const int p = s / 2 + A_RING - 1;
-                if (pair_valid(p)) {
+                if (FULL || pair_valid(p)) {
 #pragma unroll
                     for (int t = j * (A_KC_LOADS / P); t < (j + 1) * (A_KC_LOADS / P); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
                 }
@@ -430,20 +435,20 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             if (odd) {
                 if (A_KC) {
                     const int p = kc_pair_of(s, A_RING);
-                    if (pair_valid(p)) {
+                    if (FULL || pair_valid(p)) {
 #pragma unroll
                         for (int t = j * (A_KC_LOADS / H); t < (j + 1) * (A_KC_LOADS / H); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
                     }
                 }
                 if (B_KC) {
                     const int p = kc_pair_of(s, B_RING);
-                    if (pair_valid(p)) {
+                    if (FULL || pair_valid(p)) {
 #pragma unroll
                         for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
                     }
                 }
             }
-        } else if (stage_valid(s + 4)) {
+        } else if (FULL || stage_valid(s + 4)) {
             const int jj = j - H;
             if (!A_KC) {
 #pragma unroll
@@ -469,32 +474,42 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     //            the A blocks 2(j%2) and 2(j%2)+1.
     //   ACC_F16: the FP8 bytes are widened exactly to fp16 in registers and each block takes four
     //            v_mfma_f32_32x32x16_f16 (K = 16, 8 of the lane's 32 bytes each); a part is two B
-    //            blocks of one K sub-step against the four A blocks.
-    v8h a16[4];
-    auto compute_part = [&](int j, v8i (&af)[4], v8i (&bf)[NB]) {
-        if (ACC == ACC_FP8) {
-            const int nb = j >> 1;
+    //            blocks of one K sub-step against the four A blocks.  The operands of a part are
+    //            converted during the part before it (for part 0: during the last part of the
+    //            stage before, from that stage's freshly read fragments): the conversions are then
+    //            independent of the MFMAs they are issued between and run in their shadow.  A
+    //            conversion costs 8 cycles of the vector ALU (measured), an MFMA 32 of the matrix
+    //            pipe: 24 conversions fit under the 8 MFMAs of a part, but only if none of those
+    //            MFMAs waits for one of them.
+    constexpr int PPS = NB / 2;                   // parts per K sub-step (ACC_F16)
+    v8h a16[2][4], b16[2][2];                     // [sub-step parity][A block], [part parity][B block of the part]
+    auto compute_fp8 = [&](int j, v8i (&af)[4], v8i (&bf)[NB]) {
+        const int nb = j >> 1;
 #pragma unroll
-            for (int mb = 2 * (j & 1); mb < 2 * (j & 1) + 2; ++mb)
-                acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                    bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
-        } else {
-            constexpr int PPS = NB / 2;               // parts per K sub-step
-            const int s = j / PPS, nb0 = 2 * (j % PPS);
-            if (j % PPS == 0) {
+        for (int mb = 2 * (j & 1); mb < 2 * (j & 1) + 2; ++mb)
+            acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                bf[nb], af[mb], acc[nb][mb], FMT_B, FMT_A, 0, 0, 0, 0);
+    };
+    // operands of part j of a stage whose fragments are (af, bf)
+    auto convert_f16 = [&](int j, v8i (&af)[4], v8i (&bf)[NB]) {
+        const int s = j / PPS, nb0 = 2 * (j % PPS);
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb) a16[mb] = widen8<FMT_A>(af[mb][2 * s], af[mb][2 * s + 1]);
-            }
+        for (int i = 0; i < 2; ++i) b16[j & 1][i] = widen8<FMT_B>(bf[nb0 + i][2 * s], bf[nb0 + i][2 * s + 1]);
+        if (j % PPS == 0) {
 #pragma unroll
-            for (int nb = nb0; nb < nb0 + 2; ++nb) {
-                const v8h b16 = widen8<FMT_B>(bf[nb][2 * s], bf[nb][2 * s + 1]);
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b16, a16[mb], acc[nb][mb], 0, 0, 0);
-            }
+            for (int mb = 0; mb < 4; ++mb) a16[s & 1][mb] = widen8<FMT_A>(af[mb][2 * s], af[mb][2 * s + 1]);
         }
     };
-    // fragment reads of the next stage that go out in one part: 8 / P read-parts of A, one of B
+    auto compute_f16 = [&](int j) {
+        const int s = j / PPS, nb0 = 2 * (j % PPS);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+                acc[nb0 + i][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b16[j & 1][i], a16[s & 1][mb], acc[nb0 + i][mb], 0, 0, 0);
+    };
+    // fragment reads of the next stage that go out in one part: 8 / P read-parts of A, one of B;
+    // the first halves of all blocks first (the first conversions of the next stage need them)
     constexpr int A_RP = 8 / P;
     constexpr int READS_PER_PART = A_RP * (A_KC ? 1 : 2) + (B_KC ? 1 : 2);
     auto sched_part = [&]() {
@@ -507,16 +522,19 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // MFMA
-                if (NB == 4 ? (i % 2 == 0 && i / 2 < READS_PER_PART) : i < READS_PER_PART)
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, NB == 4 ? 2 : 3, 0);      // widening
+                if (i < READS_PER_PART) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);                    // widening for the next part
             }
+            __builtin_amdgcn_sched_barrier(0);        // nothing drifts into another part (register pressure)
         }
     };
     auto read_both = [&](int kt, int j, int sa, int sb, v8i (&af)[4], v8i (&bf)[NB]) {
 #pragma unroll
-        for (int r = 0; r < A_RP; ++r) read_part<A_KC, BM>(smem, opA, kt, sa, j * A_RP + r, af);
-        read_part<B_KC, BN>(smem, opB, kt, sb, j, bf);
+        for (int r = 0; r < A_RP; ++r) {
+            const int ra = j * A_RP + r;
+            read_part<A_KC, BM>(smem, opA, kt, sa, ra & 3, ra >> 2, af);
+        }
+        read_part<B_KC, BN>(smem, opB, kt, sb, j % NB, j / NB, bf);
     };
 
     // One K stage kt (not the last).  The frags of stage kt are in (af, bf); their LDS reads were
@@ -526,12 +544,13 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // (af_n, bf_n).  Spreading matters: the four waves run in step, and a wave that issues its
     // loads in one burst waits for the address unit before it reaches its first MFMA.
     // (sa, sb) = ring slots of the pair of stage kt, (sa_n, sb_n) = of the pair of stage kt+1.
-    auto k_step = [&](int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[NB],
+    auto k_step = [&](auto full_tag, int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[NB],
                       v8i (&af_n)[4], v8i (&bf_n)[NB]) {
+        constexpr bool FULL = decltype(full_tag)::value;
         // slot that A's loads of this step go to
         const int sa_ld = (A_KC && B_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
         const int sb_ld = sb;
-        if (kt + 8 < KT) {
+        if (FULL || kt + 8 < KT) {
             if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
         } else {
             wait_stage(kt + 1, kt - 1);
@@ -540,9 +559,14 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
 #pragma unroll
         for (int j = 0; j < P; ++j) {
-            issue_part(kt, odd, j, sa_ld, sb_ld);
+            issue_part(full_tag, kt, odd, j, sa_ld, sb_ld);
             read_both(kt + 1, j, sa_n, sb_n, af_n, bf_n);
-            compute_part(j, af, bf);
+            if (ACC == ACC_FP8) {
+                compute_fp8(j, af, bf);
+            } else {
+                compute_f16(j);
+                if (j + 1 < P) convert_f16(j + 1, af, bf); else convert_f16(0, af_n, bf_n);
+            }
             sched_part();
         }
     };
@@ -550,28 +574,48 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // Prologue: steps -5 .. -1 of the same schedule, then stage 0 visible and its frags read.
     // KT is even and >= 2.
     v8i af0[4], bf0[NB], af1[4], bf1[NB];
+    const std::integral_constant<bool, true> full;
+    const std::integral_constant<bool, false> checked;
     for (int s = -5; s < 0; ++s) {
         // a pair issued by a step s < 0 has an index below the ring size: slot = pair
         const int sa = !A_KC ? 0 : (s & 1) ? (s + 1) / 2 + A_RING - 1 : s / 2 + A_RING - 1;
         const int sb = !B_KC ? 0 : (s & 1) ? (s + 1) / 2 + B_RING - 1 : s / 2 + B_RING - 1;
 #pragma unroll
-        for (int j = 0; j < P; ++j) issue_part(s, s & 1, j, sa, sb);
+        for (int j = 0; j < P; ++j) issue_part(checked, s, s & 1, j, sa, sb);
     }
     wait_stage(0, -1);
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int j = 0; j < P; ++j) read_both(0, j, 0, 0, af0, bf0);
+    if (ACC == ACC_F16) convert_f16(0, af0, bf0);
     int sa = 0, sb = 0;                       // ring slots of the current stage pair
-    for (int kt = 0; kt < KT - 2; kt += 2) {
+    int kt = 0;
+    // steps whose loads all exist (the last stage a step s touches is s + 6) and whose waits are
+    // the steady ones: no tests inside
+    for (; kt + 10 < KT; kt += 2) {
         const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
         const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
-        k_step(kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
-        k_step(kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
+        k_step(full, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
+        k_step(full, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
         sa = sa_n; sb = sb_n;
     }
-    k_step(KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
+    for (; kt < KT - 2; kt += 2) {
+        const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+        const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+        k_step(checked, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
+        k_step(checked, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
+        sa = sa_n; sb = sb_n;
+    }
+    k_step(checked, KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
 #pragma unroll
-    for (int j = 0; j < P; ++j) compute_part(j, af1, bf1);
+    for (int j = 0; j < P; ++j) {
+        if (ACC == ACC_FP8) {
+            compute_fp8(j, af1, bf1);
+        } else {
+            compute_f16(j);
+            if (j + 1 < P) convert_f16(j + 1, af1, bf1);
+        }
+    }
 
     // ---- epilogue (wave-uniform choice of the output kind and of the scale granularity) --------
     __builtin_amdgcn_s_waitcnt(0xC07F);
