@@ -14,7 +14,10 @@
  * Conventions of this repository that the paper does not fix ("parity
  * unpinned", they occur in none of the benchmark workloads):
  *   - the E5M2 NaN payload emitted by encode (Table 1 allows three),
- *   - the scale returned for a zero / non-finite amax.
+ *   - the scale returned for a zero / non-finite amax (also from a history of maxima),
+ *   - the stochastic-rounding rule fp8o_encode_sr (Section 2 names the mode without defining
+ *     it; the rule's properties and its generator's published vectors are pinned, the choice
+ *     of the rule itself is this repository's).
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC (no -ffast-math: IEEE semantics are
  * part of the definition).  OpenMP only spreads independent outer-loop

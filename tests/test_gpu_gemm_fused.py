@@ -357,3 +357,57 @@ def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers(tile_n):
         finally:
             del os.environ["FP8MM_GEMM"]
         assert np.array_equal(out_to_f64(G), S / 2.0)
+
+
+def test_wgrad_of_the_ffn_up_layer_full_size():
+    """dW[49152 x 12288] = dY^T X with dY [8192 x 49152] (bf16 -> E5M2) and X [8192 x 12288] (bf16 ->
+    E4M3), K = 8192 tokens: the weight-gradient GEMM of the FFN-up layer at full size.  dY is cast
+    once, into both storage orders; the product is formed from the plain bytes with transA = 1 and
+    from the transposed bytes with transA = 0, with per-tensor factors and with per-row (per output
+    channel) factors folded in; sampled outputs against the oracle."""
+    X_bits, _ = synth.config4()                       # activations of config 4: 8192 x 12288
+    dY_bits, _ = synth.config5()                      # activation gradients of config 5: 8192 x 49152, Laplace
+    T_, d_in = X_bits.shape
+    d_out = dY_bits.shape[1]
+    sX = oracle.scale_from_amax(oracle.amax(X_bits), E4M3)
+    sY = oracle.scale_from_amax(oracle.amax(dY_bits), E5M2)
+    dX, ddY = to_dev(X_bits), to_dev(dY_bits)
+    qX = torch.empty((T_, d_in), dtype=torch.uint8, device="cuda")
+    qY = torch.empty((T_, d_out), dtype=torch.uint8, device="cuda")
+    qYt = torch.empty((d_out, T_), dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize(dX, E4M3, float(sX), qX)
+    fp8.fp8_quantize_transpose(ddY, E5M2, dev_f32(sY), qY, qYt)
+    torch.cuda.synchronize()
+    del dX, ddY
+    Yq = oracle.quantize(dY_bits, E5M2, sY)
+    Xq = oracle.quantize(X_bits, E4M3, sX)
+    del X_bits, dY_bits
+    assert np.array_equal(qX.cpu().numpy(), Xq), "cast of X differs"
+    assert np.array_equal(qY.cpu().numpy(), Yq), "cast of dY differs"
+    assert torch.equal(qYt, qY.t()), "transposed cast of dY differs from the plain one"
+    Ytq = np.ascontiguousarray(Yq.T)                  # op(A) = dY^T as an M x K matrix for the oracle
+    del Yq
+    M, N, K = d_out, d_in, T_
+    rng = np.random.default_rng(6)
+    pi, pj = sample_points(rng, M, N, 2000)
+    S, T = oracle.gemm_points(Ytq, E5M2, Xq, E4M3, pi, pj)
+    ti, tj = torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda()
+    dW = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    row_factor = (0.5 + rng.random(M)).astype(np.float32)          # an extra factor per output channel
+    for mode in MODES:
+        c_ref, b = reference(S, T, sY, sX, mode)
+        bound = b + 0.5 * oracle.ulp(c_ref, oracle.F32)
+        for A_dev, transA in ((qY, 1), (qYt, 0)):
+            fp8.fp8_gemm_ex(A_dev, E5M2, transA, qX, E4M3, 0, dW, float(sY), float(sX), flags_of(mode))
+            torch.cuda.synchronize()
+            err = np.abs(dW[ti, tj].cpu().numpy().astype(np.float64) - c_ref)
+            assert np.all(err <= bound), "wgrad %s transA=%d: worst err/bound %.3g" % (mode, transA, np.max(err / bound))
+        sA_rows = (float(sY) * row_factor).astype(np.float32)
+        fp8.fp8_gemm_fused(qY, E5M2, 1, qX, E4M3, 0, dW, fp8.FP8_OUT_F32, dev_f32(sA_rows), dev_f32(sX), None, None,
+                           flags_of(mode))
+        torch.cuda.synchronize()
+        alpha = 1.0 / (sA_rows[pi].astype(np.float64) * float(sX))
+        c_ref2 = alpha * S
+        bound2 = REL[mode] * alpha * np.abs(T) + 0.5 * oracle.ulp(c_ref2, oracle.F32)
+        err = np.abs(dW[ti, tj].cpu().numpy().astype(np.float64) - c_ref2)
+        assert np.all(err <= bound2), "wgrad per-row factors %s: worst err/bound %.3g" % (mode, np.max(err / bound2))
