@@ -5,7 +5,11 @@
  * path of "FP8 Formats for Deep Learning" (arXiv 2209.05433):
  *
  *     amax  ->  scale  ->  cast to E4M3 / E5M2  ->  FP8 x FP8 GEMM (fp32 accumulate)
- *           ->  unscale epilogue to fp32 / bf16
+ *           ->  unscale epilogue to fp32 / bf16 / FP8
+ *
+ * and the variants of these steps that scaling recipes build on (transposed operands,
+ * per-channel factors, single-pass cast with a factor from past maxima, strict and
+ * stochastic conversion, dequantize).
  *
  * General rules for every entry point
  *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns
@@ -13,6 +17,11 @@
  *     besides the thread-local error string.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     work is enqueued on it; no entry point synchronises the stream or the device.
+ *     Every entry point may be recorded into a HIP graph (kernel launches only, no
+ *     memset nodes); the first GEMM call of each kind on a device raises that kernel's
+ *     LDS limit (hipFuncSetAttribute) and should be made outside a capture.
+ *   - Output cells described as "written, not accumulated" are cleared by a small
+ *     kernel on the same stream before they are raised with atomics.
  *   - The return value is an fp8_status_t.  On anything but FP8_OK nothing was
  *     launched and no output was written; fp8_last_error() describes the reason.
  *   - Tensors are dense and contiguous.  Matrices are row-major.

@@ -43,6 +43,7 @@
 // This file is compiled once per (storage orders, accumulation mode): -DFP8MM_LAYOUT, -DFP8MM_ACC.
 #include "gemm_common.hpp"
 
+#include <atomic>
 #include <type_traits>
 
 namespace fp8mm {
@@ -651,13 +652,17 @@ int group_m_setting()
 template <int FA, int FB, int ACC, bool A_KC, bool B_KC, int NB>
 int launch_fast(const GemmArgs& g)
 {
-    static bool attr_set = false;
+    // the kernel needs more dynamic LDS than the default limit: raised once per device
+    static std::atomic<unsigned long long> attr_set{0ull};
     auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC, NB>;
-    if (!attr_set) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FP8_ERR_DEVICE, "hipGetDevice failed");
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev >= 64 || !(attr_set.load(std::memory_order_relaxed) & bit)) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
         if (e != hipSuccess)
             return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
-        attr_set = true;
+        if (dev < 64) attr_set.fetch_or(bit, std::memory_order_relaxed);
     }
     constexpr int BN = 64 * NB;
     const int tiles = (int)(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN));
