@@ -100,3 +100,12 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros(8)
     with pytest.raises(ValueError):
         fp8.fp8_amax(x, torch.zeros(1))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more must end with a message, before anything is run."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
