@@ -181,9 +181,12 @@ def test_hardware_converter_equals_bit_path_on_all_fp32_patterns(fmt):
                 "0x%08x bits->0x%02x cvt->0x%02x" % (xb[i], a[i], b[i]) for i in bad))
 
 
-@pytest.mark.skipif(not os.environ.get("FP8MM_FULL_SWEEP"), reason="minutes of oracle time; set FP8MM_FULL_SWEEP=1")
+@pytest.mark.skipif(bool(os.environ.get("FP8MM_SKIP_FULL_SWEEP")), reason="FP8MM_SKIP_FULL_SWEEP is set")
 @pytest.mark.parametrize("fmt", FMTS)
 def test_full_fp32_sweep_against_oracle(fmt):
+    """Every one of the 2^32 fp32 bit patterns through the cast (integer rounding path; the converter
+    path is compared with it on the same 2^32 inputs above) against the oracle: about 20 s per format
+    with 16 host cores."""
     chunk = 1 << 26
     for c in range((1 << 32) // chunk):
         bits = (np.arange(chunk, dtype=np.uint64) + c * chunk).astype(np.uint32)
