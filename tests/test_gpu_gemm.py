@@ -438,3 +438,26 @@ def test_training_step_gemms_of_a_linear_layer():
     check(out_to_f64(dXo), S, T, 8.0, 4.0, fp8.FP8_BF16, "dgrad")
     S, T = oracle.gemm_rows(np.ascontiguousarray(dY.T), E5M2, X, E4M3)
     check(out_to_f64(dWo), S, T, 8.0, 2.0, fp8.FP8_F32, "wgrad")
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_every_stage_count_through_the_loop_regions(transA, transB, mode, tile_n):
+    """K from 2 to 40 stages of 64: the tiled kernel's K loop has a prologue, a steady-state region
+    without load tests, a tested tail and a peeled last step; every length must hand over between
+    them correctly (a wrong wait count or ring slot shows as a wrong sum).  Integer operands: exact."""
+    rng = np.random.default_rng(70 + 2 * transA + transB)
+    M, N = 256, 384
+    for K in [128 * i for i in (1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 16, 20)]:
+        ai = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        bi = rng.integers(-4, 5, (K, N)).astype(np.float32)
+        Aq, Bq = oracle.quantize(ai, E4M3, 1.0), oracle.quantize(bi, E4M3, 1.0)
+        want = ai.astype(np.float64) @ bi.astype(np.float64)          # integers: exact in fp64 and in fp32
+        dA = to_dev(np.ascontiguousarray(Aq.T) if transA else Aq)
+        dB = to_dev(np.ascontiguousarray(Bq.T) if transB else Bq)
+        C = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+        fp8.fp8_gemm_ex(dA, E4M3, transA, dB, E4M3, transB, C, 1.0, 1.0, fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0)
+        torch.cuda.synchronize()
+        got = out_to_f64(C)
+        assert np.array_equal(got, want), "K=%d layout %d%d %s tile %s: %d outputs differ" % (
+            K, transA, transB, mode, tile_n, np.count_nonzero(got != want))
