@@ -461,3 +461,36 @@ def test_every_stage_count_through_the_loop_regions(transA, transB, mode, tile_n
         got = out_to_f64(C)
         assert np.array_equal(got, want), "K=%d layout %d%d %s tile %s: %d outputs differ" % (
             K, transA, transB, mode, tile_n, np.count_nonzero(got != want))
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_repeated_launches_give_identical_bits_while_memory_is_busy(transA, transB, mode, tile_n):
+    """The tiled kernel tracks its direct global->LDS loads with hand-counted waits; a count that is
+    one too lenient would read a slab before it has landed, but only when the memory system is slow
+    enough.  25 launches of a 32-tile problem, each racing a large copy on a second stream, must all
+    give the bits of the first launch (which is checked against the oracle)."""
+    rng = np.random.default_rng(90 + 2 * transA + transB)
+    M, N, K = 1024, 2048, 4096
+    A, B = random_codes(rng, (M, K), E5M2, 0x6F), random_codes(rng, (K, N), E4M3)
+    dA = to_dev(np.ascontiguousarray(A.T) if transA else A)
+    dB = to_dev(np.ascontiguousarray(B.T) if transB else B)
+    flags = fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0
+    C0 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    fp8.fp8_gemm_ex(dA, E5M2, transA, dB, E4M3, transB, C0, 1.0, 1.0, flags)
+    torch.cuda.synchronize()
+    rows = np.array([0, 255, 256, 700, M - 1])
+    S, T = oracle.gemm_rows(A, E5M2, B, E4M3, rows)
+    check(out_to_f64(C0[torch.from_numpy(rows).cuda()]), S, T, np.float32(1.0), np.float32(1.0), fp8.FP8_F32,
+          "first launch", mode=mode)
+    src = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    side = torch.cuda.Stream()
+    C = torch.empty_like(C0)
+    for rep in range(25):
+        with torch.cuda.stream(side):
+            dst.copy_(src, non_blocking=True)
+        C.fill_(float(rep))
+        fp8.fp8_gemm_ex(dA, E5M2, transA, dB, E4M3, transB, C, 1.0, 1.0, flags)
+        torch.cuda.synchronize()
+        assert torch.equal(C, C0), "launch %d differs from the first in %d outputs" % (rep, int((C != C0).sum()))
