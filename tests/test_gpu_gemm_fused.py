@@ -359,6 +359,32 @@ def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers(tile_n):
         assert np.array_equal(out_to_f64(G), S / 2.0)
 
 
+def test_random_shapes_layouts_formats_and_modes_exact_on_integers(tile_n):
+    """A seeded sweep over shapes (any M, N a multiple of 16 or not, K a multiple of 128 or not: tiled
+    and generic kernel), storage orders, format pairs, modes and output kinds.  Operands are small
+    integers, so every sum is exact in fp32 in any order and the output must equal the oracle's."""
+    rng = np.random.default_rng(20260)
+    for case in range(24):
+        M = int(rng.integers(1, 700))
+        N = int(rng.integers(1, 45)) * 16 if case % 4 else int(rng.integers(1, 700))
+        K = int(rng.integers(1, 9)) * 128 if case % 5 else int(rng.integers(1, 600))
+        transA, transB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        fmtA, fmtB = (E4M3, E5M2)[int(rng.integers(0, 2))], (E4M3, E5M2)[int(rng.integers(0, 2))]
+        mode = MODES[case % len(MODES)]
+        out_kind = (fp8.FP8_OUT_F32, fp8.FP8_OUT_BF16)[int(rng.integers(0, 2))]
+        A = oracle.quantize(rng.integers(-4, 5, (M, K)).astype(np.float32), fmtA, 1.0)
+        B = oracle.quantize(rng.integers(-4, 5, (K, N)).astype(np.float32), fmtB, 1.0)
+        S, _ = oracle.gemm_rows(A, fmtA, B, fmtB)
+        D, amax = run_fused(A, fmtA, B, fmtB, out_kind, np.float32(2.0), np.float32(0.25), want_amax=True, mode=mode,
+                            transA=transA, transB=transB)
+        what = "case %d: %s layout %d%d formats %d%d %s out %d" % (case, (M, N, K), transA, transB, fmtA, fmtB, mode, out_kind)
+        want = S * 2.0                                      # 1 / (2 * 0.25)
+        if out_kind == fp8.FP8_OUT_BF16:
+            want = torch.from_numpy(want.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+        assert np.array_equal(out_to_f64(D), want), what
+        assert float(amax) == np.max(np.abs(S * 2.0)), what
+
+
 def test_wgrad_of_the_ffn_up_layer_full_size():
     """dW[49152 x 12288] = dY^T X with dY [8192 x 49152] (bf16 -> E5M2) and X [8192 x 12288] (bf16 ->
     E4M3), K = 8192 tokens: the weight-gradient GEMM of the FFN-up layer at full size.  dY is cast
