@@ -298,12 +298,12 @@ def test_config3_small_gpt_forward():
 
 def test_config4_ffn_up_full_size():
     A, B = synth.config4()
-    run_config(A, B, E4M3, E4M3, fp8.FP8_BF16, npts=4000, nrows=2, label="config 4")
+    run_config(A, B, E4M3, E4M3, fp8.FP8_BF16, npts=12400, nrows=2, label="config 4")      # a point in each of the 6144 tiles
 
 
 def test_config5_dgrad_full_size():
     A, B = synth.config5()
-    run_config(A, B, E5M2, E4M3, fp8.FP8_F32, npts=3000, nrows=2, label="config 5")
+    run_config(A, B, E5M2, E4M3, fp8.FP8_F32, npts=3200, nrows=2, label="config 5")        # a point in each of the 1536 tiles
 
 
 @pytest.mark.parametrize("fmt", [E4M3, E5M2])
