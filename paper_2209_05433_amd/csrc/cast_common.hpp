@@ -11,6 +11,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kAmaxBlocks = 256 * 4;      // read-only stream: 32 KB chunks dealt to this many workgroups measured best
 constexpr int kCastBlocks = 256 * 64;     // read+write stream: many short contiguous chunks measured best
+constexpr size_t kStreamingStoreBytes = (size_t)384 << 20;   // outputs from this size on are stored non-temporally
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -110,6 +111,77 @@ __device__ __forceinline__ void scale_item(const u32x4 (&v)[DT == FP8_BF16 ? 2 :
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int d = 0; d < 4; ++d) y[4 * j + d] = as_f32(v[j][d]) * s;
+    }
+}
+
+// How the vector kernels deal the work to lanes.  A lane that took 16 consecutive elements (32 or 64
+// bytes of input) itself would make every load instruction of its wave touch 64 lines for a half
+// or a quarter of their bytes.  Instead a lane takes single 16-byte vectors, kThreads vectors apart
+// (every load instruction of a wave then reads 1 KB of consecutive bytes), rounds 16 elements from
+// 2 (bf16) or 4 (fp32) such vectors at a time with the common routine, and stores the output bytes
+// of each vector as one piece of 8 (bf16) or 4 (fp32) bytes, again consecutive across the wave.
+// Measured on 2^28 elements against 16 consecutive elements per lane: bf16 6.4 -> 6.7 TB/s,
+// fp32 4.25 -> 6.2 TB/s.
+template <int DT> struct Piece;
+template <> struct Piece<FP8_BF16> {
+    typedef u32x2 type;
+    static __device__ __forceinline__ type of(const u32x4& o, int k) { return (u32x2){o[2 * k], o[2 * k + 1]}; }
+};
+template <> struct Piece<FP8_F32> {
+    typedef unsigned type;
+    static __device__ __forceinline__ type of(const u32x4& o, int k) { return o[k]; }
+};
+
+// One group: the loaded vectors in[k] = xv[v + k * kThreads], k < VPI -> the pieces
+// qp[v + k * kThreads]; only the first `count` pieces are stored.  AMAX: the running packed maximum of the
+// vectors is kept in `run` (vectors beyond `count` must be zeros).
+template <int DT, int FMT, int PATH, bool NTS, bool AMAX>
+__device__ __forceinline__ void cast_group(const u32x4* in, typename Piece<DT>::type* __restrict__ qp,
+                                           size_t v, int count, float s, unsigned& run)
+{
+    constexpr int VPI = DT == FP8_BF16 ? 2 : 4;
+    u32x4 item[VPI];
+#pragma unroll
+    for (int k = 0; k < VPI; ++k) {
+        item[k] = in[k];
+        if (AMAX) run = vec_mag_max<DT>(item[k], run);
+    }
+    float y[16];
+    scale_item<DT>(item, s, y);
+    const u32x4 o = encode16<FMT, PATH>(y);
+#pragma unroll
+    for (int k = 0; k < VPI; ++k) {
+        if (k < count) {
+            typename Piece<DT>::type* dst = &qp[v + (size_t)k * kThreads];
+            if (NTS) __builtin_nontemporal_store(Piece<DT>::of(o, k), dst); else *dst = Piece<DT>::of(o, k);
+        }
+    }
+}
+
+// A lane's walk over the vectors [vlo, vhi) of its workgroup: 8 vectors per step, all loads of a
+// step issued before the first conversion; then the remainder, group by group.
+template <int DT, int FMT, int PATH, bool NTS, bool AMAX>
+__device__ __forceinline__ void cast_run(const u32x4* __restrict__ xv, typename Piece<DT>::type* __restrict__ qp,
+                                         size_t vlo, size_t vhi, float s, unsigned& run)
+{
+    constexpr int VPI = DT == FP8_BF16 ? 2 : 4;
+    size_t v = vlo + threadIdx.x;
+    for (; v + 7 * kThreads < vhi; v += 8 * kThreads) {
+        u32x4 in[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) in[k] = __builtin_nontemporal_load(&xv[v + (size_t)k * kThreads]);
+#pragma unroll
+        for (int g = 0; g < 8 / VPI; ++g)
+            cast_group<DT, FMT, PATH, NTS, AMAX>(in + g * VPI, qp, v + (size_t)g * VPI * kThreads, VPI, s, run);
+    }
+    for (; v < vhi; v += VPI * kThreads) {
+        const size_t left = (vhi - v + kThreads - 1) / kThreads;        // vectors of this lane still there
+        const int count = left < (size_t)VPI ? (int)left : VPI;
+        u32x4 in[VPI];
+#pragma unroll
+        for (int k = 0; k < VPI; ++k)
+            in[k] = k < count ? __builtin_nontemporal_load(&xv[v + (size_t)k * kThreads]) : (u32x4){0u, 0u, 0u, 0u};
+        cast_group<DT, FMT, PATH, NTS, AMAX>(in, qp, v, count, s, run);
     }
 }
 

@@ -90,48 +90,25 @@ __global__ void scale_kernel(const float* __restrict__ amax, int fmt, float* __r
 // largest finite value (Section 2), NaN -> NaN, inf -> NaN (E4M3) or inf (E5M2).
 // ------------------------------------------------------------------------------------------
 
-// Vector path: x and q are 16-byte aligned.  A work item is 16 consecutive elements:
-// 2 (bf16) or 4 (fp32) non-temporal 16-byte loads and one ordinary 16-byte store per lane
-// (measured: non-temporal stores cost about 15 % of the write bandwidth, non-temporal loads gain).
-// Every workgroup owns one contiguous run of items and walks it U x 4 KB of output at a time;
-// all loads of a step are issued before the first conversion.
-template <int DT, int FMT, int PATH>
+// Vector path: x and q are 16-byte aligned.  Every workgroup owns one contiguous run of the
+// tensor (see cast_run / cast_group for how its lanes share the work).  Stores are ordinary up to
+// kStreamingStoreBytes of output, where they win 5 % because part of the output stays in the
+// 256 MB memory-side cache, and non-temporal beyond (5-8 % better there).
+template <int DT, int FMT, int PATH, bool NTS>
 __global__ __launch_bounds__(kThreads) void quantize_vec_kernel(const void* __restrict__ x, size_t n,
                                                                float scale,
                                                                const float* __restrict__ scale_dev,
                                                                uint8_t* __restrict__ q)
 {
-    constexpr int V = DT == FP8_BF16 ? 2 : 4;       // 16-byte vectors per item
-    constexpr int U = DT == FP8_BF16 ? 4 : 2;       // items per lane per step
+    constexpr int VPI = DT == FP8_BF16 ? 2 : 4;     // 16-byte vectors per 16 elements
     const float s = scale_dev ? *scale_dev : scale;
-    const u32x4* xv = (const u32x4*)x;
-    u32x4* qv = (u32x4*)q;
     const size_t nitem = n / 16;
     const size_t per = (nitem + gridDim.x - 1) / gridDim.x;
     const size_t lo = (size_t)blockIdx.x * per;
     const size_t hi = lo + per < nitem ? lo + per : nitem;
-    size_t i = lo + threadIdx.x;
-    for (; i + (U - 1) * kThreads < hi; i += U * kThreads) {
-        u32x4 v[U][V];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int j = 0; j < V; ++j) v[u][j] = __builtin_nontemporal_load(&xv[V * (i + u * kThreads) + j]);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float y[16];
-            scale_item<DT>(v[u], s, y);
-            qv[i + u * kThreads] = encode16<FMT, PATH>(y);
-        }
-    }
-    for (; i < hi; i += kThreads) {
-        u32x4 v[V];
-#pragma unroll
-        for (int j = 0; j < V; ++j) v[j] = __builtin_nontemporal_load(&xv[V * i + j]);
-        float y[16];
-        scale_item<DT>(v, s, y);
-        qv[i] = encode16<FMT, PATH>(y);
-    }
+    unsigned unused = 0;
+    if (lo < hi)
+        cast_run<DT, FMT, PATH, NTS, false>((const u32x4*)x, (typename Piece<DT>::type*)q, VPI * lo, VPI * hi, s, unused);
     if (blockIdx.x == 0) {                          // fewer than 16 tail elements
         const size_t t = nitem * 16 + threadIdx.x;
         if (t < n) q[t] = (uint8_t)encode_bits<FMT, PATH != kCastBitsStrict>(load_scalar<DT>(x, t) * s);
@@ -191,15 +168,19 @@ void launch_quantize_typed(const void* x, size_t n, float scale, const float* sc
 {
     if (aligned16(x) && aligned16(q)) {
         const int grid = grid_for((n / 16 + 3) / 4, kCastBlocks);
-        if (!saturate)
-            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastBitsStrict>), dim3(grid), dim3(kThreads), 0,
-                               stream, x, n, scale, scale_dev, q);
-        else if (cast_path() == kCastCvt)
-            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastCvt>), dim3(grid), dim3(kThreads), 0,
-                               stream, x, n, scale, scale_dev, q);
-        else
-            hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, kCastBits>), dim3(grid), dim3(kThreads), 0,
-                               stream, x, n, scale, scale_dev, q);
+        // An output that does not fit the memory-side cache (256 MB) is written past it.
+        const bool nts = n >= kStreamingStoreBytes;
+#define FP8MM_LAUNCH_QV(PATH)                                                                                      \
+    do {                                                                                                           \
+        if (nts) hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, PATH, true>), dim3(grid), dim3(kThreads), 0,     \
+                                    stream, x, n, scale, scale_dev, q);                                            \
+        else hipLaunchKernelGGL((quantize_vec_kernel<DT, FMT, PATH, false>), dim3(grid), dim3(kThreads), 0,        \
+                                stream, x, n, scale, scale_dev, q);                                                \
+    } while (0)
+        if (!saturate) FP8MM_LAUNCH_QV(kCastBitsStrict);
+        else if (cast_path() == kCastCvt) FP8MM_LAUNCH_QV(kCastCvt);
+        else FP8MM_LAUNCH_QV(kCastBits);
+#undef FP8MM_LAUNCH_QV
     } else if (saturate) {
         hipLaunchKernelGGL((quantize_scalar_kernel<DT, FMT, true>), dim3(grid_for(n, 2048)), dim3(kThreads), 0,
                            stream, x, n, scale, scale_dev, q);
@@ -226,34 +207,55 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint8_t* __r
                                                              const float* __restrict__ scale_dev,
                                                              void* __restrict__ out, bool vec)
 {
-    const float s = scale_dev ? *scale_dev : scale;
+    // The result depends on the byte alone: every workgroup first tabulates the 256 results (one
+    // decode, one IEEE division and, for bf16, one rounding per thread) in LDS, then streams.  With
+    // the arithmetic done per element the kernel was bound by the vector ALU at 3.2 TB/s.
+    // A lane takes the 8 (bf16 out) or 4 (fp32 out) bytes that make one 16-byte output vector, so that
+    // the load and the store instruction of a wave both cover consecutive bytes.
+    constexpr int EPV = OUT == FP8_F32 ? 4 : 8;
+    constexpr int U = 4;                            // vectors per lane in flight
+    static_assert(kThreads == 256, "one table entry per thread");
+    __shared__ unsigned table[256];                 // fp32 bits, or bf16 bits in the low half
+    {
+        const float y = decode_fp8<FMT>(threadIdx.x) / (scale_dev ? *scale_dev : scale);
+        table[threadIdx.x] = OUT == FP8_F32 ? as_u32(y) : to_bf16_bits(y);
+    }
+    __syncthreads();
     const size_t stride = (size_t)gridDim.x * kThreads;
-    const size_t nitem = vec ? n / 16 : 0;
-    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nitem; i += stride) {
-        const u32x4 v = __builtin_nontemporal_load(&((const u32x4*)q)[i]);
-        float y[16];
+    const size_t nvec = vec ? n / EPV : 0;
+    auto load_piece = [&](size_t i) {
+        if (OUT == FP8_F32) return (u32x2){__builtin_nontemporal_load(&((const unsigned*)q)[i]), 0u};
+        return __builtin_nontemporal_load(&((const u32x2*)q)[i]);
+    };
+    auto emit = [&](size_t i, u32x2 p) {
+        unsigned r[EPV];
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) y[4 * d + b] = decode_fp8<FMT>((v[d] >> (8 * b)) & 0xffu) / s;
-        if (OUT == FP8_F32) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                ((u32x4*)out)[4 * i + j] = (u32x4){as_u32(y[4 * j]), as_u32(y[4 * j + 1]), as_u32(y[4 * j + 2]), as_u32(y[4 * j + 3])};
+        for (int e = 0; e < EPV; ++e) r[e] = table[(p[e >> 2] >> (8 * (e & 3))) & 0xffu];
+        u32x4 o;
+        if constexpr (OUT == FP8_F32) {
+            o = (u32x4){r[0], r[1], r[2], r[3]};
         } else {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                u32x4 o;
-#pragma unroll
-                for (int d = 0; d < 4; ++d) o[d] = to_bf16_bits(y[8 * j + 2 * d]) | (to_bf16_bits(y[8 * j + 2 * d + 1]) << 16);
-                ((u32x4*)out)[2 * i + j] = o;
-            }
+            for (int d = 0; d < 4; ++d) o[d] = r[2 * d] | (r[2 * d + 1] << 16);
         }
+        ((u32x4*)out)[i] = o;
+    };
+    // every workgroup owns one contiguous run of the vectors
+    const size_t per = (nvec + gridDim.x - 1) / gridDim.x;
+    const size_t lo = (size_t)blockIdx.x * per;
+    const size_t hi = lo + per < nvec ? lo + per : nvec;
+    size_t i = lo + threadIdx.x;
+    for (; i + (U - 1) * kThreads < hi; i += U * kThreads) {
+        u32x2 p[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) p[u] = load_piece(i + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) emit(i + u * kThreads, p[u]);
     }
-    for (size_t t = nitem * 16 + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
-        const float y = decode_fp8<FMT>(q[t]) / s;
-        if (OUT == FP8_F32) ((float*)out)[t] = y;
-        else ((unsigned short*)out)[t] = (unsigned short)to_bf16_bits(y);
+    for (; i < hi; i += kThreads) emit(i, load_piece(i));
+    for (size_t t = nvec * EPV + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
+        if (OUT == FP8_F32) ((unsigned*)out)[t] = table[q[t]];
+        else ((unsigned short*)out)[t] = (unsigned short)table[q[t]];
     }
 }
 }  // namespace
@@ -277,7 +279,7 @@ int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const fl
 {
     if (n == 0) return FP8_OK;
     const bool vec = aligned16(q) && aligned16(out);
-    const int grid = grid_for(vec ? n / 16 + 1 : n, 256 * 16);
+    const int grid = grid_for(vec ? n / 16 + 1 : n, 256 * 256);     // many short runs measured best (write-heavy stream)
     if (fmt == FP8_E4M3) {
         if (out_dtype == FP8_F32) hipLaunchKernelGGL((dequantize_kernel<FP8_E4M3, FP8_F32>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
         else hipLaunchKernelGGL((dequantize_kernel<FP8_E4M3, FP8_BF16>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
