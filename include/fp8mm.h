@@ -195,9 +195,13 @@ int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dty
  * C_ref being the exact product of the decoded operands: the FP8 bytes are widened
  * exactly to fp16 in registers and multiplied by the fp16 matrix-core instructions,
  * whose accumulation is fp32-grade.  M, N or K equal to 0 is valid (K == 0 writes
- * zeros).  Any shape is accepted; shapes with K a multiple of 128, N a multiple of 16 (M
- * too where A is given as K x M, see fp8_gemm_ex) and 16-byte aligned pointers take the
- * tiled matrix-core kernel, the others a plain FMA kernel.  fp8_gemm_dscale reads the two scales from device memory instead.
+ * zeros).  Any shape is accepted.  The tiled matrix-core kernel takes those with K a
+ * multiple of 128 and 16-byte aligned A and B whose operand rows start on 16-byte
+ * boundaries: N a multiple of 16 where B is given as K x N, M a multiple of 16 where A is
+ * given as K x M (see fp8_gemm_ex); with B given as N x K any N goes.  A C that is not
+ * 16-byte aligned, or whose rows are not (N not a multiple of 16), is stored element by
+ * element.  The other shapes take a plain FMA kernel.  fp8_gemm_dscale reads the two
+ * scales from device memory instead.
  */
 int fp8_gemm(const uint8_t* A, int fmtA, float sA,
              const uint8_t* B, int fmtB, float sB,

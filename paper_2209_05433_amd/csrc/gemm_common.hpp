@@ -35,6 +35,8 @@ struct EpilogueArgs {
     float* amax_out;              // null or one cell, zeroed by the launcher, raised with atomicMax
     int out_kind;
     int a_per_row, b_per_col;
+    int ragged_n;                 // set by the dispatcher for the tiled kernel: rows of C or the per-column
+                                  // factors do not start on 16-byte boundaries, outputs are stored one by one
 };
 
 struct GemmArgs {

@@ -1,8 +1,8 @@
 // GEMM dispatcher and the generic kernel for gfx950 (MI355X).
 //
-// Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 128, N a multiple of
-// 16, M too if A is stored K x M, 16-byte aligned pointers) go to one of its instances; everything else is computed by the
-// generic kernel below: any shape, any alignment, every storage order, the same epilogue
+// Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 128, 16-byte aligned
+// operands whose rows start on 16-byte boundaries) go to one of its instances; everything else is
+// computed by the generic kernel below: any shape, any alignment, every storage order, the same epilogue
 // (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
 #include "gemm_common.hpp"
 
@@ -124,17 +124,19 @@ int launch_gemm(const GemmArgs& g)
         hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, g.stream, (unsigned char*)g.C, nbytes);
         return check_launch("gemm (K = 0 fill)");
     }
-    const bool aligned = aligned16(g.A) && aligned16(g.B) && aligned16(g.C) &&
-                         (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
                         K < (1ll << 31) && ((M + TILE_M - 1) / TILE_M) * ((N + TILE_N - 1) / TILE_N) < (1ll << 31);
     // The tiled kernel works on 256 x 256 tiles and clips the last ones: loads of rows / columns
     // beyond the edge are redirected to existing ones and their outputs are not stored.  What it
-    // needs: K in whole pairs of stages; rows of C and of an N-contiguous B that start on 16-byte
-    // boundaries (N % 16); the same for an M-contiguous A (M % 16).
-    const bool fast = !force_generic() && aligned && fits32 && K % (2 * TILE_K) == 0 && N % 16 == 0 &&
-                      (!g.transA || M % 16 == 0);
+    // needs: K in whole pairs of stages; 16-byte aligned operands; rows of an N-contiguous B and
+    // of an M-contiguous A that start on 16-byte boundaries (N % 16, M % 16).  Rows of C (and a
+    // per-column factor vector) that do not start on 16-byte boundaries are served by the
+    // element-wise stores of the epilogue: with B stored N x K any N goes (a vocabulary-sized
+    // output layer, weights stored [out, in]).
+    const bool c_lines = N % 16 == 0 && aligned16(g.C) && (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
+    const bool fast = !force_generic() && aligned16(g.A) && aligned16(g.B) && fits32 && K % (2 * TILE_K) == 0 &&
+                      (g.transB || N % 16 == 0) && (!g.transA || M % 16 == 0);
     if (fast) {
         // Tile width.  One workgroup per compute unit (256 of them) runs at a time.  The 256 x 128
         // tile sustains about 0.88 of the rate of the 256 x 256 tile (measured on 8192 x 49152 x
@@ -142,6 +144,7 @@ int launch_gemm(const GemmArgs& g)
         // workgroups that much better (4096 x 6144: 384 wide tiles = 1.5 rounds, 768 narrow ones = 3).
         // FP8MM_TILE_N=128|256 (environment, read per call) overrides the choice.
         GemmArgs gt = g;
+        gt.ep.ragged_n = c_lines ? 0 : 1;
         auto fill = [&](int64_t bn) {
             const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + bn - 1) / bn);
             return (double)tiles / (double)(((tiles + 255) / 256) * 256);

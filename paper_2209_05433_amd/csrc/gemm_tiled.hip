@@ -6,9 +6,11 @@
 // products are accumulated in fp32 by the matrix cores and the reciprocals of the scaling factors
 // are applied once per output (Section 2); the result is written as fp32, bf16 or FP8.
 //
-// Conditions (checked by the dispatcher): K a multiple of 128; N a multiple of 16, M too if A is
-// stored K x M; 16-byte aligned pointers.  M and N need not be multiples of the tile: loads of
-// rows / columns beyond the edge are redirected to existing ones, their outputs are not stored.
+// Conditions (checked by the dispatcher): K a multiple of 128; 16-byte aligned A and B; N a multiple
+// of 16 if B is stored K x N, M a multiple of 16 if A is stored K x M.  M and N need not be
+// multiples of the tile: loads of rows / columns beyond the edge are redirected to existing ones,
+// their outputs are not stored.  Where the rows of C (or a per-column factor vector) do not start
+// on 16-byte boundaries the epilogue stores element by element (EpilogueArgs::ragged_n).
 //
 //   - one workgroup of 4 waves per 256 x 256 output tile, each wave owns 128 x 128 of it as
 //     4 x 4 blocks of v_mfma_f32_32x32x64_f8f6f4 (K = 64 per instruction, operand formats
@@ -255,7 +257,14 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const v4f s = *(const v4f*)(ep.sB_dev + min(wave_n0 + nb * 32 + 8 * q + 4 * h, N - 4));
+                const int col = wave_n0 + nb * 32 + 8 * q + 4 * h;
+                v4f s;
+                if (ep.ragged_n) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) s[i] = ep.sB_dev[min(col + i, N - 1)];
+                } else {
+                    s = *(const v4f*)(ep.sB_dev + min(col, N - 4));
+                }
                 cb[BVEC ? nb : 0][BVEC ? q : 0] = (v4f){1.0f / s.x, 1.0f / s.y, 1.0f / s.z, 1.0f / s.w};
             }
     }
@@ -279,11 +288,13 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
                 }
                 if (ep.amax_out) {
                     // outputs beyond the edges of C hold products of redirected loads: not counted
-                    // (N is a multiple of 16, so the four columns are inside or outside together)
-                    const bool inside = wave_m0 + mb * 32 + (l & 31) < M && wave_n0 + nb * 32 + 8 * q + 4 * h < N;
-                    const unsigned keep = inside ? 0x7fffffffu : 0u;
-                    const unsigned m01 = max(as_u32(c0) & keep, as_u32(c1) & keep);
-                    const unsigned m23 = max(as_u32(c2) & keep, as_u32(c3) & keep);
+                    // (unless N is ragged, the four columns are inside or outside together)
+                    const int col = wave_n0 + nb * 32 + 8 * q + 4 * h;
+                    const bool row_in = wave_m0 + mb * 32 + (l & 31) < M;
+                    const unsigned k0 = row_in && col < N ? 0x7fffffffu : 0u, k1 = row_in && col + 1 < N ? 0x7fffffffu : 0u;
+                    const unsigned k2 = row_in && col + 2 < N ? 0x7fffffffu : 0u, k3 = row_in && col + 3 < N ? 0x7fffffffu : 0u;
+                    const unsigned m01 = max(as_u32(c0) & k0, as_u32(c1) & k1);
+                    const unsigned m23 = max(as_u32(c2) & k2, as_u32(c3) & k3);
                     amax_bits = max(amax_bits, max(m01, m23));
                 }
                 uint8_t* dst = blk + (l & 31) * ROWB + (nb * 32 + 8 * q + 4 * h) * LSZ;
@@ -303,6 +314,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
             const int row = i * ROWS_PER_ST + st_row;
             uint8_t* out = c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col;
             if (wave_m0 + mb * 32 + row >= M || wave_n0 + st_col / ESZ >= N) continue;   // beyond the edges of C
+            u32x4 o;
             if (FP8OUT) {
                 float y[16];
 #pragma unroll
@@ -310,9 +322,22 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
                     const v4f v = *LDS_PTR(v4f, blk + row * ROWB + st_col * 4 + j * 16);
                     y[4 * j] = v.x; y[4 * j + 1] = v.y; y[4 * j + 2] = v.z; y[4 * j + 3] = v.w;
                 }
-                *(u32x4*)out = encode16<OUT == OUT_E4M3 ? FP8_E4M3 : FP8_E5M2, kCastCvt>(y);
+                o = encode16<OUT == OUT_E4M3 ? FP8_E4M3 : FP8_E5M2, kCastCvt>(y);
             } else {
-                *(v4i*)out = *LDS_PTR(v4i, blk + row * ROWB + st_col);
+                o = *LDS_PTR(u32x4, blk + row * ROWB + st_col);
+            }
+            if (!ep.ragged_n) {
+                *(u32x4*)out = o;
+            } else {                                    // rows of C start anywhere: element by element
+                const int left = N - (wave_n0 + st_col / ESZ);          // columns from the lane's first one to the edge
+#pragma unroll
+                for (int e = 0; e < 16 / ESZ; ++e) {
+                    if (e < left) {
+                        if (ESZ == 4) ((unsigned*)out)[e] = o[e];
+                        else if (ESZ == 2) ((unsigned short*)out)[e] = (unsigned short)(o[e >> 1] >> (16 * (e & 1)));
+                        else out[e] = (uint8_t)(o[e >> 2] >> (8 * (e & 3)));
+                    }
+                }
             }
         }
     }

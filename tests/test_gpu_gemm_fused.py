@@ -359,6 +359,46 @@ def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers(tile_n):
         assert np.array_equal(out_to_f64(G), S / 2.0)
 
 
+@pytest.mark.parametrize("mode", MODES)
+def test_any_n_with_b_stored_n_by_k_and_unaligned_outputs(mode, tile_n):
+    """With B stored N x K (weights kept [out, in]) the tiled kernel takes any N, e.g. a vocabulary
+    size, and an output or a per-column factor vector that does not start on a 16-byte boundary: its
+    epilogue then stores element by element.  Every output kind, factors per row and per column, the
+    output amax; nothing may be written outside D."""
+    rng = np.random.default_rng(77)
+    for (M, N, K, transA, off) in [(300, 1001, 256, 0, 0), (64, 17, 128, 0, 0), (257, 1, 128, 0, 0),
+                                   (128, 50257 // 16, 384, 1, 0), (200, 272, 256, 0, 3), (513, 255, 128, 0, 1)]:
+        A = random_codes(rng, (M, K), E4M3)
+        B = random_codes(rng, (K, N), E5M2, 0x6F)
+        S, T = oracle.gemm_rows(A, E4M3, B, E5M2)
+        sA = rng.uniform(0.5, 4.0, M).astype(np.float32)
+        sB = rng.uniform(0.5, 4.0, N).astype(np.float32)
+        dA = to_dev(np.ascontiguousarray(A.T) if transA else A)
+        dB = to_dev(np.ascontiguousarray(B.T))
+        c_ref, b = reference(S, T, sA, sB, mode)
+        sBbuf = torch.zeros(N + 8, device="cuda")
+        sBbuf[off:off + N] = torch.from_numpy(sB).cuda()
+        for out_kind in (fp8.FP8_OUT_F32, fp8.FP8_OUT_BF16, fp8.FP8_OUT_E4M3):
+            esz = {fp8.FP8_OUT_F32: 4, fp8.FP8_OUT_BF16: 2, fp8.FP8_OUT_E4M3: 1}[out_kind]
+            pad = 4096 // esz
+            buf = torch.zeros(2 * pad + M * N + 8, dtype=OUT_T[out_kind], device="cuda")
+            buf.fill_(7)
+            D = buf[pad + off:pad + off + M * N].view(M, N)
+            amax = torch.full((1,), -1.0, device="cuda")
+            sD = dev_f32(np.float32(448.0 / np.max(np.abs(c_ref)))) if out_kind == fp8.FP8_OUT_E4M3 else None
+            fp8.fp8_gemm_fused(dA, E4M3, transA, dB, E5M2, 1, D, out_kind, dev_f32(sA), sBbuf[off:off + N], sD, amax,
+                               flags_of(mode))
+            torch.cuda.synchronize()
+            what = "any N %s transA %d offset %d out %d %s" % ((M, N, K), transA, off, out_kind, mode)
+            assert bool((buf[:pad + off] == 7).all()) and bool((buf[pad + off + M * N:] == 7).all()), what + ": wrote outside D"
+            if out_kind == fp8.FP8_OUT_E4M3:
+                check_fp8_bytes(D.cpu().numpy(), c_ref, b, np.float32(sD.item()), E4M3, what,
+                                min_exact=0.99 if mode == "f16" else 0.80)
+            else:
+                check_wide(D, S, T, sA, sB, out_kind, mode, what)
+            check_amax(np.float32(amax.item()), c_ref, b, what)
+
+
 def test_random_shapes_layouts_formats_and_modes_exact_on_integers(tile_n):
     """A seeded sweep over shapes (any M, N a multiple of 16 or not, K a multiple of 128 or not: tiled
     and generic kernel), storage orders, format pairs, modes and output kinds.  Operands are small
