@@ -48,6 +48,36 @@ def test_cast_and_amax_beyond_2_to_31_elements():
     assert torch.equal(q, q2)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_cast_of_an_output_beyond_the_memory_side_cache(dtype):
+    """From 384 MiB of output on the casts store non-temporally and from many short runs: 384 Mi + 37
+    elements (ragged end, both input types), E5M2, every byte against the oracle in windows, the
+    single-pass cast against the plain one on everything."""
+    n = (384 << 20) + 37
+    g = torch.Generator(device="cuda")
+    g.manual_seed(384)
+    x = torch.empty(n, dtype=dtype, device="cuda")
+    step = 1 << 27
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        x[lo:hi] = (torch.randn(hi - lo, device="cuda", generator=g) * 3.0).to(dtype)
+    scale = torch.full((1,), 100.0, device="cuda")
+    q = torch.empty(n, dtype=torch.uint8, device="cuda")
+    q2 = torch.empty(n, dtype=torch.uint8, device="cuda")
+    amax2 = torch.zeros(1, device="cuda")
+    fp8.fp8_quantize_dscale(x, E5M2, scale, q)
+    fp8.fp8_quantize_amax(x, E5M2, scale, q2, amax2)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2)
+    assert amax2.item() == x.abs().max().item()
+    w = 1 << 21
+    for lo in (0, n // 3, n - w):
+        xs = x[lo:lo + w].cpu()
+        xs = xs.numpy() if dtype == torch.float32 else xs.view(torch.int16).numpy().view(np.uint16)
+        want = oracle.quantize(xs, oracle.E5M2, np.float32(100.0))
+        assert np.array_equal(q[lo:lo + w].cpu().numpy(), want), "cast differs in the window at %d" % lo
+
+
 def test_gemm_with_operand_and_output_offsets_beyond_32_bits():
     """A of 65536 x 65536 bytes (4 GiB: row offsets pass 2^32) against a narrow B; and a product with
     2^31 outputs (65536 x 32768, 4 GiB of bf16: output offsets pass 2^32).  Sampled outputs, the last
