@@ -301,6 +301,37 @@ __device__ __forceinline__ unsigned encode_sr_bits(float y, unsigned r16)
     return sign | code;
 }
 
+// The same rule through the converter instructions of gfx950 (v_cvt_sr_fp8_f32 / v_cvt_sr_bf8_f32:
+// the random operand's upper bits are added below the kept mantissa; with the 16 random bits in
+// its upper half and zeros below, the carry is exactly that of T + r; subnormal results included.
+// Checked against the integer form on the GPU test inputs and on constructed carry boundaries).
+// The instructions do not saturate (a magnitude beyond the largest value comes out as NaN / inf), so
+// the value is clamped first; NaN and infinities take the integer form.
+// Four scaled values and their four 16-bit fields (r01 = fields 0, 1; r23 = fields 2, 3) -> 4 bytes.
+template <int FMT>
+__device__ __forceinline__ unsigned encode_sr4(float y0, float y1, float y2, float y3, unsigned r01, unsigned r23)
+{
+    if (is_special(y0) | is_special(y1) | is_special(y2) | is_special(y3))
+        return encode_sr_bits<FMT>(y0, r01 & 0xffffu) | (encode_sr_bits<FMT>(y1, r01 >> 16) << 8) |
+               (encode_sr_bits<FMT>(y2, r23 & 0xffffu) << 16) | (encode_sr_bits<FMT>(y3, r23 >> 16) << 24);
+    constexpr float FMAX = FMT == FP8_E4M3 ? 448.0f : 57344.0f;
+    y0 = __builtin_amdgcn_fmed3f(y0, FMAX, -FMAX); y1 = __builtin_amdgcn_fmed3f(y1, FMAX, -FMAX);
+    y2 = __builtin_amdgcn_fmed3f(y2, FMAX, -FMAX); y3 = __builtin_amdgcn_fmed3f(y3, FMAX, -FMAX);
+    int w = 0;
+    if (FMT == FP8_E4M3) {
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(y0, r01 << 16, w, 0);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(y1, r01 & 0xffff0000u, w, 1);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(y2, r23 << 16, w, 2);
+        w = __builtin_amdgcn_cvt_sr_fp8_f32(y3, r23 & 0xffff0000u, w, 3);
+    } else {
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y0, r01 << 16, w, 0);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y1, r01 & 0xffff0000u, w, 1);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y2, r23 << 16, w, 2);
+        w = __builtin_amdgcn_cvt_sr_bf8_f32(y3, r23 & 0xffff0000u, w, 3);
+    }
+    return (unsigned)w;
+}
+
 // Philox4x32-10 (Salmon et al., SC 2011): counter (c0, c1, 0, 0), key (k0, k1).
 __device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned k0, unsigned k1, unsigned (&out)[4])
 {
@@ -320,48 +351,59 @@ __device__ __forceinline__ void philox4x32_10(unsigned c0, unsigned c1, unsigned
 }
 
 // Element e uses the 16-bit field e % 8 (low half of word 0 first) of generator block e / 8.
+// The unit of work is one generator block = 8 elements: one 16-byte vector of bf16 input (a wave's
+// load instruction reads 1 KB of consecutive bytes) or two adjacent ones of fp32, 8 bytes of output.
+// Workgroups own contiguous runs of blocks; a lane takes blocks kThreads apart, four in flight.
 template <int DT, int FMT>
 __global__ __launch_bounds__(kThreads) void quantize_sr_kernel(const void* __restrict__ x, size_t n, float scale,
                                                               const float* __restrict__ scale_dev,
                                                               unsigned seed_lo, unsigned seed_hi,
                                                               uint8_t* __restrict__ q, bool vec)
 {
-    constexpr int V = DT == FP8_BF16 ? 2 : 4;
+    constexpr int V = DT == FP8_BF16 ? 1 : 2;       // 16-byte vectors per block
+    constexpr int U = 4;
     const float s = scale_dev ? *scale_dev : scale;
-    const size_t stride = (size_t)gridDim.x * kThreads;
     size_t done = 0;
     if (vec) {
         const u32x4* xv = (const u32x4*)x;
-        u32x4* qv = (u32x4*)q;
-        const size_t nitem = n / 16;
-        for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < nitem; i += stride) {
+        u32x2* qp = (u32x2*)q;
+        const size_t nblock = n / 8;
+        const size_t per = (nblock + gridDim.x - 1) / gridDim.x;
+        const size_t lo = (size_t)blockIdx.x * per;
+        const size_t hi = lo + per < nblock ? lo + per : nblock;
+        auto emit = [&](size_t block, const u32x4 (&v)[V]) {
+            float y[8];
+            if (DT == FP8_BF16) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) { y[2 * d] = as_f32(v[0][d] << 16) * s; y[2 * d + 1] = as_f32(v[0][d] & 0xffff0000u) * s; }
+            } else {
+#pragma unroll
+                for (int d = 0; d < 8; ++d) y[d] = as_f32(v[V - 1 < d / 4 ? V - 1 : d / 4][d & 3]) * s;
+            }
+            unsigned w[4];
+            philox4x32_10((unsigned)block, (unsigned)(block >> 32), seed_lo, seed_hi, w);
+            qp[block] = (u32x2){encode_sr4<FMT>(y[0], y[1], y[2], y[3], w[0], w[1]),
+                                encode_sr4<FMT>(y[4], y[5], y[6], y[7], w[2], w[3])};
+        };
+        size_t b = lo + threadIdx.x;
+        for (; b + (U - 1) * kThreads < hi; b += U * kThreads) {
+            u32x4 v[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < V; ++k) v[u][k] = __builtin_nontemporal_load(&xv[V * (b + (size_t)u * kThreads) + k]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) emit(b + (size_t)u * kThreads, v[u]);
+        }
+        for (; b < hi; b += kThreads) {
             u32x4 v[V];
 #pragma unroll
-            for (int j = 0; j < V; ++j) v[j] = __builtin_nontemporal_load(&xv[V * i + j]);
-            float y[16];
-            scale_item<DT>(v, s, y);
-            u32x4 o;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const size_t block = 2 * i + half;
-                unsigned w[4];
-                philox4x32_10((unsigned)block, (unsigned)(block >> 32), seed_lo, seed_hi, w);
-#pragma unroll
-                for (int d = 0; d < 2; ++d) {
-                    unsigned bytes = 0;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int f = 4 * d + b;                       // field within the block
-                        const unsigned r = (w[f / 2] >> (16 * (f % 2))) & 0xffffu;
-                        bytes |= encode_sr_bits<FMT>(y[8 * half + f], r) << (8 * b);
-                    }
-                    o[2 * half + d] = bytes;
-                }
-            }
-            qv[i] = o;
+            for (int k = 0; k < V; ++k) v[k] = __builtin_nontemporal_load(&xv[V * b + k]);
+            emit(b, v);
         }
-        done = nitem * 16;
+        done = nblock * 8;
     }
+    const size_t stride = (size_t)gridDim.x * kThreads;
     for (size_t t = done + (size_t)blockIdx.x * kThreads + threadIdx.x; t < n; t += stride) {
         const size_t block = t / 8;
         unsigned w[4];
@@ -414,7 +456,7 @@ int launch_quantize_sr(const void* x, size_t n, int in_dtype, int fmt, float sca
 {
     if (n == 0) return FP8_OK;
     const bool vec = aligned16(x) && aligned16(q_out);
-    const dim3 grid(vec ? grid_for(n / 16 + 1, kCastBlocks) : grid_for(n, 2048));
+    const dim3 grid(vec ? grid_for((n / 8 + 3) / 4, kCastBlocks) : grid_for(n, 2048));     // 4 blocks of 8 elements per lane
     FP8MM_DISPATCH_DT_FMT(quantize_sr_kernel, grid, x, n, scale, scale_dev, (unsigned)seed, (unsigned)(seed >> 32), q_out, vec);
     return check_launch("quantize_sr");
 }

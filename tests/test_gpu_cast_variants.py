@@ -205,6 +205,57 @@ def test_stochastic_rounding_cast(fmt):
     assert np.array_equal(q2.cpu().numpy(), oracle.quantize_sr(h[3:], fmt, s, 99))
 
 
+@pytest.mark.parametrize("fmt", FMTS)
+def test_stochastic_rounding_carry_boundaries_and_a_large_sweep(fmt):
+    """The kernel rounds through the converter instructions; the oracle through the definition.
+    (1) Inputs built, element by element, from the element's own random bits r so that T + r is
+    exactly 2^16 - 1 (must stay) or 2^16 (must go up), with every bit below T set: normal and
+    subnormal results.  (2) 2^24 random fp32 patterns."""
+    seed = 0x1234ABCD5678
+    mb = 3 if fmt == E4M3 else 2
+    drop = 23 - mb
+    n = 40_000
+    rng = np.random.default_rng(5 + fmt)
+    r = np.array([oracle.sr_bits(seed, i) for i in range(n)], dtype=np.int64)
+    T = np.where(np.arange(n) % 2 == 0, 65535 - r, (65536 - r) & 0xFFFF)
+    low = (1 << (drop - 16)) - 1
+    # normal results: random exponent inside the format's normal range, random kept mantissa
+    emin, emax = (-6, 7) if fmt == E4M3 else (-14, 14)
+    e = rng.integers(emin, emax + 1, n)
+    kept = rng.integers(0, 1 << mb, n)
+    bits = ((rng.integers(0, 2, n) << 31) | ((e + 127) << 23) | (kept << drop) | (T << (drop - 16)) | low).astype(np.uint32)
+    x = bits.view(np.float32).copy()
+    # subnormal results (every fourth element): |y| = (k 2^16 + T + (1 - 2^-4)) 2^-16 steps
+    step_log2 = (1 - (7 if fmt == E4M3 else 15)) - mb
+    sub = np.arange(n) % 4 >= 2
+    k = rng.integers(0, 1 << mb, n)
+    mag = ((k * 65536 + T) * 16 + 15).astype(np.float64) * 2.0 ** (step_log2 - 20)
+    x[sub] = (np.where(rng.integers(0, 2, n) == 1, -1.0, 1.0) * mag).astype(np.float32)[sub]
+    assert np.array_equal(x[sub].astype(np.float64), (np.sign(x[sub]) * mag[sub]))            # exactly representable
+    q = torch.empty(n, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_sr(to_dev(x), fmt, 1.0, seed, q)
+    torch.cuda.synchronize()
+    want = oracle.quantize_sr(x, fmt, 1.0, seed)
+    got = q.cpu().numpy()
+    assert np.array_equal(got, want), report_byte_mismatch(x.view(np.uint32), got, want)
+    # the construction does what it says: odd elements sit one code above the truncation, even ones on it
+    head = 2000
+    truncated = np.array([oracle.encode_sr(fmt, v, 0) for v in x[:head]], dtype=np.uint8)     # r = 0 never goes up
+    stays = want[:head] == truncated
+    assert stays[0::2].all() and not stays[1::2][r[1:head:2] > 0].any()
+
+    m = 1 << 24
+    big = rng.integers(0, 2 ** 32, m, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    q = torch.empty(m, dtype=torch.uint8, device="cuda")
+    fp8.fp8_quantize_sr(to_dev(big), fmt, 1.0, seed + 1, q)
+    torch.cuda.synchronize()
+    want = oracle.quantize_sr(big, fmt, 1.0, seed + 1)
+    got = q.cpu().numpy()
+    ok = ~np.isnan(big)
+    assert np.array_equal(got[ok], want[ok]), report_byte_mismatch(big.view(np.uint32)[ok], got[ok], want[ok])
+    assert np.all((got[~ok] & 0x7F) == 0x7F)
+
+
 def test_stochastic_rounding_is_unbiased_on_the_device():
     n = 1 << 22
     x = torch.full((n,), 0.3, device="cuda")
