@@ -32,6 +32,39 @@ def test_binding_has_the_same_names():
         assert callable(getattr(fp8, n)), n
 
 
+def test_header_is_plain_c_and_a_c_program_links(tmp_path):
+    """include/fp8mm.h must compile as C and as C++ without HIP or torch headers, and a C program
+    must link against the library and get an error status for a bad call (nothing is launched)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <string.h>\n#include "fp8mm.h"\n'
+        "int main(void) {\n"
+        "    float cell = 0.0f;\n"
+        "    int st = fp8_amax(&cell, 4, 99, &cell, 0);          /* bad dtype: rejected on the host */\n"
+        '    printf("%d %s|%s\\n", st, fp8_version(), fp8_last_error());\n'
+        "    return st == FP8_ERR_INVALID_ARG && strstr(fp8_last_error(), \"in_dtype\") ? 0 : 1;\n"
+        "}\n")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        if shutil.which(cc) is None:
+            continue
+        unit = tmp_path / ("hdr_" + cc + (".c" if cc == "gcc" else ".cpp"))
+        unit.write_text('#include "fp8mm.h"\nint unused_symbol_of_this_unit;\n')
+        subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", str(unit), "-o", str(unit) + ".o"],
+                       check=True, capture_output=True, text=True)
+    libdir = os.path.dirname(fp8.LIB_PATH)
+    exe = tmp_path / "use"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lfp8mm", "-Wl,-rpath," + libdir],
+                   check=True, capture_output=True, text=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "gfx950" in res.stdout
+
+
 def test_version_and_error_strings():
     assert "gfx950" in fp8.fp8_version()
     L = fp8.lib()
