@@ -1,0 +1,77 @@
+"""Two HIP streams and two host threads drive the library at once: the entry points keep no state
+between calls (the amax cells are the callers', the error text is per thread), so every result must
+equal the one obtained alone."""
+import threading
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2209_05433_amd as fp8
+
+pytestmark = pytest.mark.gpu
+
+E4M3, E5M2 = fp8.FP8_E4M3, fp8.FP8_E5M2
+
+
+def whole_path(x, w, fmt_x, out, stream):
+    """amax -> scale -> cast of both operands -> GEMM, all on `stream`; returns the intermediates."""
+    amax = torch.zeros(2, device="cuda")
+    scale = torch.zeros(2, device="cuda")
+    qx = torch.empty(x.shape, dtype=torch.uint8, device="cuda")
+    qw = torch.empty(w.shape, dtype=torch.uint8, device="cuda")
+    for t, q, i, f in ((x, qx, 0, fmt_x), (w, qw, 1, E4M3)):
+        fp8.fp8_amax(t, amax[i:i + 1], stream=stream)
+        fp8.fp8_scale_from_amax(amax[i:i + 1], f, scale[i:i + 1], stream=stream)
+        fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q, stream=stream)
+    fp8.fp8_gemm_dscale(qx, fmt_x, scale[0:1], qw, E4M3, scale[1:2], out, stream=stream)
+    return amax, scale, qx, qw
+
+
+def test_two_streams_and_two_threads_give_the_single_stream_results():
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    jobs = []
+    for (M, N, K, fmt, dt) in ((1024, 1536, 2048, E4M3, torch.bfloat16), (768, 4096, 1024, E5M2, torch.float32)):
+        x = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+        w = (torch.randn((K, N), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        jobs.append((x, w, fmt, dt, (M, N)))
+    torch.cuda.synchronize()
+    # alone, on the default stream
+    alone = []
+    for x, w, fmt, dt, shape in jobs:
+        out = torch.empty(shape, dtype=dt, device="cuda")
+        mids = whole_path(x, w, fmt, out, None)
+        torch.cuda.synchronize()
+        alone.append((out.clone(), [m.clone() for m in mids]))
+    # together: one host thread and one stream per job, several rounds each
+    streams = [torch.cuda.Stream() for _ in jobs]
+    results = [None] * len(jobs)
+    errors = []
+
+    def worker(j):
+        try:
+            x, w, fmt, dt, shape = jobs[j]
+            with torch.cuda.stream(streams[j]):
+                for _ in range(6):
+                    out = torch.full(shape, 3.0, dtype=dt, device="cuda")
+                    mids = whole_path(x, w, fmt, out, streams[j])
+                streams[j].synchronize()
+                results[j] = (out, mids)
+        except Exception as e:                                  # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for j in range(len(jobs)):
+        out, mids = results[j]
+        ref_out, ref_mids = alone[j]
+        assert torch.equal(out.view(torch.int16 if out.dtype == torch.bfloat16 else torch.int32),
+                           ref_out.view(torch.int16 if out.dtype == torch.bfloat16 else torch.int32)), j
+        for a, b in zip(mids, ref_mids):
+            assert torch.equal(a, b), j
