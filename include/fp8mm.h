@@ -280,6 +280,22 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
                    const float* sA_dev, int64_t nsA, const float* sB_dev, int64_t nsB,
                    const float* sD_dev, float* amax_out, int flags, void* stream);
 
+/*
+ * Which kernel the GEMM entry points would run for a problem (diagnostics; nothing is launched and
+ * no pointer is dereferenced: only shapes, storage orders and pointer alignment decide).  Pass the
+ * pointers of the intended call; sB_per_column is the per-column factor vector of fp8_gemm_fused or
+ * NULL.  Returns FP8_PLAN_NO_GEMM if M, N or K is 0, otherwise one of FP8_PLAN_TILED_256x256,
+ * FP8_PLAN_TILED_256x128 (matrix-core kernel, tile chosen for how well it fills the chip) or
+ * FP8_PLAN_FMA_KERNEL (any shape and alignment, far slower), ORed with
+ * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries.
+ * A negative value is minus an fp8_status_t (bad arguments).  Section 2 fixes the arithmetic,
+ * not the kernel: every plan computes the same product within the stated bounds.
+ */
+typedef enum { FP8_PLAN_NO_GEMM = 0, FP8_PLAN_FMA_KERNEL = 1, FP8_PLAN_TILED_256x256 = 2,
+               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_ELEMENTWISE_STORES = 16 } fp8_plan_t;
+int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
+                  int64_t M, int64_t N, int64_t K, const float* sB_per_column);
+
 /* Text of the last error on the calling thread ("" if none).  Static storage. */
 const char* fp8_last_error(void);
 

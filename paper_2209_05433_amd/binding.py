@@ -14,6 +14,8 @@ FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
 FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
+FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128 = 0, 1, 2, 3
+FP8_PLAN_ELEMENTWISE_STORES = 16
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
@@ -22,7 +24,7 @@ EXPORTS = (
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_last_error", "fp8_version",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_last_error", "fp8_version",
 )
 
 _lib = None
@@ -66,6 +68,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_amax_rows.argtypes, L.fp8_amax_rows.restype = [vp, i64, i64, i, vp, vp], i
     L.fp8_quantize_rows.argtypes, L.fp8_quantize_rows.restype = [vp, i64, i64, i, i, vp, vp, vp], i
     L.fp8_quantize_transpose.argtypes, L.fp8_quantize_transpose.restype = [vp, i64, i64, i, i, vp, vp, vp, vp], i
+    L.fp8_gemm_plan.argtypes, L.fp8_gemm_plan.restype = [vp, i, vp, i, vp, i64, i64, i64, vp], i
     L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
     L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
     _lib = L
@@ -105,6 +108,18 @@ def fp8_last_error() -> str:
 
 def fp8_version() -> str:
     return lib().fp8_version().decode()
+
+
+def fp8_gemm_plan(A: torch.Tensor, transA: bool, B: torch.Tensor, transB: bool, C: torch.Tensor, sB_per_column=None) -> int:
+    """Which kernel the GEMM entry points would run for these tensors (an fp8_plan_t, possibly ORed
+    with FP8_PLAN_ELEMENTWISE_STORES); nothing is launched."""
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    plan = lib().fp8_gemm_plan(A.data_ptr(), int(bool(transA)), B.data_ptr(), int(bool(transB)), C.data_ptr(), M, N, K,
+                               None if sB_per_column is None else sB_per_column.data_ptr())
+    if plan < 0:
+        raise Fp8Error(-plan, lib().fp8_last_error().decode())
+    return plan
 
 
 def fp8_amax(x: torch.Tensor, amax_out: torch.Tensor, stream=None) -> None:

@@ -333,4 +333,21 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
     return launch_gemm(g);
 }
 
+int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
+                  int64_t M, int64_t N, int64_t K, const float* sB_per_column)
+{
+    clear_error();
+    if (M < 0 || N < 0 || K < 0) return -fail(FP8_ERR_INVALID_ARG, "fp8_gemm_plan: negative dimension (M=%lld N=%lld K=%lld)", (long long)M, (long long)N, (long long)K);
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return -fail(FP8_ERR_INVALID_ARG, "fp8_gemm_plan: transA/transB must be 0 or 1");
+    if (M == 0 || N == 0 || K == 0) return FP8_PLAN_NO_GEMM;
+    GemmArgs g{};
+    g.A = A; g.B = B; g.C = const_cast<void*>(C); g.M = M; g.N = N; g.K = K;
+    g.transA = transA != 0; g.transB = transB != 0;
+    g.ep.sB_dev = sB_per_column; g.ep.b_per_col = sB_per_column != nullptr;
+    const GemmPlan plan = plan_gemm(g);
+    const int kernel = plan.kernel == GEMM_GENERIC ? FP8_PLAN_FMA_KERNEL
+                     : plan.kernel == GEMM_TILED_128 ? FP8_PLAN_TILED_256x128 : FP8_PLAN_TILED_256x256;
+    return kernel | (plan.elementwise_stores ? FP8_PLAN_ELEMENTWISE_STORES : 0);
+}
+
 }  // extern "C"

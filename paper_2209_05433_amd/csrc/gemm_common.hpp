@@ -67,6 +67,11 @@ constexpr int TILE_M = 256, TILE_N = 256, TILE_K = 64;
 
 int launch_gemm(const GemmArgs& g);
 
+// The dispatcher's decision for a problem with M, N, K > 0 (what launch_gemm acts on).
+enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3 };
+struct GemmPlan { int kernel; bool elementwise_stores; };
+GemmPlan plan_gemm(const GemmArgs& g);
+
 // ---- small device helpers used by both kernels ----------------------------------------------
 __device__ __forceinline__ float scale_value(const float* dev, float host) { return dev ? *dev : host; }
 

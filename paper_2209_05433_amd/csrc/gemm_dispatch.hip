@@ -111,19 +111,11 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace
 
-int launch_gemm(const GemmArgs& g)
+// Which kernel a (non-empty, K > 0) problem takes.
+GemmPlan plan_gemm(const GemmArgs& g)
 {
     const int64_t M = g.M, N = g.N, K = g.K;
-    if (g.ep.amax_out) {                                     // written, not accumulated
-        hipLaunchKernelGGL(zero_cell_kernel, dim3(1), dim3(1), 0, g.stream, (unsigned*)g.ep.amax_out);
-        if (M == 0 || N == 0) return check_launch("gemm (amax init)");
-    }
-    if (M == 0 || N == 0) return FP8_OK;
-    if (K == 0) {                                            // empty sums: every output is +0
-        const size_t nbytes = (size_t)M * (size_t)N * (size_t)out_elem_size(g.ep.out_kind);
-        hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, g.stream, (unsigned char*)g.C, nbytes);
-        return check_launch("gemm (K = 0 fill)");
-    }
+    GemmPlan plan{GEMM_GENERIC, false};
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
                         K < (1ll << 31) && ((M + TILE_M - 1) / TILE_M) * ((N + TILE_N - 1) / TILE_N) < (1ll << 31);
@@ -137,21 +129,41 @@ int launch_gemm(const GemmArgs& g)
     const bool c_lines = N % 16 == 0 && aligned16(g.C) && (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
     const bool fast = !force_generic() && aligned16(g.A) && aligned16(g.B) && fits32 && K % (2 * TILE_K) == 0 &&
                       (g.transB || N % 16 == 0) && (!g.transA || M % 16 == 0);
-    if (fast) {
-        // Tile width.  One workgroup per compute unit (256 of them) runs at a time.  The 256 x 128
-        // tile sustains about 0.88 of the rate of the 256 x 256 tile (measured on 8192 x 49152 x
-        // 12288: 0.80-0.92 over the layouts and modes), so it is chosen when it fills the rounds of
-        // workgroups that much better (4096 x 6144: 384 wide tiles = 1.5 rounds, 768 narrow ones = 3).
-        // FP8MM_TILE_N=128|256 (environment, read per call) overrides the choice.
+    if (!fast) return plan;
+    // Tile width.  One workgroup per compute unit (256 of them) runs at a time.  The 256 x 128
+    // tile sustains about 0.88 of the rate of the 256 x 256 tile (measured on 8192 x 49152 x
+    // 12288: 0.80-0.92 over the layouts and modes), so it is chosen when it fills the rounds of
+    // workgroups that much better (4096 x 6144: 384 wide tiles = 1.5 rounds, 768 narrow ones = 3).
+    // FP8MM_TILE_N=128|256 (environment, read per call) overrides the choice.
+    auto fill = [&](int64_t bn) {
+        const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + bn - 1) / bn);
+        return (double)tiles / (double)(((tiles + 255) / 256) * 256);
+    };
+    const char* tn = getenv("FP8MM_TILE_N");
+    const bool narrow = tn ? atoi(tn) == 128 : 0.88 * fill(128) > fill(256);
+    plan.kernel = narrow ? GEMM_TILED_128 : GEMM_TILED_256;
+    plan.elementwise_stores = !c_lines;
+    return plan;
+}
+
+int launch_gemm(const GemmArgs& g)
+{
+    const int64_t M = g.M, N = g.N, K = g.K;
+    if (g.ep.amax_out) {                                     // written, not accumulated
+        hipLaunchKernelGGL(zero_cell_kernel, dim3(1), dim3(1), 0, g.stream, (unsigned*)g.ep.amax_out);
+        if (M == 0 || N == 0) return check_launch("gemm (amax init)");
+    }
+    if (M == 0 || N == 0) return FP8_OK;
+    if (K == 0) {                                            // empty sums: every output is +0
+        const size_t nbytes = (size_t)M * (size_t)N * (size_t)out_elem_size(g.ep.out_kind);
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(1024), dim3(256), 0, g.stream, (unsigned char*)g.C, nbytes);
+        return check_launch("gemm (K = 0 fill)");
+    }
+    const GemmPlan plan = plan_gemm(g);
+    if (plan.kernel != GEMM_GENERIC) {
         GemmArgs gt = g;
-        gt.ep.ragged_n = c_lines ? 0 : 1;
-        auto fill = [&](int64_t bn) {
-            const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + bn - 1) / bn);
-            return (double)tiles / (double)(((tiles + 255) / 256) * 256);
-        };
-        const char* tn = getenv("FP8MM_TILE_N");
-        if (tn) gt.tile_n = atoi(tn) == 128 ? 128 : 256;
-        else gt.tile_n = 0.88 * fill(128) > fill(256) ? 128 : 256;
+        gt.ep.ragged_n = plan.elementwise_stores ? 1 : 0;
+        gt.tile_n = plan.kernel == GEMM_TILED_128 ? 128 : 256;
         typedef int (*tiled_fn)(const GemmArgs&);
         static const tiled_fn table[4][2] = {
             {FP8MM_TILED_NAME(0, 0), FP8MM_TILED_NAME(0, 1)}, {FP8MM_TILED_NAME(1, 0), FP8MM_TILED_NAME(1, 1)},

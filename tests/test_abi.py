@@ -65,6 +65,32 @@ def test_header_is_plain_c_and_a_c_program_links(tmp_path):
     assert "gfx950" in res.stdout
 
 
+def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
+    """fp8_gemm_plan is host logic over shapes, storage orders and pointer alignment (no pointer is
+    dereferenced, so made-up aligned addresses do): the five workloads and the layer GEMMs around them
+    must land on the matrix-core kernel, and only shapes it cannot take on the FMA kernel."""
+    L = fp8.lib()
+    A, B, C = 1 << 20, 1 << 24, 1 << 28                         # 16-byte aligned stand-ins
+    T256, T128, FMA, EW = fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_FMA_KERNEL, fp8.FP8_PLAN_ELEMENTWISE_STORES
+    plan = lambda ta, tb, M, N, K, a=A, b=B, c=C, sb=None: L.fp8_gemm_plan(a, ta, b, tb, c, M, N, K, sb)
+    assert plan(0, 0, 8192, 49152, 12288) == T256                # config 4
+    assert plan(1, 0, 8192, 12288, 49152) == T256                # config 5 with A stored K x M
+    assert plan(0, 0, 4096, 6144, 2048) == T128                  # config 3: 384 wide tiles would leave half a round empty
+    assert plan(0, 0, 256, 256, 256) in (T256, T128)             # config 1
+    for ta in (0, 1):
+        for tb in (0, 1):
+            assert plan(ta, tb, 12288, 49152, 8192) == T256      # weight gradient of the FFN-up layer, any storage order
+    assert plan(0, 1, 8192, 50257, 12288) == T256 | EW           # vocabulary-sized N with weights stored [out, in]
+    assert plan(0, 0, 8192, 50257, 12288) == FMA                 # ... stored [in, out]: rows of B start anywhere
+    assert plan(1, 0, 50257, 12288, 8192) == FMA                 # rows of an M-contiguous A start anywhere
+    assert plan(0, 0, 512, 512, 448) == FMA                      # K not a multiple of 128
+    assert plan(0, 0, 512, 512, 512, a=A + 4) == FMA             # operand not 16-byte aligned
+    assert plan(0, 0, 4096, 4096, 512, c=C + 2) == T256 | EW     # output not 16-byte aligned
+    assert plan(0, 0, 4096, 4096, 512, sb=C + 4) == T256 | EW    # per-column factors not 16-byte aligned
+    assert plan(0, 0, 0, 5, 5) == fp8.FP8_PLAN_NO_GEMM and plan(0, 0, 5, 5, 0) == fp8.FP8_PLAN_NO_GEMM
+    assert plan(2, 0, 5, 5, 5) == -fp8.FP8_ERR_INVALID_ARG and plan(0, 0, -1, 5, 5) == -fp8.FP8_ERR_INVALID_ARG
+
+
 def test_version_and_error_strings():
     assert "gfx950" in fp8.fp8_version()
     L = fp8.lib()

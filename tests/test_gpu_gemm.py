@@ -251,6 +251,7 @@ def run_config(A_bits, B_bits, fmtA, fmtB, out_dtype, npts, nrows, label):
         fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
     fp8.fp8_gemm_dscale(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C)
     torch.cuda.synchronize()
+    assert fp8.fp8_gemm_plan(qA, 0, qB, 0, C) in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), label
     del dA, dB
     Aq, sA, Bq, sB = quantize_pair(A_bits, B_bits, fmtA, fmtB)
     assert np.float32(scale[0].item()) == sA and np.float32(scale[1].item()) == sB, label
