@@ -22,8 +22,12 @@
  *     LDS limit (hipFuncSetAttribute) and should be made outside a capture.
  *   - Output cells described as "written, not accumulated" are cleared by a small
  *     kernel on the same stream before they are raised with atomics.
- *   - The return value is an fp8_status_t.  On anything but FP8_OK nothing was
- *     launched and no output was written; fp8_last_error() describes the reason.
+ *   - The return value is an fp8_status_t; fp8_last_error() describes the reason of a
+ *     failure.  FP8_ERR_INVALID_ARG and FP8_ERR_UNSUPPORTED are found on the host before
+ *     anything is enqueued: nothing was launched, no output was written.  FP8_ERR_DEVICE
+ *     reports what the HIP runtime said at a launch; kernels enqueued earlier in the same
+ *     call (the clearing of a "written, not accumulated" cell) may already have run, and
+ *     the outputs of the call are then unspecified.
  *   - Tensors are dense and contiguous.  Matrices are row-major.
  *   - bfloat16 data is the upper 16 bits of an IEEE single (uint16_t storage).
  */
@@ -64,6 +68,23 @@ typedef enum {
  * order like the values (Section 3.1).
  */
 int fp8_amax(const void* x, size_t n, int in_dtype, float* amax_out, void* stream);
+
+/*
+ * fp8_amax_scale -- fp8_amax and fp8_scale_from_amax in ONE kernel launch (Section 2: the factor
+ * is chosen from the tensor's largest magnitude; amax and factor are those of the two calls, bit for
+ * bit).  No cell is cleared beforehand: every workgroup leaves its maximum in the workspace and the
+ * last one to finish reduces them and writes both results.  For the per-step path
+ * amax -> scale -> cast, where two one-thread launches cost as much as casting a small tensor.
+ *   amax_out   device, one fp32, overwritten;  scale_out  device, one fp32, or NULL (amax only)
+ *   workspace  device, FP8_AMAX_WORKSPACE_BYTES bytes, 4-byte aligned.  Its first 4 bytes must be
+ *              zero before the first call that uses it; every call leaves them zero again, so
+ *              calls that follow one another on a stream can share one workspace.  Calls that may
+ *              overlap (different streams) need a workspace each.
+ * n == 0 gives amax 0 and scale 1.  Errors as fp8_amax.
+ */
+#define FP8_AMAX_WORKSPACE_BYTES 8192
+int fp8_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out,
+                   void* workspace, void* stream);
 
 /*
  * fp8_scale_from_amax_host / fp8_scale_from_amax -- scale = fmt_max / amax in IEEE
@@ -159,7 +180,7 @@ int fp8_scale_from_amax_n(const float* amax, size_t n, int fmt, float* scale_out
 
 /*
  * fp8_amax_rows / fp8_quantize_rows -- one maximum / one scaling factor per row of a
- * rows x cols row-major matrix (Section 5: per-channel scaling factors for weights; a weight
+ * rows x cols row-major matrix (Section 4.2: per-channel scaling factors for weights; a weight
  * stored [out x in] with one factor per output channel is the N x K form of operand B, and its
  * factors are the per-column factors of fp8_gemm_fused).
  *   amax_out   device, rows fp32:  amax_out[r] = max_c |x[r][c]| (NaN propagates; cols == 0: 0)
@@ -196,7 +217,7 @@ int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dty
  * exactly to fp16 in registers and multiplied by the fp16 matrix-core instructions,
  * whose accumulation is fp32-grade.  M, N or K equal to 0 is valid (K == 0 writes
  * zeros).  Any shape is accepted.  The tiled matrix-core kernel takes those with K a
- * multiple of 128 and 16-byte aligned A and B whose operand rows start on 16-byte
+ * multiple of 16 and 16-byte aligned A and B whose operand rows start on 16-byte
  * boundaries: N a multiple of 16 where B is given as K x N, M a multiple of 16 where A is
  * given as K x M (see fp8_gemm_ex); with B given as N x K any N goes.  A C that is not
  * 16-byte aligned, or whose rows are not (N not a multiple of 16), is stored element by
@@ -249,6 +270,31 @@ int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fm
                 void* stream);
 
 /*
+ * fp8_gemm_splitk -- fp8_gemm_ex for problems with few output tiles and a long K, above all the
+ * weight gradient dW = dY^T X (Section 4.1: activation gradients and activations are GEMM inputs;
+ * its K is the number of tokens).  K is cut into slices; every slice of every 256 x 256 tile is a
+ * workgroup of its own, so that a 1024 x 1024 x 65536 problem occupies the whole chip instead of 16
+ * compute units.  The slices' fp32 sums go to `workspace`; a second kernel adds them in slice order
+ * (results are the same in every run), applies 1 / (sA sB) once per output (Section 2) and converts.
+ * Arguments, bounds and error behaviour as fp8_gemm_ex, and:
+ *   splits           0: the library chooses (about 256 / tiles, slices of at least 512 along K);
+ *                    1..64: that many slices (fewer if K is too short to give each one 128)
+ *   workspace        device, 4-byte aligned (16 for the fastest stores), at least
+ *                    fp8_gemm_splitk_workspace_size(M, N, K, transA, transB, splits) bytes
+ *                    = slices x M x N x 4; contents on entry are irrelevant, they are overwritten.
+ *                    May be NULL where that size is 0 (one slice, or a problem the tiled kernel
+ *                    does not take: the call is then fp8_gemm_ex).
+ *   workspace_bytes  size of the workspace; too small is an FP8_ERR_INVALID_ARG, nothing launched
+ * fp8_gemm_splitk_workspace_size assumes 16-byte aligned A and B (what the tiled kernel needs) and
+ * returns 0 for M, N or K <= 0 or splits outside 0..64.
+ */
+size_t fp8_gemm_splitk_workspace_size(int64_t M, int64_t N, int64_t K, int transA, int transB, int splits);
+int fp8_gemm_splitk(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                    void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
+                    float sA, float sB, const float* sA_dev, const float* sB_dev, int flags,
+                    int splits, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * fp8_gemm_fused -- the GEMM with the scale granularities and the output conversions that
  * training recipes build on:
  *     c_ij    = (sum_k a_ik b_kj) / (sA_i * sB_j)
@@ -256,7 +302,7 @@ int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fm
  *     D_ij    = cast_out(c_ij)            for FP8_OUT_F32 / FP8_OUT_BF16
  *     D_ij    = encode_fmt(fl32(c_ij * sD))  for FP8_OUT_E4M3 / FP8_OUT_E5M2
  * Section 2: results of FP8 matrix products may be converted to FP8 before they are written
- * to memory, with a scaling factor of their own; Section 5 uses per-channel scaling factors
+ * to memory, with a scaling factor of their own; Section 4.2 uses per-channel scaling factors
  * for weights; Section 4.3 / Section 2 leave the choice of the factor to software -- the
  * output amax is what a recipe that derives the next step's factor from past maxima needs.
  *   A, B, transA, transB, M, N, K, flags: as for fp8_gemm_ex
@@ -295,6 +341,25 @@ typedef enum { FP8_PLAN_NO_GEMM = 0, FP8_PLAN_FMA_KERNEL = 1, FP8_PLAN_TILED_256
                FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_ELEMENTWISE_STORES = 16 } fp8_plan_t;
 int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
                   int64_t M, int64_t N, int64_t K, const float* sB_per_column);
+
+/*
+ * Tuning knobs, for diagnostics, tests and benchmarks (the paper fixes the arithmetic, not the
+ * kernels: no knob changes a result beyond the stated bounds).  Process-wide; each is seeded once
+ * from the environment variable named below and changed with fp8_set_knob, which returns the
+ * previous value (or minus an fp8_status_t for a bad knob or value).  Set them while no other
+ * thread is inside a library call.
+ *   FP8_KNOB_CAST_PATH    0 the FP8 conversion instructions of gfx950 (default), 1 the integer
+ *                         rounding written from Table 1 (FP8MM_CAST_PATH=bits); both are bit-equal
+ *   FP8_KNOB_TILE_N       0 the dispatcher chooses, 128 or 256 forces the tile width of the
+ *                         matrix-core kernel (FP8MM_TILE_N)
+ *   FP8_KNOB_GROUP_M      tile rows per band of the tile order, 0 = default 8 (FP8MM_GROUP_M)
+ *   FP8_KNOB_GEMM_KERNEL  0 the dispatcher chooses, 1 always the plain FMA kernel (FP8MM_GEMM=generic)
+ *   FP8_KNOB_SPLIT_K      0 fp8_gemm_splitk chooses its number of K slices, n > 0 forces n (FP8MM_SPLIT_K)
+ */
+typedef enum { FP8_KNOB_CAST_PATH = 0, FP8_KNOB_TILE_N = 1, FP8_KNOB_GROUP_M = 2, FP8_KNOB_GEMM_KERNEL = 3,
+               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_COUNT = 5 } fp8_knob_t;
+int fp8_set_knob(int knob, int value);
+int fp8_get_knob(int knob);
 
 /* Text of the last error on the calling thread ("" if none).  Static storage. */
 const char* fp8_last_error(void);

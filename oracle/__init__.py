@@ -60,6 +60,9 @@ def _load():
     lib.fp8o_gemm_rows.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_int,
                                    c.c_int64, c.c_int64, c.c_int64,
                                    c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
+    lib.fp8o_gemm_block_sums.restype = c.c_int
+    lib.fp8o_gemm_block_sums.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int64,
+                                         c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.fp8o_encode_sr.restype = c.c_uint8
     lib.fp8o_encode_sr.argtypes = [c.c_int, c.c_float, c.c_uint32]
     lib.fp8o_philox4x32.restype = None
@@ -148,7 +151,7 @@ def quantize_sr(x: np.ndarray, fmt: int, scale, seed: int) -> np.ndarray:
 
 def amax_rows(x: np.ndarray) -> np.ndarray:
     """amax of every row of a 2-D tensor: the per-tensor definition applied to each row on its own
-    (per-channel granularity, Section 5)."""
+    (per-channel granularity, Section 4.2)."""
     return np.array([amax(x[r]) for r in range(x.shape[0])], dtype=np.float32)
 
 
@@ -228,7 +231,7 @@ def unscale(S, sA, sB):
 
 def unscale_channels(S, sA, sB):
     """C_ref[i, j] = S[i, j] / (sA[i] * sB[j]) in double precision: per-channel scaling factors
-    (Section 5 uses them for weights) taken out once per dot product.  sA: one value or one per
+    (Section 4.2 uses them for weights) taken out once per dot product.  sA: one value or one per
     row of S; sB: one value or one per column.  Returns (C_ref, alpha) with alpha[i, j] =
     1 / (sA[i] * sB[j]) broadcast to the shape of S."""
     S = np.asarray(S, dtype=np.float64)
@@ -256,3 +259,27 @@ def gemm_bound(S, T, sA, sB, out_dtype: int):
     c_ref, alpha = unscale_channels(S, sA, sB) if (np.size(sA) > 1 or np.size(sB) > 1) else unscale(S, sA, sB)
     bound = 2.0 ** -20 * alpha * np.asarray(T, dtype=np.float64) + 0.5 * ulp(c_ref, out_dtype)
     return c_ref, bound
+
+
+def gemm_block_sums(A, fmtA, B, fmtB, r, block: int):
+    """Signed sums of the reference product over blocks of consecutive columns, in double precision:
+        SR[i, t] = sum_{j in block t} r[j] * S[i, j],    TR[i, t] = sum_{j in block t} T[i, j]
+    with S, T as in gemm_rows (sum and sum of magnitudes of the products a_ik b_kj over k), r one
+    multiplier of magnitude 1 per column and block t = columns [t*block, (t+1)*block).  By linearity
+    SR = dec(A) (dec(B) R) with R the N x nb matrix that holds r on its block pattern, which costs
+    O(MK nb + KN) instead of O(MNK): the whole-matrix check for problems whose every output the plain
+    loops cannot reach (a Freivalds check, one random sign vector per block of columns).  Finite
+    operands only."""
+    A, B, M, N, K = _check_ab(A, B)
+    r = np.ascontiguousarray(r, dtype=np.float64).reshape(-1)
+    if r.size != N or block <= 0 or not np.all(np.abs(r) == 1.0):
+        raise ValueError("one multiplier of magnitude 1 per column and a positive block width expected")
+    nb = (N + block - 1) // block
+    BR = np.empty((K, nb), dtype=np.float64)
+    BT = np.empty((K, nb), dtype=np.float64)
+    SR = np.empty((M, nb), dtype=np.float64)
+    TR = np.empty((M, nb), dtype=np.float64)
+    if _load().fp8o_gemm_block_sums(_ptr(A), fmtA, _ptr(B), fmtB, M, N, K, _ptr(r), block,
+                                    _ptr(BR), _ptr(BT), _ptr(SR), _ptr(TR)):
+        raise ValueError("gemm_block_sums takes finite operands only")
+    return SR, TR

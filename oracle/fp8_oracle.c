@@ -384,6 +384,63 @@ void fp8o_gemm_rows(const uint8_t *A, int fmtA, const uint8_t *B, int fmtB,
     }
 }
 
+/* Signed block sums of the reference product, for the whole-matrix check of problems whose
+ * every output the loops above cannot reach.  With r one multiplier (+-1) per column and block t =
+ * columns [t * block, (t + 1) * block):
+ *     SR[i][t] = sum_{j in block t} r[j] * S[i][j] = sum_k decode(A[i,k]) * BR[k][t],
+ *     BR[k][t] = sum_{j in block t} r[j] * decode(B[k,j]),
+ * and the same with magnitudes for TR (|r[j]| = 1 is assumed: TR[i][t] = sum_j T[i][j]).
+ * Plain reassociation of the definition (every term is exact in double); SR, TR are M x nb. */
+int fp8o_gemm_block_sums(const uint8_t *A, int fmtA, const uint8_t *B, int fmtB,
+                         int64_t M, int64_t N, int64_t K, const double *r, int64_t block,
+                         double *BR, double *BT, double *SR, double *TR)
+{
+    double va[256], vb[256];
+    const int64_t nb = (N + block - 1) / block;
+    int64_t k, i;
+    int nonfinite = 0;             /* set if an operand byte decodes to inf or NaN: sums are then meaningless */
+    decode_table(fmtA, va);
+    decode_table(fmtB, vb);
+#pragma omp parallel for schedule(static)
+    for (k = 0; k < K; ++k) {
+        const uint8_t *brow = B + k * N;
+        int64_t j;
+        for (j = 0; j < nb; ++j) { BR[k * nb + j] = 0.0; BT[k * nb + j] = 0.0; }
+        for (j = 0; j < N; ++j) {
+            const double b = vb[brow[j]];
+            const int64_t t = j / block;
+            BR[k * nb + t] += r[j] * b;
+            BT[k * nb + t] += fabs(b);
+        }
+        for (j = 0; j < nb; ++j)
+            if (!isfinite(BT[k * nb + j])) {
+#pragma omp atomic write
+                nonfinite = 1;
+            }
+    }
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < M; ++i) {
+        const uint8_t *arow = A + i * K;
+        double *s = SR + i * nb, *t = TR + i * nb;
+        int64_t kk, j;
+        for (j = 0; j < nb; ++j) { s[j] = 0.0; t[j] = 0.0; }
+        for (kk = 0; kk < K; ++kk) {
+            const double a = va[arow[kk]], aa = fabs(a);
+            const double *br = BR + kk * nb, *bt = BT + kk * nb;
+            for (j = 0; j < nb; ++j) {
+                s[j] += a * br[j];
+                t[j] += aa * bt[j];
+            }
+        }
+        for (j = 0; j < nb; ++j)
+            if (!isfinite(t[j])) {
+#pragma omp atomic write
+                nonfinite = 1;
+            }
+    }
+    return nonfinite;
+}
+
 int fp8o_num_threads(void)
 {
     int n = 1;

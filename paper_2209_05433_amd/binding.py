@@ -12,19 +12,22 @@ FP8_E4M3, FP8_E5M2 = 0, 1
 FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
+FP8_AMAX_WORKSPACE_BYTES = 8192
 FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
 FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128 = 0, 1, 2, 3
 FP8_PLAN_ELEMENTWISE_STORES = 16
+FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K = 0, 1, 2, 3, 4
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
 EXPORTS = (
-    "fp8_amax", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
+    "fp8_amax", "fp8_amax_scale", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_last_error", "fp8_version",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_splitk", "fp8_gemm_splitk_workspace_size", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_set_knob", "fp8_get_knob",
+    "fp8_last_error", "fp8_version",
 )
 
 _lib = None
@@ -49,6 +52,7 @@ def lib() -> ctypes.CDLL:
     c = ctypes
     vp, sz, i, i64, f = c.c_void_p, c.c_size_t, c.c_int, c.c_int64, c.c_float
     L.fp8_amax.argtypes, L.fp8_amax.restype = [vp, sz, i, vp, vp], i
+    L.fp8_amax_scale.argtypes, L.fp8_amax_scale.restype = [vp, sz, i, i, vp, vp, vp, vp], i
     L.fp8_scale_from_amax_host.argtypes, L.fp8_scale_from_amax_host.restype = [f, i], f
     L.fp8_scale_from_amax.argtypes, L.fp8_scale_from_amax.restype = [vp, i, vp, vp], i
     L.fp8_quantize.argtypes, L.fp8_quantize.restype = [vp, sz, i, i, f, vp, vp], i
@@ -60,6 +64,8 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
+    L.fp8_gemm_splitk.argtypes, L.fp8_gemm_splitk.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, i, vp, sz, vp], i
+    L.fp8_gemm_splitk_workspace_size.argtypes, L.fp8_gemm_splitk_workspace_size.restype = [i64, i64, i64, i, i, i], sz
     L.fp8_gemm_fused.argtypes, L.fp8_gemm_fused.restype = [vp, i, i, vp, i, i, vp, i, i64, i64, i64, vp, i64, vp, i64, vp, vp, i, vp], i
     L.fp8_quantize_sr.argtypes, L.fp8_quantize_sr.restype = [vp, sz, i, i, f, vp, c.c_uint64, vp, vp], i
     L.fp8_quantize_amax.argtypes, L.fp8_quantize_amax.restype = [vp, sz, i, i, vp, vp, vp, vp], i
@@ -69,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.fp8_quantize_rows.argtypes, L.fp8_quantize_rows.restype = [vp, i64, i64, i, i, vp, vp, vp], i
     L.fp8_quantize_transpose.argtypes, L.fp8_quantize_transpose.restype = [vp, i64, i64, i, i, vp, vp, vp, vp], i
     L.fp8_gemm_plan.argtypes, L.fp8_gemm_plan.restype = [vp, i, vp, i, vp, i64, i64, i64, vp], i
+    L.fp8_set_knob.argtypes, L.fp8_set_knob.restype = [i, i], i
+    L.fp8_get_knob.argtypes, L.fp8_get_knob.restype = [i], i
     L.fp8_last_error.argtypes, L.fp8_last_error.restype = [], c.c_char_p
     L.fp8_version.argtypes, L.fp8_version.restype = [], c.c_char_p
     _lib = L
@@ -110,6 +118,21 @@ def fp8_version() -> str:
     return lib().fp8_version().decode()
 
 
+def fp8_set_knob(knob: int, value: int) -> int:
+    """Sets a tuning knob (fp8_knob_t) and returns its previous value."""
+    old = lib().fp8_set_knob(int(knob), int(value))
+    if old < 0:
+        raise Fp8Error(-old, lib().fp8_last_error().decode())
+    return old
+
+
+def fp8_get_knob(knob: int) -> int:
+    v = lib().fp8_get_knob(int(knob))
+    if v < 0:
+        raise Fp8Error(-v, lib().fp8_last_error().decode())
+    return v
+
+
 def fp8_gemm_plan(A: torch.Tensor, transA: bool, B: torch.Tensor, transB: bool, C: torch.Tensor, sB_per_column=None) -> int:
     """Which kernel the GEMM entry points would run for these tensors (an fp8_plan_t, possibly ORed
     with FP8_PLAN_ELEMENTWISE_STORES); nothing is launched."""
@@ -125,6 +148,16 @@ def fp8_gemm_plan(A: torch.Tensor, transA: bool, B: torch.Tensor, transB: bool, 
 def fp8_amax(x: torch.Tensor, amax_out: torch.Tensor, stream=None) -> None:
     _check(lib().fp8_amax(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x),
                           _dev(amax_out, "amax_out"), _stream(stream)))
+
+
+def fp8_amax_scale(x: torch.Tensor, fmt: int, amax_out: torch.Tensor, scale_out, workspace: torch.Tensor, stream=None) -> None:
+    """amax and scale = fmt_max / amax in one launch; workspace: device tensor of at least
+    FP8_AMAX_WORKSPACE_BYTES bytes whose first 4 bytes were zero before its first use."""
+    if workspace.numel() * workspace.element_size() < FP8_AMAX_WORKSPACE_BYTES:
+        raise ValueError("workspace must hold FP8_AMAX_WORKSPACE_BYTES bytes")
+    _check(lib().fp8_amax_scale(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
+                                _dev(amax_out, "amax_out"), _dev(scale_out, "scale_out") if scale_out is not None else None,
+                                _dev(workspace, "workspace"), _stream(stream)))
 
 
 def fp8_scale_from_amax_host(amax: float, fmt: int) -> float:
@@ -227,6 +260,39 @@ def fp8_gemm_ex(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, s
                              0.0 if dev else float(sA), 0.0 if dev else float(sB),
                              _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
                              int(flags), _stream(stream)))
+
+
+def _gemm_ex_dims(A, transA, B, transB, C):
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8 or A.dim() != 2 or B.dim() != 2:
+        raise ValueError("A and B must be 2-D uint8 tensors of FP8 bytes")
+    M, K = (A.shape[1], A.shape[0]) if transA else A.shape
+    N, K2 = (B.shape[0], B.shape[1]) if transB else (B.shape[1], B.shape[0])
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not form C[M,N] = op(A)[M,K] op(B)[K,N]")
+    return M, N, K
+
+
+def fp8_gemm_splitk_workspace_size(M: int, N: int, K: int, transA: bool, transB: bool, splits: int = 0) -> int:
+    return int(lib().fp8_gemm_splitk_workspace_size(M, N, K, int(bool(transA)), int(bool(transB)), int(splits)))
+
+
+def fp8_gemm_splitk(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, sB, workspace, flags: int = 0,
+                    splits: int = 0, stream=None) -> None:
+    """fp8_gemm_ex with K cut into slices; `workspace` is a device tensor (any dtype) of at least
+    fp8_gemm_splitk_workspace_size(...) bytes, or None where that is 0."""
+    M, N, K = _gemm_ex_dims(A, transA, B, transB, C)
+    dev = isinstance(sA, torch.Tensor)
+    if dev != isinstance(sB, torch.Tensor):
+        raise ValueError("sA and sB must both be floats or both device tensors")
+    _check(lib().fp8_gemm_splitk(_dev(A, "A") if A.numel() else None, fmtA, int(bool(transA)),
+                                 _dev(B, "B") if B.numel() else None, fmtB, int(bool(transB)),
+                                 _dev(C, "C") if C.numel() else None, M, N, K, dtype_code(C),
+                                 0.0 if dev else float(sA), 0.0 if dev else float(sB),
+                                 _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
+                                 int(flags), int(splits),
+                                 _dev(workspace, "workspace") if workspace is not None else None,
+                                 workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                 _stream(stream)))
 
 
 def fp8_gemm_fused(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, D, out_kind: int, sA, sB,

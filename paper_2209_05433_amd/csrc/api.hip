@@ -1,6 +1,8 @@
 // extern "C" entry points of libfp8mm: argument validation, then one launcher each.
 #include "gemm_common.hpp"
 
+#include <atomic>
+#include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -28,10 +30,55 @@ int check_launch(const char* what)
     return FP8_OK;
 }
 
-CastPath cast_path()
+// ---- tuning knobs -------------------------------------------------------------------------------
+static std::atomic<int> g_knob[FP8_KNOB_COUNT];
+static std::once_flag g_knob_once;
+
+static void seed_knobs()
 {
-    const char* e = getenv("FP8MM_CAST_PATH");     // read per call: a test may switch it
-    return (e && strcmp(e, "bits") == 0) ? kCastBits : kCastCvt;
+    const char* e;
+    if ((e = getenv("FP8MM_CAST_PATH")) && strcmp(e, "bits") == 0) g_knob[FP8_KNOB_CAST_PATH] = 1;
+    if ((e = getenv("FP8MM_TILE_N")) && (atoi(e) == 128 || atoi(e) == 256)) g_knob[FP8_KNOB_TILE_N] = atoi(e);
+    if ((e = getenv("FP8MM_GROUP_M")) && atoi(e) > 0) g_knob[FP8_KNOB_GROUP_M] = atoi(e);
+    if ((e = getenv("FP8MM_GEMM")) && e[0] == 'g') g_knob[FP8_KNOB_GEMM_KERNEL] = 1;
+    if ((e = getenv("FP8MM_SPLIT_K")) && atoi(e) > 0) g_knob[FP8_KNOB_SPLIT_K] = atoi(e);
+}
+
+int knob(int which)
+{
+    std::call_once(g_knob_once, seed_knobs);
+    return g_knob[which].load(std::memory_order_relaxed);
+}
+
+CastPath cast_path() { return knob(FP8_KNOB_CAST_PATH) == 1 ? kCastBits : kCastCvt; }
+
+int fill_gemm_args(const char* who, GemmArgs& g, const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB,
+                   int transB, void* C, int64_t M, int64_t N, int64_t K, int out_dtype, float sA, float sB,
+                   const float* sA_dev, const float* sB_dev, int flags, void* stream)
+{
+    clear_error();
+    if (flags & ~FP8_GEMM_MFMA8) return fail(FP8_ERR_INVALID_ARG, "%s: unknown flag bits 0x%x", who, flags & ~FP8_GEMM_MFMA8);
+    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return fail(FP8_ERR_INVALID_ARG, "%s: transA/transB must be 0 or 1", who);
+    if ((sA_dev == nullptr) != (sB_dev == nullptr)) return fail(FP8_ERR_INVALID_ARG, "%s: give both scales on the device or neither", who);
+    if (sA_dev && ((uintptr_t)sA_dev | (uintptr_t)sB_dev) % 4) return fail(FP8_ERR_INVALID_ARG, "%s: scale pointer is misaligned", who);
+    if (!valid_format(fmtA) || !valid_format(fmtB))
+        return fail(FP8_ERR_INVALID_ARG, "%s: operand formats (%d, %d) are not fp8_format_t", who, fmtA, fmtB);
+    if (!valid_dtype(out_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: out_dtype %d is not an fp8_dtype_t", who, out_dtype);
+    if (M < 0 || N < 0 || K < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (M=%lld N=%lld K=%lld)", who, (long long)M, (long long)N, (long long)K);
+    if (M > 0 && N > 0) {
+        if (!C) return fail(FP8_ERR_INVALID_ARG, "%s: C is NULL", who);
+        if (K > 0 && (!A || !B)) return fail(FP8_ERR_INVALID_ARG, "%s: A or B is NULL", who);
+        const uintptr_t osz = out_dtype == FP8_F32 ? 4 : 2;
+        if ((uintptr_t)C % osz) return fail(FP8_ERR_INVALID_ARG, "%s: C is not aligned to its element size", who);
+    }
+    g = GemmArgs{};
+    g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.fmtA = fmtA; g.fmtB = fmtB;
+    g.transA = transA != 0; g.transB = transB != 0; g.acc = (flags & FP8_GEMM_MFMA8) ? ACC_FP8 : ACC_F16;
+    g.ep.sA = sA; g.ep.sB = sB; g.ep.sA_dev = sA_dev; g.ep.sB_dev = sB_dev;
+    g.ep.out_kind = out_dtype;                      // fp8_dtype_t values are the first two output kinds
+    g.splits = 1;
+    g.stream = (hipStream_t)stream;
+    return FP8_OK;
 }
 
 }  // namespace fp8mm
@@ -42,7 +89,32 @@ extern "C" {
 
 const char* fp8_last_error(void) { return g_error; }
 
-const char* fp8_version(void) { return "fp8mm 0.1 (gfx950)"; }
+const char* fp8_version(void) { return "fp8mm 0.2 (gfx950)"; }
+
+int fp8_get_knob(int which)
+{
+    clear_error();
+    if (which < 0 || which >= FP8_KNOB_COUNT) return -fail(FP8_ERR_INVALID_ARG, "fp8_get_knob: %d is not an fp8_knob_t", which);
+    return knob(which);
+}
+
+int fp8_set_knob(int which, int value)
+{
+    clear_error();
+    if (which < 0 || which >= FP8_KNOB_COUNT) return -fail(FP8_ERR_INVALID_ARG, "fp8_set_knob: %d is not an fp8_knob_t", which);
+    bool ok = false;
+    switch (which) {
+        case FP8_KNOB_CAST_PATH: ok = value == 0 || value == 1; break;
+        case FP8_KNOB_TILE_N: ok = value == 0 || value == 128 || value == 256; break;
+        case FP8_KNOB_GROUP_M: ok = value >= 0 && value <= 4096; break;
+        case FP8_KNOB_GEMM_KERNEL: ok = value == 0 || value == 1; break;
+        case FP8_KNOB_SPLIT_K: ok = value >= 0 && value <= 64; break;
+    }
+    if (!ok) return -fail(FP8_ERR_INVALID_ARG, "fp8_set_knob: value %d is not valid for knob %d", value, which);
+    const int old = knob(which);                    // seeds from the environment first
+    g_knob[which].store(value, std::memory_order_relaxed);
+    return old;
+}
 
 int fp8_amax(const void* x, size_t n, int in_dtype, float* amax_out, void* stream)
 {
@@ -54,6 +126,22 @@ int fp8_amax(const void* x, size_t n, int in_dtype, float* amax_out, void* strea
     if ((uintptr_t)x % esz) return fail(FP8_ERR_INVALID_ARG, "fp8_amax: x is not aligned to its element size");
     if ((uintptr_t)amax_out % 4) return fail(FP8_ERR_INVALID_ARG, "fp8_amax: amax_out is not 4-byte aligned");
     return launch_amax(x, n, in_dtype, amax_out, (hipStream_t)stream);
+}
+
+int fp8_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out,
+                   void* workspace, void* stream)
+{
+    const char* who = "fp8_amax_scale";
+    clear_error();
+    if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
+    if (!valid_format(fmt)) return fail(FP8_ERR_INVALID_ARG, "%s: fmt %d is not an fp8_format_t", who, fmt);
+    if (!amax_out) return fail(FP8_ERR_INVALID_ARG, "%s: amax_out is NULL", who);
+    if (!workspace) return fail(FP8_ERR_INVALID_ARG, "%s: workspace is NULL", who);
+    if (n > 0 && !x) return fail(FP8_ERR_INVALID_ARG, "%s: x is NULL with n = %zu", who, n);
+    if ((uintptr_t)x % (in_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "%s: x is not aligned to its element size", who);
+    if (((uintptr_t)amax_out | (uintptr_t)scale_out | (uintptr_t)workspace) % 4)
+        return fail(FP8_ERR_INVALID_ARG, "%s: amax_out, scale_out and workspace must be 4-byte aligned", who);
+    return launch_amax_scale(x, n, in_dtype, fmt, amax_out, scale_out, workspace, (hipStream_t)stream);
 }
 
 float fp8_scale_from_amax_host(float amax, int fmt)
@@ -233,23 +321,10 @@ static int gemm_checked(const char* who, const uint8_t* A, int fmtA, const uint8
                         const float* sA_dev, const float* sB_dev, bool fp8_accumulate, void* stream,
                         bool transA = false, bool transB = false)
 {
-    clear_error();
-    if (!valid_format(fmtA) || !valid_format(fmtB))
-        return fail(FP8_ERR_INVALID_ARG, "%s: operand formats (%d, %d) are not fp8_format_t", who, fmtA, fmtB);
-    if (!valid_dtype(out_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: out_dtype %d is not an fp8_dtype_t", who, out_dtype);
-    if (M < 0 || N < 0 || K < 0) return fail(FP8_ERR_INVALID_ARG, "%s: negative dimension (M=%lld N=%lld K=%lld)", who, (long long)M, (long long)N, (long long)K);
-    if (M > 0 && N > 0) {
-        if (!C) return fail(FP8_ERR_INVALID_ARG, "%s: C is NULL", who);
-        if (K > 0 && (!A || !B)) return fail(FP8_ERR_INVALID_ARG, "%s: A or B is NULL", who);
-        const uintptr_t osz = out_dtype == FP8_F32 ? 4 : 2;
-        if ((uintptr_t)C % osz) return fail(FP8_ERR_INVALID_ARG, "%s: C is not aligned to its element size", who);
-    }
     GemmArgs g{};
-    g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.fmtA = fmtA; g.fmtB = fmtB;
-    g.transA = transA; g.transB = transB; g.acc = fp8_accumulate ? ACC_FP8 : ACC_F16;
-    g.ep.sA = sA; g.ep.sB = sB; g.ep.sA_dev = sA_dev; g.ep.sB_dev = sB_dev;
-    g.ep.out_kind = out_dtype;                      // fp8_dtype_t values are the first two output kinds
-    g.stream = (hipStream_t)stream;
+    if (int e = fill_gemm_args(who, g, A, fmtA, transA, B, fmtB, transB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev,
+                               fp8_accumulate ? FP8_GEMM_MFMA8 : 0, stream))
+        return e;
     return launch_gemm(g);
 }
 
@@ -289,13 +364,11 @@ int fp8_gemm_ex(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fm
                 void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
                 float sA, float sB, const float* sA_dev, const float* sB_dev, int flags, void* stream)
 {
-    clear_error();
-    if (flags & ~FP8_GEMM_MFMA8) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: unknown flag bits 0x%x", flags & ~FP8_GEMM_MFMA8);
-    if ((transA != 0 && transA != 1) || (transB != 0 && transB != 1)) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: transA/transB must be 0 or 1");
-    if ((sA_dev == nullptr) != (sB_dev == nullptr)) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: give both scales on the device or neither");
-    if (sA_dev && ((uintptr_t)sA_dev | (uintptr_t)sB_dev) % 4) return fail(FP8_ERR_INVALID_ARG, "fp8_gemm_ex: scale pointer is misaligned");
-    return gemm_checked("fp8_gemm_ex", A, fmtA, B, fmtB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev,
-                        (flags & FP8_GEMM_MFMA8) != 0, stream, transA != 0, transB != 0);
+    GemmArgs g{};
+    if (int e = fill_gemm_args("fp8_gemm_ex", g, A, fmtA, transA, B, fmtB, transB, C, M, N, K, out_dtype, sA, sB, sA_dev,
+                               sB_dev, flags, stream))
+        return e;
+    return launch_gemm(g);
 }
 
 int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
@@ -329,6 +402,7 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
     g.ep.amax_out = amax_out; g.ep.out_kind = out_kind;
     g.ep.a_per_row = nsA == M && M != 1;
     g.ep.b_per_col = nsB == N && N != 1;
+    g.splits = 1;
     g.stream = (hipStream_t)stream;
     return launch_gemm(g);
 }

@@ -19,9 +19,41 @@ namespace {
 // per workgroup the thousands of atomics on one cell cost a quarter of the run time).
 constexpr int kAmaxChunkVecs = kThreads * 8;
 
-template <int DT>
+// Last step of the amax kernels in their one-launch form (fp8_amax_scale): no cell has to be
+// cleared beforehand and the scale comes out of the same launch.  Every workgroup leaves its
+// maximum in ws[1 + blockIdx.x] and takes a ticket from ws[0]; the workgroup that draws the last
+// ticket reduces the gridDim.x partial maxima, writes amax and scale = fmt_max / amax, and puts the
+// ticket counter back to 0 for the next call.  r: the workgroup's maximum, valid in thread 0.
+__device__ __forceinline__ void amax_finish_ticket(unsigned r, unsigned* __restrict__ ws, int fmt,
+                                                   float* __restrict__ amax_out, float* __restrict__ scale_out)
+{
+    __shared__ bool last;
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&ws[1 + blockIdx.x], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();                                    // the partial maximum is visible before the ticket is
+        last = atomicAdd(&ws[0], 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!last) return;
+    __threadfence();
+    unsigned m = 0;
+    for (unsigned i = threadIdx.x; i < gridDim.x; i += kThreads) {
+        const unsigned p = __hip_atomic_load(&ws[1 + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        m = m > p ? m : p;
+    }
+    m = block_max_u32(m);
+    if (threadIdx.x == 0) {
+        const float a = as_f32(m);
+        *amax_out = a;
+        if (scale_out) *scale_out = scale_rule(a, fmt);
+        __hip_atomic_store(&ws[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int DT, bool TICKET>
 __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restrict__ x, size_t n,
-                                                           unsigned* __restrict__ out_bits)
+                                                           unsigned* __restrict__ out_bits, unsigned* __restrict__ ws,
+                                                           int fmt, float* __restrict__ scale_out)
 {
     constexpr int PV = Elem<DT>::per_vec;
     const u32x4* xv = (const u32x4*)x;
@@ -60,14 +92,20 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
         }
     }
     r = block_max_u32(r);
+    if (TICKET) {
+        __syncthreads();                                    // block_max_u32's LDS cells are used again below
+        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out);
+        return;
+    }
     // most workgroups find the cell already large enough and skip the atomic
     if (threadIdx.x == 0 && r > __hip_atomic_load(out_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out_bits, r);
 }
 
 // Any alignment the element type allows: one element per lane per step.
-template <int DT>
+template <int DT, bool TICKET>
 __global__ __launch_bounds__(kThreads) void amax_scalar_kernel(const void* __restrict__ x, size_t n,
-                                                              unsigned* __restrict__ out_bits)
+                                                              unsigned* __restrict__ out_bits, unsigned* __restrict__ ws,
+                                                              int fmt, float* __restrict__ scale_out)
 {
     const size_t stride = (size_t)gridDim.x * kThreads;
     unsigned r = 0;
@@ -76,7 +114,19 @@ __global__ __launch_bounds__(kThreads) void amax_scalar_kernel(const void* __res
         r = r > m ? r : m;
     }
     r = block_max_u32(r);
+    if (TICKET) {
+        __syncthreads();
+        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out);
+        return;
+    }
     if (threadIdx.x == 0) atomicMax(out_bits, r);
+}
+
+// n == 0 in the one-launch form: amax 0, scale by the degenerate rule.
+__global__ void amax_empty_kernel(int fmt, float* __restrict__ amax_out, float* __restrict__ scale_out)
+{
+    *amax_out = 0.0f;
+    if (scale_out) *scale_out = scale_rule(0.0f, fmt);
 }
 
 __global__ void scale_kernel(const float* __restrict__ amax, int fmt, float* __restrict__ out)
@@ -130,27 +180,47 @@ __global__ __launch_bounds__(kThreads) void quantize_scalar_kernel(const void* _
 
 }  // namespace
 
-int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream)
+namespace {
+// ws == nullptr: amax_out was cleared by the caller, workgroups raise it with atomics.
+// ws != nullptr: the one-launch form (see amax_finish_ticket); grids stay within kAmaxWorkgroupsMax.
+template <bool TICKET>
+void launch_amax_kernels(const void* x, size_t n, int in_dtype, unsigned* out, unsigned* ws, int fmt, float* scale_out,
+                         hipStream_t stream)
 {
-    unsigned* out = (unsigned*)amax_out;
-    hipLaunchKernelGGL(store_u32_kernel, dim3(1), dim3(1), 0, stream, out, 0u);
-    if (n == 0) return check_launch("amax init");
     if (aligned16(x)) {
         const size_t per_vec = in_dtype == FP8_F32 ? 4 : 8;
         const size_t nchunk = n / per_vec / kAmaxChunkVecs;
         const int grid = (int)(nchunk < 1 ? 1 : nchunk > (size_t)kAmaxBlocks ? (size_t)kAmaxBlocks : nchunk);
         if (in_dtype == FP8_F32)
-            hipLaunchKernelGGL(amax_vec_kernel<FP8_F32>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+            hipLaunchKernelGGL((amax_vec_kernel<FP8_F32, TICKET>), dim3(grid), dim3(kThreads), 0, stream, x, n, out, ws, fmt, scale_out);
         else
-            hipLaunchKernelGGL(amax_vec_kernel<FP8_BF16>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+            hipLaunchKernelGGL((amax_vec_kernel<FP8_BF16, TICKET>), dim3(grid), dim3(kThreads), 0, stream, x, n, out, ws, fmt, scale_out);
     } else {
-        const int grid = grid_for(n, 2048);
+        const int grid = grid_for(n, kAmaxBlocks);
         if (in_dtype == FP8_F32)
-            hipLaunchKernelGGL(amax_scalar_kernel<FP8_F32>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+            hipLaunchKernelGGL((amax_scalar_kernel<FP8_F32, TICKET>), dim3(grid), dim3(kThreads), 0, stream, x, n, out, ws, fmt, scale_out);
         else
-            hipLaunchKernelGGL(amax_scalar_kernel<FP8_BF16>, dim3(grid), dim3(kThreads), 0, stream, x, n, out);
+            hipLaunchKernelGGL((amax_scalar_kernel<FP8_BF16, TICKET>), dim3(grid), dim3(kThreads), 0, stream, x, n, out, ws, fmt, scale_out);
     }
+}
+}  // namespace
+
+int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream)
+{
+    unsigned* out = (unsigned*)amax_out;
+    hipLaunchKernelGGL(store_u32_kernel, dim3(1), dim3(1), 0, stream, out, 0u);
+    if (n == 0) return check_launch("amax init");
+    launch_amax_kernels<false>(x, n, in_dtype, out, nullptr, 0, nullptr, stream);
     return check_launch("amax");
+}
+
+int launch_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out, void* workspace,
+                      hipStream_t stream)
+{
+    static_assert((kAmaxBlocks + 1) * sizeof(unsigned) <= FP8_AMAX_WORKSPACE_BYTES, "ticket + one partial per workgroup");
+    if (n == 0) hipLaunchKernelGGL(amax_empty_kernel, dim3(1), dim3(1), 0, stream, fmt, amax_out, scale_out);
+    else launch_amax_kernels<true>(x, n, in_dtype, (unsigned*)amax_out, (unsigned*)workspace, fmt, scale_out, stream);
+    return check_launch("amax_scale");
 }
 
 float scale_from_amax_host(float amax, int fmt) { return scale_rule(amax, fmt); }

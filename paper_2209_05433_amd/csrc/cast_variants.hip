@@ -1,6 +1,6 @@
 // Variants of the amax / cast kernels for gfx950 (MI355X) that scaling recipes beyond the plain
 // two-pass per-tensor one build on (arXiv 2209.05433: Section 2 leaves the choice of the scaling
-// factor to software; Section 5 uses per-channel factors for weights; Section 4.1: activations,
+// factor to software; Section 4.2 uses per-channel factors for weights; Section 4.1: activations,
 // weights and activation gradients are all GEMM inputs, so a tensor is consumed in both storage
 // orders during training):
 //   - cast + amax in one pass, for a factor chosen beforehand from past maxima (3 bytes per bf16

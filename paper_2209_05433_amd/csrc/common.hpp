@@ -24,12 +24,19 @@ inline bool valid_dtype(int d) { return d == FP8_F32 || d == FP8_BF16; }
 //   kCastCvt  : the gfx950 v_cvt_pk_{fp8,bf8}_f32 instructions, with the saturation and
 //               special-value rules applied around them
 // The converter path is the default (it was checked against the bit path on all 2^32 inputs);
-// the environment variable FP8MM_CAST_PATH=bits|cvt, read per call, overrides it.
+// the knob FP8_KNOB_CAST_PATH overrides it.
 enum CastPath { kCastBits = 0, kCastCvt = 1, kCastBitsStrict = 2 /* non-saturating, kernels only */ };
 CastPath cast_path();
 
+// Current value of a tuning knob (fp8_knob_t).  The knobs are process-wide atomics, seeded once
+// from the environment (FP8MM_CAST_PATH, FP8MM_TILE_N, FP8MM_GROUP_M, FP8MM_GEMM, FP8MM_SPLIT_K)
+// and changed through fp8_set_knob(); no launch path reads the environment.
+int knob(int which);
+
 // ---- launchers (each enqueues on `stream` and returns a status) -------------------------
 int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream);
+int launch_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out, void* workspace,
+                      hipStream_t stream);
 float scale_from_amax_host(float amax, int fmt);
 int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream);
 int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,

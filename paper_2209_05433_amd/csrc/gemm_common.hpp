@@ -46,6 +46,8 @@ struct GemmArgs {
     bool transA, transB;          // A stored K x M / B stored N x K
     int acc;                      // ACC_*
     int tile_n;                   // width of the tiled kernel's tile: 256, or 128 (chosen by the dispatcher)
+    int splits, pairs_per_split;  // tiled kernel only: splits > 1 cuts K into slices of pairs_per_split stage pairs
+                                  // (128 bytes each); C is then a workspace of `splits` fp32 M x N matrices
     EpilogueArgs ep;
     hipStream_t stream;
 };
@@ -67,6 +69,24 @@ constexpr int TILE_M = 256, TILE_N = 256, TILE_K = 64;
 
 int launch_gemm(const GemmArgs& g);
 
+// The tiled kernel instance for g's storage orders and accumulation mode, with g.tile_n, g.splits,
+// g.pairs_per_split and g.ep.ragged_n as given (the caller has checked that the tiled kernel takes
+// the problem).
+int launch_tiled(const GemmArgs& g);
+
+// Split-K (gemm_splitk.hip): K cut into `splits` slices of pairs_per_split stage pairs.
+constexpr int kMaxSplitK = 64;
+struct SplitPlan { int splits, pairs_per_split, tile_n; };
+SplitPlan plan_splitk(const GemmArgs& g, int requested);
+size_t splitk_workspace_bytes(const GemmArgs& g, const SplitPlan& sp);
+int launch_gemm_splitk(const GemmArgs& g, const SplitPlan& sp, void* workspace);
+
+// Argument checks shared by the GEMM entry points that take the arguments of fp8_gemm_ex; fills g.
+// Returns FP8_OK or the status to return (the error text is set).
+int fill_gemm_args(const char* who, GemmArgs& g, const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB,
+                   int transB, void* C, int64_t M, int64_t N, int64_t K, int out_dtype, float sA, float sB,
+                   const float* sA_dev, const float* sB_dev, int flags, void* stream);
+
 // The dispatcher's decision for a problem with M, N, K > 0 (what launch_gemm acts on).
 enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3 };
 struct GemmPlan { int kernel; bool elementwise_stores; };
@@ -84,8 +104,9 @@ __device__ __forceinline__ void wave_amax_commit(unsigned bits, float* amax_out)
         const unsigned o = (unsigned)__shfl_xor((int)bits, d, 64);
         bits = o > bits ? o : bits;
     }
-    // most waves find the cell already large enough and skip the atomic
-    if ((threadIdx.x & 63) == 0 &&
+    // most waves find the cell already large enough and skip the atomic (the lane index comes from
+    // the execution mask count, not from threadIdx: nothing has to stay in a register for it)
+    if (__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) == 0 &&
         bits > __hip_atomic_load((unsigned*)amax_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
         atomicMax((unsigned*)amax_out, bits);
 }

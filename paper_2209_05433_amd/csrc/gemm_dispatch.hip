@@ -1,6 +1,6 @@
 // GEMM dispatcher and the generic kernel for gfx950 (MI355X).
 //
-// Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 128, 16-byte aligned
+// Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 16, 16-byte aligned
 // operands whose rows start on 16-byte boundaries) go to one of its instances; everything else is
 // computed by the generic kernel below: any shape, any alignment, every storage order, the same epilogue
 // (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
@@ -33,7 +33,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     __shared__ float Bs[GK][GT + 1];
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    const int64_t m0 = (int64_t)blockIdx.y * GT, n0 = (int64_t)blockIdx.x * GT;
+    // tiles are numbered row by row in the x dimension of the grid (the y dimension stops at 65 535)
+    const int64_t tiles_n = (N + GT - 1) / GT;
+    const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * GT, n0 = (int64_t)(blockIdx.x % tiles_n) * GT;
     float acc[4][4] = {};
     for (int64_t k0 = 0; k0 < K; k0 += GK) {
         for (int e = tid; e < GT * GK; e += 256) {
@@ -86,7 +88,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 template <int FA, int FB>
 int launch_generic(const GemmArgs& g)
 {
-    const dim3 grid((unsigned)((g.N + GT - 1) / GT), (unsigned)((g.M + GT - 1) / GT));
+    const int64_t tiles = ((g.N + GT - 1) / GT) * ((g.M + GT - 1) / GT);
+    if (tiles > 0x7fffffffll)
+        return fail(FP8_ERR_UNSUPPORTED, "gemm (generic kernel): %lld tiles of 64 x 64 exceed the grid limit", (long long)tiles);
+    const dim3 grid((unsigned)tiles);
     hipLaunchKernelGGL((gemm_generic_kernel<FA, FB>), grid, dim3(256), 0, g.stream, g.A, g.B, g.C, g.M, g.N, g.K,
                        g.ep, g.transA, g.transB);
     return check_launch("gemm (generic kernel)");
@@ -100,12 +105,8 @@ __global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
 
 __global__ void zero_cell_kernel(unsigned* p) { *p = 0u; }
 
-// FP8MM_GEMM=generic (environment, read per call) forces the generic kernel.
-bool force_generic()
-{
-    const char* e = getenv("FP8MM_GEMM");
-    return e && e[0] == 'g';
-}
+// The knob FP8_KNOB_GEMM_KERNEL = 1 forces the generic kernel.
+bool force_generic() { return knob(FP8_KNOB_GEMM_KERNEL) == 1; }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -118,32 +119,44 @@ GemmPlan plan_gemm(const GemmArgs& g)
     GemmPlan plan{GEMM_GENERIC, false};
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
-                        K < (1ll << 31) && ((M + TILE_M - 1) / TILE_M) * ((N + TILE_N - 1) / TILE_N) < (1ll << 31);
+                        K < (1ll << 31) &&
+                        // the grid holds one workgroup per tile: counted with the narrow tile, the larger count
+                        ((M + TILE_M - 1) / TILE_M) * ((N + TILE_N / 2 - 1) / (TILE_N / 2)) < (1ll << 31);
     // The tiled kernel works on 256 x 256 tiles and clips the last ones: loads of rows / columns
     // beyond the edge are redirected to existing ones and their outputs are not stored.  What it
-    // needs: K in whole pairs of stages; 16-byte aligned operands; rows of an N-contiguous B and
-    // of an M-contiguous A that start on 16-byte boundaries (N % 16, M % 16).  Rows of C (and a
+    // needs: K a multiple of 16 (it walks K in pairs of stages of 64 and fills a last, partial pair
+    // up with zeros; rows of a K-contiguous operand start every K bytes); 16-byte aligned operands;
+    // rows of an N-contiguous B and of an M-contiguous A that start on 16-byte boundaries (N % 16, M % 16).  Rows of C (and a
     // per-column factor vector) that do not start on 16-byte boundaries are served by the
     // element-wise stores of the epilogue: with B stored N x K any N goes (a vocabulary-sized
     // output layer, weights stored [out, in]).
     const bool c_lines = N % 16 == 0 && aligned16(g.C) && (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
-    const bool fast = !force_generic() && aligned16(g.A) && aligned16(g.B) && fits32 && K % (2 * TILE_K) == 0 &&
+    const bool fast = !force_generic() && aligned16(g.A) && aligned16(g.B) && fits32 && K % 16 == 0 &&
                       (g.transB || N % 16 == 0) && (!g.transA || M % 16 == 0);
     if (!fast) return plan;
     // Tile width.  One workgroup per compute unit (256 of them) runs at a time.  The 256 x 128
     // tile sustains about 0.88 of the rate of the 256 x 256 tile (measured on 8192 x 49152 x
     // 12288: 0.80-0.92 over the layouts and modes), so it is chosen when it fills the rounds of
     // workgroups that much better (4096 x 6144: 384 wide tiles = 1.5 rounds, 768 narrow ones = 3).
-    // FP8MM_TILE_N=128|256 (environment, read per call) overrides the choice.
+    // The knob FP8_KNOB_TILE_N = 128 | 256 overrides the choice.
     auto fill = [&](int64_t bn) {
         const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + bn - 1) / bn);
         return (double)tiles / (double)(((tiles + 255) / 256) * 256);
     };
-    const char* tn = getenv("FP8MM_TILE_N");
-    const bool narrow = tn ? atoi(tn) == 128 : 0.88 * fill(128) > fill(256);
+    const int tn = knob(FP8_KNOB_TILE_N);
+    const bool narrow = tn ? tn == 128 : 0.88 * fill(128) > fill(256);
     plan.kernel = narrow ? GEMM_TILED_128 : GEMM_TILED_256;
     plan.elementwise_stores = !c_lines;
     return plan;
+}
+
+int launch_tiled(const GemmArgs& g)
+{
+    typedef int (*tiled_fn)(const GemmArgs&);
+    static const tiled_fn table[4][2] = {
+        {FP8MM_TILED_NAME(0, 0), FP8MM_TILED_NAME(0, 1)}, {FP8MM_TILED_NAME(1, 0), FP8MM_TILED_NAME(1, 1)},
+        {FP8MM_TILED_NAME(2, 0), FP8MM_TILED_NAME(2, 1)}, {FP8MM_TILED_NAME(3, 0), FP8MM_TILED_NAME(3, 1)}};
+    return table[(g.transA ? 2 : 0) + (g.transB ? 1 : 0)][g.acc == ACC_FP8 ? 1 : 0](g);
 }
 
 int launch_gemm(const GemmArgs& g)
@@ -164,11 +177,8 @@ int launch_gemm(const GemmArgs& g)
         GemmArgs gt = g;
         gt.ep.ragged_n = plan.elementwise_stores ? 1 : 0;
         gt.tile_n = plan.kernel == GEMM_TILED_128 ? 128 : 256;
-        typedef int (*tiled_fn)(const GemmArgs&);
-        static const tiled_fn table[4][2] = {
-            {FP8MM_TILED_NAME(0, 0), FP8MM_TILED_NAME(0, 1)}, {FP8MM_TILED_NAME(1, 0), FP8MM_TILED_NAME(1, 1)},
-            {FP8MM_TILED_NAME(2, 0), FP8MM_TILED_NAME(2, 1)}, {FP8MM_TILED_NAME(3, 0), FP8MM_TILED_NAME(3, 1)}};
-        return table[(g.transA ? 2 : 0) + (g.transB ? 1 : 0)][g.acc == ACC_FP8 ? 1 : 0](gt);
+        gt.splits = 1;
+        return launch_tiled(gt);
     }
     if (g.fmtA == FP8_E4M3)
         return g.fmtB == FP8_E4M3 ? launch_generic<FP8_E4M3, FP8_E4M3>(g) : launch_generic<FP8_E4M3, FP8_E5M2>(g);

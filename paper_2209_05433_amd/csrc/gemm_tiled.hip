@@ -6,8 +6,9 @@
 // products are accumulated in fp32 by the matrix cores and the reciprocals of the scaling factors
 // are applied once per output (Section 2); the result is written as fp32, bf16 or FP8.
 //
-// Conditions (checked by the dispatcher): K a multiple of 128; 16-byte aligned A and B; N a multiple
-// of 16 if B is stored K x N, M a multiple of 16 if A is stored K x M.  M and N need not be
+// Conditions (checked by the dispatcher): K a multiple of 16; 16-byte aligned A and B; N a multiple
+// of 16 if B is stored K x N, M a multiple of 16 if A is stored K x M.  K is walked in pairs of
+// stages (128 bytes); where K is not a multiple of 128 the last pair is filled up with zero bytes.  M and N need not be
 // multiples of the tile: loads of rows / columns beyond the edge are redirected to existing ones,
 // their outputs are not stored.  Where the rows of C (or a per-column factor vector) do not start
 // on 16-byte boundaries the epilogue stores element by element (EpilogueArgs::ragged_n).
@@ -87,7 +88,18 @@ constexpr int NUM_XCD = 8;
 // wave instruction (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read
 // 7.3 clocks.
 __device__ __forceinline__ int swz_kc(int row) { return (row >> 1) & 7; }
-__device__ __forceinline__ int swz_mc(int krow) { return krow & 7; }
+// MN-contiguous slab: position in its K-row of the chunk whose index in memory is c (and, the map
+// being its own inverse, the memory chunk that sits at position c).  The XOR with the K-row spreads
+// the 8 K-rows that one 16-lane group of a transposing read touches over 8 chunk positions.  In a
+// 256-byte row (16 chunks, all 64 banks) the odd chunks also change halves: the two 16-lane
+// groups that are served together read neighbouring chunks (columns 0-15 and 16-31 of a block),
+// which then lie in different halves of the banks instead of sharing 32 of them.
+template <int CH>
+__device__ __forceinline__ int mc_chunk(int c, int krow)
+{
+    const int q = c ^ (krow & 7 & (CH - 1));
+    return CH == 16 ? q ^ ((q & 1) << 3) : q;
+}
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
 // vmcnt = bits 3:0 and 15:14, expcnt = 6:4, lgkmcnt = 11:8).
@@ -180,24 +192,39 @@ __device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, 
 #pragma unroll
         for (int t = 0; t < LW; ++t) {
             const int krow = (w * LW + t) * KR + l / CH;
-            const int chunk = (l % CH) ^ (swz_mc(krow) & (CH - 1));   // 16 columns; `valid` is a multiple of 16 here
+            const int chunk = mc_chunk<CH>(l % CH, krow);              // 16 columns; `valid` is a multiple of 16 here
             op.off[t] = (unsigned)krow * ld + min(chunk, (valid - 1) >> 4) * 16;
         }
         // lane = (r = l % 32, h): column r, K bytes 32h .. 32h+31, gathered by four transposing
         // reads of 8 K-rows x 16 columns per 16-lane group; lanes 2q and 2q+1 address K-row q
         const int t16 = l & 15, gq = (l >> 4) & 1;
         const int krow = 32 * h + (t16 >> 1);
-        op.rd = region + krow * EXT + (((wsel * (CH / 2) + gq) ^ (swz_mc(krow) & (CH - 1))) * 16) + (t16 & 1) * 8;
+        op.rd = region + krow * EXT + mc_chunk<CH>(wsel * (CH / 2) + gq, krow) * 16 + (t16 & 1) * 8;
     }
 }
 
 // Direct loads are written as inline assembly: the compiler then keeps no account of them and
 // inserts no waits of its own; completion is tracked by explicit vmcnt waits.  LDS placement:
-// M0 holds the wave-uniform base, lane i writes 16 bytes at M0 + 16 i.
+// M0 holds the wave-uniform base, lane i writes 16 bytes at M0 + 16 i.  M0 is an input operand of
+// the statement (physical-register constraint): the compiler loads it and knows it is in use.  The
+// s_nop is the wait state the hardware wants between a scalar write of M0 and its use here.
 __device__ __forceinline__ void direct_load(const uint8_t* base, unsigned off, unsigned lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(off), "s"(base), "s"(lds_addr) : "memory");
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "{m0}"(lds_addr) : "memory");
+}
+
+// Sixteen zero bytes in device memory, never written: where K is not a multiple of 128 the chunks of
+// the last stage pair that lie beyond K are fetched from here, so that every lane of every direct
+// load still issues (the wait counts stay those of the schedule) and the products of the padding
+// are 0 x 0.
+__device__ __attribute__((aligned(16))) uint8_t g_zero_chunk[16];
+
+// The same load with a full address per lane: the lane's chunk if it lies inside K, else the zeros.
+__device__ __forceinline__ void direct_load_or_zero(const uint8_t* base, unsigned off, bool valid, unsigned lds_addr)
+{
+    const uint8_t* p = valid ? base + off : g_zero_chunk;
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(p), "{m0}"(lds_addr) : "memory");
 }
 
 // One read-part of the fragment reads of stage kt for one operand: 16 bytes per lane of block blk
@@ -242,12 +269,15 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
     const int h = l >> 5;
 
     // reciprocal scales: per row in ra (with the per-tensor sB folded in), per column in cb
+    // (the by-value factors are copied out of the argument block first: a choice between two
+    // memory locations would force the block into scratch memory)
+    const float sA_host = ep.sA, sB_host = ep.sB;
     float ra[4];
     {
-        const double b = BVEC ? 1.0 : (double)scale_value(ep.sB_dev, ep.sB);
+        const double b = BVEC ? 1.0 : (double)scale_value(ep.sB_dev, sB_host);
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-            const float a = ep.a_per_row ? ep.sA_dev[min(wave_m0 + mb * 32 + (l & 31), M - 1)] : scale_value(ep.sA_dev, ep.sA);
+            const float a = ep.a_per_row ? ep.sA_dev[min(wave_m0 + mb * 32 + (l & 31), M - 1)] : scale_value(ep.sA_dev, sA_host);
             ra[mb] = (float)(1.0 / ((double)a * b));
         }
     }
@@ -350,7 +380,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
 template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
-    int M, int N, int K, EpilogueArgs ep, int group_m)
+    int M, int N, int K, EpilogueArgs ep, int group_m, int splits, int pairs_per_split)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     constexpr int BN = 64 * NB;                             // tile width
@@ -367,14 +397,26 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int wm = w >> 1, wn = w & 1;
-    const TileMap tile = map_tile(blockIdx.x, (M + BM - 1) / BM, (N + BN - 1) / BN, group_m);
+    // K is walked in pairs of stages (128 bytes); a last pair that reaches beyond K is filled up
+    // with zeros.  With splits > 1 the workgroup computes one slice of K (pairs_per_split pairs,
+    // the last slice what is left) of its tile and writes the fp32 sums, without the scales, into
+    // slice `split` of C, which is then a workspace of `splits` M x N matrices.
+    int bid = blockIdx.x, split = 0;
+    if (splits > 1) { split = bid % splits; bid /= splits; }
+    const TileMap tile = map_tile(bid, (M + BM - 1) / BM, (N + BN - 1) / BN, group_m);
     const int m0 = tile.tm * BM, n0 = tile.tn * BN;
-    const int KT = K / BK;
+    const int pair0 = split * pairs_per_split;
+    const int KT = 2 * min(pairs_per_split, (K + 2 * BK - 1) / (2 * BK) - pair0);
+    const int kend = K - pair0 * 2 * BK;                    // bytes of K from the start of the slice to the end of K
+    const bool ktail = kend < KT * BK;                      // the slice ends in a partly filled pair
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
+    C = (uint8_t*)C + (size_t)split * (size_t)M * (size_t)N * 4;
 
     Operand opA, opB;
-    operand_setup<A_KC, BM>(opA, A, A_KC ? (unsigned)K : (unsigned)M, m0, min(BM, M - m0), A_REGION, w, l, wm);
-    operand_setup<B_KC, BN>(opB, B, B_KC ? (unsigned)K : (unsigned)N, n0, min(BN, N - n0), B_REGION, w, l, wn);
+    operand_setup<A_KC, BM>(opA, A + (size_t)pair0 * 2 * BK * (A_KC ? 1 : (size_t)M), A_KC ? (unsigned)K : (unsigned)M, m0,
+                            min(BM, M - m0), A_REGION, w, l, wm);
+    operand_setup<B_KC, BN>(opB, B + (size_t)pair0 * 2 * BK * (B_KC ? 1 : (size_t)N), B_KC ? (unsigned)K : (unsigned)N, n0,
+                            min(BN, N - n0), B_REGION, w, l, wn);
 
     // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
     // the steps -5 .. -1).  Step s issues, in this order:
@@ -426,13 +468,27 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         }
     };
     // load t of this wave for a pair slab (loads-per-wave lw: the slab takes 4 lw KB) / a stage slab
-    auto issue_kc = [&](const Operand& op, int lw, int pair, int slot, int t) {
-        direct_load(op.tile + (size_t)pair * 2 * BK, op.off[t],
-                    lds0 + op.region + slot * (lw * 4096) + w * (lw * 1024) + t * 1024);
+    // TAIL (compile-time, never in the steady-state steps): the slice may end in a partly filled
+    // pair; then the lane's chunk is tested against the end of K (see direct_load_or_zero).
+    auto issue_kc = [&](auto tail_tag, const Operand& op, int lw, int pair, int slot, int t) {
+        const unsigned lds = lds0 + op.region + slot * (lw * 4096) + w * (lw * 1024) + t * 1024;
+        if (decltype(tail_tag)::value && ktail) {
+            // row of the slab = (w lw + t) 8 + l / 8, chunk = (l % 8) ^ swz_kc(row)
+            const int chunk = (l & 7) ^ (((w * lw + t) * 4 + (l >> 4)) & 7);
+            direct_load_or_zero(op.tile + (size_t)pair * 2 * BK, op.off[t], pair * 2 * BK + chunk * 16 < kend, lds);
+        } else {
+            direct_load(op.tile + (size_t)pair * 2 * BK, op.off[t], lds);
+        }
     };
-    auto issue_mc = [&](const Operand& op, int lw, int st, int t) {
-        direct_load(op.tile + (size_t)st * BK * op.ld, op.off[t],
-                    lds0 + op.region + (st & (MC_SLOTS - 1)) * (lw * 4096) + w * (lw * 1024) + t * 1024);
+    auto issue_mc = [&](auto tail_tag, const Operand& op, int lw, int st, int t) {
+        const unsigned lds = lds0 + op.region + (st & (MC_SLOTS - 1)) * (lw * 4096) + w * (lw * 1024) + t * 1024;
+        if (decltype(tail_tag)::value && ktail) {
+            // K-row of the slab = (w lw + t) KR + l / CH with KR = 16 / lw rows per load, CH = 4 lw chunks per row
+            const int krow = (w * lw + t) * (16 / lw) + l / (4 * lw);
+            direct_load_or_zero(op.tile + (size_t)st * BK * op.ld, op.off[t], st * BK + krow < kend, lds);
+        } else {
+            direct_load(op.tile + (size_t)st * BK * op.ld, op.off[t], lds);
+        }
     };
     // the loads of step s that fall into part j; sa, sb = ring slots the K-contiguous slabs of
     // this step go to (the slots of the pair that stage s ends; for A in an even step when both
@@ -443,18 +499,19 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     auto issue_part = [&](auto full_tag, int s, bool odd, int j, int sa, int sb) {
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr int H = P / 2;
+        const std::integral_constant<bool, !FULL> tail;
         if (A_KC && B_KC) {
             if (odd) {
                 const int p = kc_pair_of(s, B_RING);
                 if (j < H && (FULL || pair_valid(p))) {
 #pragma unroll
-                    for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
+                    for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(tail, opB, B_KC_LOADS, p, sb, t);
                 }
             } else {
                 const int p = s / 2 + A_RING - 1;
                 if (FULL || pair_valid(p)) {
 #pragma unroll
-                    for (int t = j * (A_KC_LOADS / P); t < (j + 1) * (A_KC_LOADS / P); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
+                    for (int t = j * (A_KC_LOADS / P); t < (j + 1) * (A_KC_LOADS / P); ++t) issue_kc(tail, opA, A_KC_LOADS, p, sa, t);
                 }
             }
         } else if (j < H) {
@@ -463,14 +520,14 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
                     const int p = kc_pair_of(s, A_RING);
                     if (FULL || pair_valid(p)) {
 #pragma unroll
-                        for (int t = j * (A_KC_LOADS / H); t < (j + 1) * (A_KC_LOADS / H); ++t) issue_kc(opA, A_KC_LOADS, p, sa, t);
+                        for (int t = j * (A_KC_LOADS / H); t < (j + 1) * (A_KC_LOADS / H); ++t) issue_kc(tail, opA, A_KC_LOADS, p, sa, t);
                     }
                 }
                 if (B_KC) {
                     const int p = kc_pair_of(s, B_RING);
                     if (FULL || pair_valid(p)) {
 #pragma unroll
-                        for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(opB, B_KC_LOADS, p, sb, t);
+                        for (int t = j * (B_KC_LOADS / H); t < (j + 1) * (B_KC_LOADS / H); ++t) issue_kc(tail, opB, B_KC_LOADS, p, sb, t);
                     }
                 }
             }
@@ -478,11 +535,11 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             const int jj = j - H;
             if (!A_KC) {
 #pragma unroll
-                for (int t = jj * (A_MC_LOADS / H); t < (jj + 1) * (A_MC_LOADS / H); ++t) issue_mc(opA, A_MC_LOADS, s + 4, t);
+                for (int t = jj * (A_MC_LOADS / H); t < (jj + 1) * (A_MC_LOADS / H); ++t) issue_mc(tail, opA, A_MC_LOADS, s + 4, t);
             }
             if (!B_KC) {
 #pragma unroll
-                for (int t = jj * (B_MC_LOADS / H); t < (jj + 1) * (B_MC_LOADS / H); ++t) issue_mc(opB, B_MC_LOADS, s + 4, t);
+                for (int t = jj * (B_MC_LOADS / H); t < (jj + 1) * (B_MC_LOADS / H); ++t) issue_mc(tail, opB, B_MC_LOADS, s + 4, t);
             }
         }
     };
@@ -598,7 +655,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     };
 
     // Prologue: steps -5 .. -1 of the same schedule, then stage 0 visible and its frags read.
-    // KT is even and >= 2.
+    // KT is even and >= 2 (a stage beyond K holds zeros).
     v8i af0[4], bf0[NB], af1[4], bf1[NB];
     const std::integral_constant<bool, true> full;
     const std::integral_constant<bool, false> checked;
@@ -647,30 +704,31 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     __builtin_amdgcn_s_waitcnt(0xC07F);
     __builtin_amdgcn_s_barrier();                           // every wave is done with the operand slabs
     const int wave_m0 = m0 + wm * 128, wave_n0 = n0 + wn * (32 * NB);
+    // The lane index is taken afresh from the execution mask count: values derived from the one
+    // computed before the K loop would have to stay in registers (or be spilled) all through it.
+    const int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
     if (ep.b_per_col) {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            case OUT_BF16: epilogue<OUT_BF16, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            default: epilogue<OUT_E5M2, true, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
         }
     } else {
         switch (ep.out_kind) {
-            case OUT_F32: epilogue<OUT_F32, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_BF16: epilogue<OUT_BF16, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            case OUT_E4M3: epilogue<OUT_E4M3, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
-            default: epilogue<OUT_E5M2, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, l); break;
+            case OUT_F32: epilogue<OUT_F32, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            case OUT_BF16: epilogue<OUT_BF16, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            case OUT_E4M3: epilogue<OUT_E4M3, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
+            default: epilogue<OUT_E5M2, false, NB>(acc, smem, ep, C, M, N, wave_m0, wave_n0, w, le); break;
         }
     }
 }
 
 // ---- launch ------------------------------------------------------------------------------
-// FP8MM_GROUP_M (environment, read per call) sets the number of tile rows per band of the tile
-// order (default GROUP_M).
+// The knob FP8_KNOB_GROUP_M sets the number of tile rows per band of the tile order (0: GROUP_M).
 int group_m_setting()
 {
-    const char* e = getenv("FP8MM_GROUP_M");
-    const int v = e ? atoi(e) : 0;
+    const int v = knob(FP8_KNOB_GROUP_M);
     return v > 0 ? v : GROUP_M;
 }
 
@@ -691,8 +749,11 @@ int launch_fast(const GemmArgs& g)
     }
     constexpr int BN = 64 * NB;
     const int tiles = (int)(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN));
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
-                       (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting());
+    const int pairs = (int)((g.K + 2 * BK - 1) / (2 * BK));
+    const int splits = g.splits > 1 ? g.splits : 1;
+    hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
+                       (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting(), splits,
+                       splits > 1 ? g.pairs_per_split : pairs);
     return check_launch("gemm (tiled kernel)");
 }
 

@@ -83,12 +83,52 @@ def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
     assert plan(0, 1, 8192, 50257, 12288) == T256 | EW           # vocabulary-sized N with weights stored [out, in]
     assert plan(0, 0, 8192, 50257, 12288) == FMA                 # ... stored [in, out]: rows of B start anywhere
     assert plan(1, 0, 50257, 12288, 8192) == FMA                 # rows of an M-contiguous A start anywhere
-    assert plan(0, 0, 512, 512, 448) == FMA                      # K not a multiple of 128
+    assert plan(0, 0, 512, 512, 448) in (T256, T128)             # K = 7 stages of 64: the last stage pair is half zeros
+    assert plan(0, 0, 8192, 12288, 12352) == T256                # K = 64 x odd
+    assert plan(0, 1, 8192, 12288, 12304) == T256                # K a multiple of 16 only
+    assert plan(0, 0, 512, 512, 440) == FMA                      # K not a multiple of 16: rows of A start anywhere
     assert plan(0, 0, 512, 512, 512, a=A + 4) == FMA             # operand not 16-byte aligned
     assert plan(0, 0, 4096, 4096, 512, c=C + 2) == T256 | EW     # output not 16-byte aligned
     assert plan(0, 0, 4096, 4096, 512, sb=C + 4) == T256 | EW    # per-column factors not 16-byte aligned
     assert plan(0, 0, 0, 5, 5) == fp8.FP8_PLAN_NO_GEMM and plan(0, 0, 5, 5, 0) == fp8.FP8_PLAN_NO_GEMM
     assert plan(2, 0, 5, 5, 5) == -fp8.FP8_ERR_INVALID_ARG and plan(0, 0, -1, 5, 5) == -fp8.FP8_ERR_INVALID_ARG
+
+
+def test_knobs_round_trip_and_reject_bad_values():
+    assert fp8.fp8_get_knob(fp8.FP8_KNOB_TILE_N) == 0
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_TILE_N, 128) == 0
+    assert fp8.fp8_get_knob(fp8.FP8_KNOB_TILE_N) == 128
+    L = fp8.lib()
+    A, B, C = 1 << 20, 1 << 24, 1 << 28
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_TILED_256x128
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_TILE_N, 0) == 128
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_TILED_256x256
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 1) == 0
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_FMA_KERNEL
+    fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 0)
+    for knob, bad in ((fp8.FP8_KNOB_TILE_N, 64), (fp8.FP8_KNOB_CAST_PATH, 2), (fp8.FP8_KNOB_SPLIT_K, 65), (99, 0)):
+        with pytest.raises(fp8.Fp8Error):
+            fp8.fp8_set_knob(knob, bad)
+
+
+def test_splitk_workspace_size_is_slices_times_the_fp32_output():
+    size = fp8.fp8_gemm_splitk_workspace_size
+    assert size(1024, 1024, 65536, 1, 0, 0) == 16 * 1024 * 1024 * 4        # 16 tiles -> 16 slices of 32 stage pairs
+    assert size(1024, 1024, 65536, 1, 0, 8) == 8 * 1024 * 1024 * 4
+    assert size(1024, 1024, 65536, 1, 0, 1) == 0                           # one slice: the plain kernel, no workspace
+    assert size(8192, 49152, 12288, 0, 0, 0) == 0                          # enough tiles to fill the chip
+    assert size(256, 256, 256, 0, 0, 0) == 0                               # too short a K to cut
+    assert size(256, 256, 300, 0, 0, 4) == 0                               # not a problem of the tiled kernel
+    assert size(256, 256, 384, 0, 0, 64) == 3 * 256 * 256 * 4              # never more slices than stage pairs
+    assert size(0, 5, 5, 0, 0, 0) == 0 and size(5, 5, 5, 0, 0, 65) == 0
+    L = fp8.lib()
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.addressof(buf)
+    INV = fp8.FP8_ERR_INVALID_ARG
+    assert L.fp8_gemm_splitk(p, 0, 0, p, 0, 0, p, 4, 4, 4, 0, 1.0, 1.0, None, None, 0, 65, None, 0, None) == INV
+    assert L.fp8_gemm_splitk(p, 0, 0, p, 0, 0, p, 4, 4, 4, 0, 1.0, 1.0, None, None, 0, 2, p + 2, 64, None) == INV
+    assert L.fp8_gemm_splitk(p, 0, 0, p, 0, 0, p, 1024, 1024, 65536, 0, 1.0, 1.0, None, None, 0, 8, p, 64, None) == INV
+    assert "workspace of 33554432 bytes" in fp8.fp8_last_error()
 
 
 def test_version_and_error_strings():

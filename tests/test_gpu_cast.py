@@ -148,6 +148,53 @@ def test_device_scale_pipeline_without_host_round_trip(fmt):
     assert (got & 0x7F).max() == (0x7E if fmt == fp8.FP8_E4M3 else 0x7B)
 
 
+@pytest.mark.parametrize("fmt", FMTS)
+def test_amax_scale_in_one_launch_equals_the_oracle_and_reuses_its_workspace(fmt):
+    """fp8_amax_scale: amax and scale out of one launch, no cell cleared beforehand.  One workspace is
+    used for a sequence of calls of very different sizes (1024 workgroups, then 1, then a few): a
+    partial maximum left over from a larger call must not enter a smaller one, and the ticket must
+    come back to zero every time.  Also NaN / inf / empty / unaligned inputs, and amax alone."""
+    rng = np.random.default_rng(19)
+    ws = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    ws[1:] = 0x7F000000                                 # stale partials (a huge magnitude) must never be read
+    amax = torch.full((1,), -1.0, device="cuda")
+    scale = torch.full((1,), -1.0, device="cuda")
+    sizes = [(1 << 24) + 5, 3, 1 << 20, 0, 70_001, 1 << 24, 9]
+    for k, n in enumerate(sizes):
+        x = (rng.standard_normal(n) * np.float32(2.0 ** (8 - 3 * k))).astype(np.float32)     # later calls hold smaller values
+        for h in (x, synth.to_bf16_bits(x)):
+            d = to_dev(h) if n else torch.empty(0, dtype=torch.float32 if h.dtype == np.float32 else torch.bfloat16, device="cuda")
+            fp8.fp8_amax_scale(d, fmt, amax, scale, ws)
+            torch.cuda.synchronize()
+            a = oracle.amax(h)
+            assert amax.item() == a, (n, h.dtype)
+            assert np.float32(scale.item()) == oracle.scale_from_amax(a, fmt), (n, h.dtype)
+            assert ws[0].item() == 0
+    x = np.ones(300_000, dtype=np.float32)
+    x[123_456] = -np.inf
+    fp8.fp8_amax_scale(to_dev(x), fmt, amax, scale, ws)
+    assert amax.item() == np.inf and scale.item() == 1.0
+    x[7] = np.nan
+    fp8.fp8_amax_scale(to_dev(synth.to_bf16_bits(x)), fmt, amax, scale, ws)
+    assert np.isnan(amax.item()) and scale.item() == 1.0
+    # unaligned input (element path) and amax without a scale
+    buf = to_dev(np.arange(10_000, dtype=np.float32) - 5000.0)
+    scale.fill_(-3.0)
+    fp8.fp8_amax_scale(buf[1:9_998], fmt, amax, None, ws)
+    torch.cuda.synchronize()
+    assert amax.item() == 4999.0 and scale.item() == -3.0 and ws[0].item() == 0
+    # the pipeline with the one-launch form, bit for bit
+    h = synth.config2(1 << 22)
+    xd = to_dev(h)
+    q = torch.empty(h.size, dtype=torch.uint8, device="cuda")
+    fp8.fp8_amax_scale(xd, fmt, amax, scale, ws)
+    fp8.fp8_quantize_dscale(xd, fmt, scale, q)
+    torch.cuda.synchronize()
+    s_ref = oracle.scale_from_amax(oracle.amax(h), fmt)
+    assert np.float32(scale.item()) == s_ref
+    assert np.array_equal(q.cpu().numpy(), oracle.quantize(h, fmt, s_ref))
+
+
 def test_device_scale_rule_degenerate_cases():
     for a in (0.0, np.inf, np.nan, 1e-45, 3.0, 4567.0):
         for fmt in FMTS:

@@ -15,7 +15,7 @@ import torch
 import oracle
 import paper_2209_05433_amd as fp8
 from workloads import synth
-from gpu_util import to_dev, out_to_f64
+from gpu_util import to_dev, out_to_f64, knob
 from test_gpu_gemm import random_codes, sample_points, REL, MODES
 
 pytestmark = pytest.mark.gpu
@@ -294,9 +294,9 @@ RAGGED = [(300, 272, 256), (8, 16, 128), (1, 1008, 384), (1000, 48, 128), (513, 
 def tile_n(request):
     """Both tile widths of the tiled kernel, whatever the dispatcher would choose."""
     import os
-    os.environ["FP8MM_TILE_N"] = request.param
+    old = fp8.fp8_set_knob(fp8.FP8_KNOB_TILE_N, int(request.param))
     yield request.param
-    del os.environ["FP8MM_TILE_N"]
+    fp8.fp8_set_knob(fp8.FP8_KNOB_TILE_N, old)
 
 
 @pytest.mark.parametrize("mode", MODES)
@@ -351,11 +351,8 @@ def test_edge_tiles_agree_with_the_generic_kernel_exactly_on_integers(tile_n):
             D, amax = run_fused(A, E4M3, B, E4M3, fp8.FP8_OUT_F32, np.float32(0.5), np.float32(4.0), want_amax=True, mode=mode)
             assert np.array_equal(out_to_f64(D), S / 2.0), (M, N, K, mode)
             assert float(amax) == np.max(np.abs(S / 2.0))
-        os.environ["FP8MM_GEMM"] = "generic"
-        try:
+        with knob(fp8.FP8_KNOB_GEMM_KERNEL, 1):
             G, _ = run_fused(A, E4M3, B, E4M3, fp8.FP8_OUT_F32, np.float32(0.5), np.float32(4.0))
-        finally:
-            del os.environ["FP8MM_GEMM"]
         assert np.array_equal(out_to_f64(G), S / 2.0)
 
 

@@ -181,3 +181,30 @@ def test_unscale_channels_is_row_and_column_scaling_of_the_operands():
     # bound with vectors: 2^-20 * alpha_ij * T_ij + ulp/2
     _, bound = oracle.gemm_bound(S, T, sA, sB, F32)
     assert np.allclose(bound, 2.0 ** -20 * alpha * T + 0.5 * oracle.ulp(c, F32), rtol=1e-15)
+
+
+def test_block_sums_equal_the_blockwise_sums_of_the_row_reference():
+    """gemm_block_sums (the whole-matrix check of the large workloads) against the plain
+    definition: S and T of every output from gemm_rows, multiplied by r and added up block by block
+    with Python loops; ragged last block, both signs, all four format mixes."""
+    rng = np.random.default_rng(41)
+    M, N, K, block = 9, 23, 37, 5
+    for fmtA in (oracle.E4M3, oracle.E5M2):
+        for fmtB in (oracle.E4M3, oracle.E5M2):
+            A = rng.integers(0, 0x70 if fmtA == oracle.E4M3 else 0x60, (M, K)).astype(np.uint8) | \
+                (rng.integers(0, 2, (M, K)).astype(np.uint8) << 7)
+            B = rng.integers(0, 0x70 if fmtB == oracle.E4M3 else 0x60, (K, N)).astype(np.uint8) | \
+                (rng.integers(0, 2, (K, N)).astype(np.uint8) << 7)
+            r = rng.choice([-1.0, 1.0], N)
+            S, T = oracle.gemm_rows(A, fmtA, B, fmtB)
+            SR, TR = oracle.gemm_block_sums(A, fmtA, B, fmtB, r, block)
+            nb = (N + block - 1) // block
+            assert SR.shape == (M, nb) and TR.shape == (M, nb)
+            for i in range(M):
+                for t in range(nb):
+                    want_s = sum(r[j] * S[i, j] for j in range(t * block, min(N, (t + 1) * block)))
+                    want_t = sum(T[i, j] for j in range(t * block, min(N, (t + 1) * block)))
+                    assert abs(SR[i, t] - want_s) <= 1e-12 * want_t + 1e-300
+                    assert abs(TR[i, t] - want_t) <= 1e-12 * want_t + 1e-300
+    with pytest.raises(ValueError):
+        oracle.gemm_block_sums(np.full((2, 2), 0x7F, np.uint8), oracle.E4M3, np.zeros((2, 2), np.uint8), oracle.E4M3, [1, 1], 2)
