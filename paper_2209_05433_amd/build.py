@@ -1,4 +1,5 @@
-"""Builds libfp8mm.so (the HIP kernels and their C ABI) for gfx950 with hipcc, in-tree.
+"""Builds libfp8mm.so (the HIP kernels and their C ABI) and libfp8probes.so (the measurement probes
+of bench.py) for gfx950 with hipcc, in-tree.
 
 Every translation unit is compiled to an object of its own, in parallel; the tiled GEMM source is
 compiled eight times, once per pair of operand storage orders (-DFP8MM_LAYOUT=0..3) and
@@ -15,6 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfp8mm.so")
+PROBES_LIB = os.path.join(PKG, "libfp8probes.so")     # measurement probes for bench.py, not part of the product library
 
 # (source, extra defines, object name)
 UNITS = [("gemm_tiled.hip", ["-DFP8MM_LAYOUT=%d" % k, "-DFP8MM_ACC=%d" % a], "gemm_tiled_l%d_a%d.o" % (k, a))
@@ -57,6 +59,7 @@ def build(verbose: bool = False) -> str:
     inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     jobs = [[hipcc(), *HIPCC_FLAGS, *inc, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ, obj)]
             for src, defs, obj in UNITS]
+    jobs.append([hipcc(), *HIPCC_FLAGS, *inc, "-shared", os.path.join(CSRC, "probes.hip"), "-o", PROBES_LIB])
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         list(ex.map(lambda c: _run(c, verbose), jobs))
     _run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB,

@@ -88,17 +88,24 @@ constexpr int NUM_XCD = 8;
 // wave instruction (the conflict-free rate, 64 banks of 4 bytes) and a transposing 8-byte read
 // 7.3 clocks.
 __device__ __forceinline__ int swz_kc(int row) { return (row >> 1) & 7; }
-// MN-contiguous slab: position in its K-row of the chunk whose index in memory is c (and, the map
-// being its own inverse, the memory chunk that sits at position c).  The XOR with the K-row spreads
-// the 8 K-rows that one 16-lane group of a transposing read touches over 8 chunk positions.  In a
-// 256-byte row (16 chunks, all 64 banks) the odd chunks also change halves: the two 16-lane
-// groups that are served together read neighbouring chunks (columns 0-15 and 16-31 of a block),
-// which then lie in different halves of the banks instead of sharing 32 of them.
+// MN-contiguous slab: mc_pos = position in its K-row of the chunk whose index in memory is c; mc_mem
+// = the memory chunk that sits at position p (the inverse map, used on the global side of the direct
+// loads, whose LDS placement is fixed).  The XOR with the K-row spreads the 8 K-rows that one 16-lane
+// group of a transposing read touches over 8 chunk positions.  In a 256-byte row (16 chunks, all 64
+// banks) the odd memory chunks also change halves: the two 16-lane groups that are served
+// together read neighbouring chunks (columns 0-15 and 16-31 of a block), which then lie in
+// different halves of the banks instead of sharing 32 of them.
 template <int CH>
-__device__ __forceinline__ int mc_chunk(int c, int krow)
+__device__ __forceinline__ int mc_pos(int c, int krow)
 {
-    const int q = c ^ (krow & 7 & (CH - 1));
-    return CH == 16 ? q ^ ((q & 1) << 3) : q;
+    const int p = c ^ (krow & 7 & (CH - 1));
+    return CH == 16 ? p ^ ((c & 1) << 3) : p;
+}
+template <int CH>
+__device__ __forceinline__ int mc_mem(int p, int krow)
+{
+    const int c = p ^ (krow & 7 & (CH - 1));               // right but for bit 3, which does not enter bit 0
+    return CH == 16 ? c ^ ((c & 1) << 3) : c;
 }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -192,14 +199,14 @@ __device__ __forceinline__ void operand_setup(Operand& op, const uint8_t* base, 
 #pragma unroll
         for (int t = 0; t < LW; ++t) {
             const int krow = (w * LW + t) * KR + l / CH;
-            const int chunk = mc_chunk<CH>(l % CH, krow);              // 16 columns; `valid` is a multiple of 16 here
+            const int chunk = mc_mem<CH>(l % CH, krow);                // 16 columns; `valid` is a multiple of 16 here
             op.off[t] = (unsigned)krow * ld + min(chunk, (valid - 1) >> 4) * 16;
         }
         // lane = (r = l % 32, h): column r, K bytes 32h .. 32h+31, gathered by four transposing
         // reads of 8 K-rows x 16 columns per 16-lane group; lanes 2q and 2q+1 address K-row q
         const int t16 = l & 15, gq = (l >> 4) & 1;
         const int krow = 32 * h + (t16 >> 1);
-        op.rd = region + krow * EXT + mc_chunk<CH>(wsel * (CH / 2) + gq, krow) * 16 + (t16 & 1) * 8;
+        op.rd = region + krow * EXT + mc_pos<CH>(wsel * (CH / 2) + gq, krow) * 16 + (t16 & 1) * 8;
     }
 }
 

@@ -1,24 +1,50 @@
 """Small driver for profiler runs (rocprofv3 --kernel-trace / --pmc): launches a plain copy of
 known size (the calibration kernel for HBM byte counters) and then the kernels of one workload a
-few times, with random FP8 bytes / bf16 values already resident in HBM.
+few times, on the data bench.py times (--data synth: the workload's seeded synthetic tensors, cast
+to FP8 by the library itself) or on uniformly random FP8 codes (--data random).
 
-    python3 -m paper_2209_05433_amd.profile_run --workload ffn_up_175b --mode f16 --iters 3
-    python3 -m paper_2209_05433_amd.profile_run --workload quantize_only --iters 3
-    python3 -m paper_2209_05433_amd.profile_run --workload cast_variants --iters 3
+    python3 profile_run.py --workload ffn_up_175b --mode f16 --iters 3
+    python3 profile_run.py --workload quantize_only --iters 3
+    python3 profile_run.py --workload cast_variants --iters 3
 """
 from __future__ import annotations
 
 import argparse
+import os
+import sys
 
+import numpy as np
 import torch
 
-from . import binding as fp8
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
-SHAPES = {  # name: (M, N, K, fmtA, out dtype)
-    "ffn_up_175b": (8192, 49152, 12288, 0, torch.bfloat16),
-    "dgrad_175b": (8192, 12288, 49152, 1, torch.float32),
-    "small_gpt_fwd": (4096, 6144, 2048, 0, torch.bfloat16),
+import paper_2209_05433_amd as fp8
+from workloads import synth
+
+SHAPES = {  # name: (M, N, K, fmtA, out dtype, generator)
+    "ffn_up_175b": (8192, 49152, 12288, 0, torch.bfloat16, synth.config4),
+    "dgrad_175b": (8192, 12288, 49152, 1, torch.float32, synth.config5),
+    "small_gpt_fwd": (4096, 6144, 2048, 0, torch.bfloat16, synth.config3),
 }
+
+
+def synth_codes(gen, M, N, K, fmtA, trans_a, trans_b):
+    """The workload's tensors, cast on the device with per-tensor amax scaling as in bench.py."""
+    A_bits, B_bits = gen(M, N, K)
+    ws = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    amax, scale = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    out = []
+    for bits, fmt in ((A_bits, fmtA), (B_bits, fp8.FP8_E4M3)):
+        x = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+        q = torch.empty(bits.shape, dtype=torch.uint8, device="cuda")
+        fp8.fp8_amax_scale(x, fmt, amax, scale, ws)
+        fp8.fp8_quantize_dscale(x, fmt, scale, q)
+        torch.cuda.synchronize()
+        out.append(q)
+    A, B = out
+    return (A.t().contiguous() if trans_a else A), (B.t().contiguous() if trans_b else B)
 
 
 def random_codes(shape, top=0x5F):
@@ -31,10 +57,12 @@ def main():
     ap.add_argument("--workload", default="ffn_up_175b", choices=sorted(SHAPES) + ["quantize_only", "cast_variants"])
     ap.add_argument("--mode", default="f16", choices=["f16", "mfma8"])
     ap.add_argument("--iters", type=int, default=3)
+    ap.add_argument("--ramp", type=int, default=12, help="untimed GEMM launches first (clock ramp after idle), as in bench.py")
     ap.add_argument("--copy-mib", type=int, default=1024, help="size of the calibration copy")
     ap.add_argument("--mnk", type=int, nargs=3, default=None, help="GEMM shape overriding the workload's")
     ap.add_argument("--trans-a", type=int, default=0, help="1: A stored K x M")
     ap.add_argument("--trans-b", type=int, default=0, help="1: B stored N x K")
+    ap.add_argument("--data", default="synth", choices=["synth", "random"], help="GEMM operands: the workload's synthetic tensors or uniform codes")
     args = ap.parse_args()
 
     n = args.copy_mib << 20
@@ -46,14 +74,15 @@ def main():
 
     if args.workload == "quantize_only":
         m = 1 << 28
-        x = torch.randn(m, device="cuda").to(torch.bfloat16)
+        h = synth.config2(m)
+        x = torch.from_numpy(h.view(np.int16)).view(torch.bfloat16).cuda()
         q = torch.empty(m, dtype=torch.uint8, device="cuda")
         amax = torch.zeros(1, device="cuda")
         scale = torch.zeros(1, device="cuda")
+        ws = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
         for _ in range(args.iters):
-            fp8.fp8_amax(x, amax)
             for fmt in (fp8.FP8_E4M3, fp8.FP8_E5M2):
-                fp8.fp8_scale_from_amax(amax, fmt, scale)
+                fp8.fp8_amax_scale(x, fmt, amax, scale, ws)
                 fp8.fp8_quantize_dscale(x, fmt, scale, q)
     elif args.workload == "cast_variants":
         rows = cols = 1 << 14
@@ -70,14 +99,17 @@ def main():
             fp8.fp8_amax_rows(x, row_amax)
             fp8.fp8_quantize_rows(x, fp8.FP8_E4M3, row_scale, q)
     else:
-        M, N, K, fmtA, out = SHAPES[args.workload]
+        M, N, K, fmtA, out, gen = SHAPES[args.workload]
         if args.mnk:
             M, N, K = args.mnk
-        A = random_codes((K, M) if args.trans_a else (M, K))
-        B = random_codes((N, K) if args.trans_b else (K, N))
+        if args.data == "synth":
+            A, B = synth_codes(gen, M, N, K, fmtA, args.trans_a, args.trans_b)
+        else:
+            A = random_codes((K, M) if args.trans_a else (M, K))
+            B = random_codes((N, K) if args.trans_b else (K, N))
         C = torch.empty((M, N), dtype=out, device="cuda")
         flags = 0 if args.mode == "f16" else fp8.FP8_GEMM_MFMA8
-        for _ in range(args.iters):
+        for _ in range(args.ramp + args.iters):
             fp8.fp8_gemm_ex(A, fmtA, args.trans_a, B, fp8.FP8_E4M3, args.trans_b, C, 1.0, 1.0, flags)
     torch.cuda.synchronize()
 
