@@ -295,6 +295,27 @@ int fp8_gemm_splitk(const uint8_t* A, int fmtA, int transA, const uint8_t* B, in
                     int splits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * fp8_gemm_splitk_static -- fp8_gemm_splitk for callers that cannot allocate or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine): the slices' sums go
+ * to a device array inside the library, FP8_SPLITK_STATIC_BYTES (64 MiB) per device, which every
+ * device the library runs on holds until the process ends.  Results are those of fp8_gemm_splitk
+ * with the same number of slices, bit for bit.
+ *   splits  0: the library's choice, cut down to the slices the array holds (if it cannot hold
+ *           two, the call is the plain fp8_gemm_ex);  1..64: that many slices -- if they need
+ *           more than the array holds (slices x M x N x 4 bytes), FP8_ERR_UNSUPPORTED, nothing launched
+ * All calls on one device share that device's array: calls that may overlap on a device (different
+ * streams, different threads) race on it and must be serialised by the caller; calls that follow
+ * one another on a stream are fine.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress) and should be made outside a graph capture.
+ */
+#define FP8_SPLITK_STATIC_BYTES ((size_t)64 << 20)
+int fp8_gemm_splitk_static(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                           void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
+                           float sA, float sB, const float* sA_dev, const float* sB_dev, int flags,
+                           int splits, void* stream);
+
+/*
  * fp8_gemm_fused -- the GEMM with the scale granularities and the output conversions that
  * training recipes build on:
  *     c_ij    = (sum_k a_ik b_kj) / (sA_i * sB_j)

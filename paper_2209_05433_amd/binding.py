@@ -13,6 +13,7 @@ FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
 FP8_AMAX_WORKSPACE_BYTES = 8192
+FP8_SPLITK_STATIC_BYTES = 64 << 20
 FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
 FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128 = 0, 1, 2, 3
@@ -26,7 +27,7 @@ EXPORTS = (
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_splitk", "fp8_gemm_splitk_workspace_size", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_set_knob", "fp8_get_knob",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_splitk", "fp8_gemm_splitk_workspace_size", "fp8_gemm_splitk_static", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_set_knob", "fp8_get_knob",
     "fp8_last_error", "fp8_version",
 )
 
@@ -65,6 +66,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
     L.fp8_gemm_splitk.argtypes, L.fp8_gemm_splitk.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, i, vp, sz, vp], i
+    L.fp8_gemm_splitk_static.argtypes, L.fp8_gemm_splitk_static.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, i, vp], i
     L.fp8_gemm_splitk_workspace_size.argtypes, L.fp8_gemm_splitk_workspace_size.restype = [i64, i64, i64, i, i, i], sz
     L.fp8_gemm_fused.argtypes, L.fp8_gemm_fused.restype = [vp, i, i, vp, i, i, vp, i, i64, i64, i64, vp, i64, vp, i64, vp, vp, i, vp], i
     L.fp8_quantize_sr.argtypes, L.fp8_quantize_sr.restype = [vp, sz, i, i, f, vp, c.c_uint64, vp, vp], i
@@ -293,6 +295,21 @@ def fp8_gemm_splitk(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, s
                                  _dev(workspace, "workspace") if workspace is not None else None,
                                  workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                  _stream(stream)))
+
+
+def fp8_gemm_splitk_static(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, sB, flags: int = 0,
+                           splits: int = 0, stream=None) -> None:
+    """fp8_gemm_splitk with the library's own scratch array in place of a workspace; allocates nothing."""
+    M, N, K = _gemm_ex_dims(A, transA, B, transB, C)
+    dev = isinstance(sA, torch.Tensor)
+    if dev != isinstance(sB, torch.Tensor):
+        raise ValueError("sA and sB must both be floats or both device tensors")
+    _check(lib().fp8_gemm_splitk_static(_dev(A, "A") if A.numel() else None, fmtA, int(bool(transA)),
+                                        _dev(B, "B") if B.numel() else None, fmtB, int(bool(transB)),
+                                        _dev(C, "C") if C.numel() else None, M, N, K, dtype_code(C),
+                                        0.0 if dev else float(sA), 0.0 if dev else float(sB),
+                                        _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
+                                        int(flags), int(splits), _stream(stream)))
 
 
 def fp8_gemm_fused(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, D, out_kind: int, sA, sB,

@@ -7,6 +7,8 @@
 // unscaling is applied once per dot product) and converts to the output type.
 #include "gemm_common.hpp"
 
+#include <mutex>
+
 namespace fp8mm {
 namespace {
 
@@ -123,6 +125,39 @@ int launch_gemm_splitk(const GemmArgs& g, const SplitPlan& sp, void* ws)
     return check_launch("gemm (split-K reduction)");
 }
 
+// ---- the form that allocates nothing ---------------------------------------------------------
+// The slices' sums go to a file-scope device array instead of a caller-supplied workspace.  Every
+// device the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle: its device address comes from
+// hipGetSymbolAddress, asked once per device with that device current, and is what kernels get.
+namespace {
+
+constexpr size_t kScratchBytes = FP8_SPLITK_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each device, 0 = not asked yet
+
+int scratch_of_current_device(const char* who, void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(FP8_ERR_DEVICE, "%s: hipGetDevice: %s", who, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(FP8_ERR_UNSUPPORTED, "%s: device index %d is beyond %d", who, dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(FP8_ERR_DEVICE, "%s: hipGetSymbolAddress(scratch) on device %d: %s", who, dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FP8_OK;
+}
+
+}  // namespace
 }  // namespace fp8mm
 
 using namespace fp8mm;
@@ -158,6 +193,35 @@ int fp8_gemm_splitk(const uint8_t* A, int fmtA, int transA, const uint8_t* B, in
         return fail(FP8_ERR_INVALID_ARG, "%s: %d slices of %lld x %lld fp32 sums need a workspace of %zu bytes, %zu given",
                     who, sp.splits, (long long)M, (long long)N, need, workspace ? workspace_bytes : (size_t)0);
     return launch_gemm_splitk(g, sp, workspace);
+}
+
+int fp8_gemm_splitk_static(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int fmtB, int transB,
+                           void* C, int64_t M, int64_t N, int64_t K, int out_dtype,
+                           float sA, float sB, const float* sA_dev, const float* sB_dev, int flags,
+                           int splits, void* stream)
+{
+    const char* who = "fp8_gemm_splitk_static";
+    GemmArgs g{};
+    if (int e = fill_gemm_args(who, g, A, fmtA, transA, B, fmtB, transB, C, M, N, K, out_dtype, sA, sB, sA_dev, sB_dev,
+                               flags, stream))
+        return e;
+    if (splits < 0 || splits > kMaxSplitK) return fail(FP8_ERR_INVALID_ARG, "%s: splits = %d is not in 0..%d", who, splits, kMaxSplitK);
+    if (M == 0 || N == 0 || K == 0) return launch_gemm(g);
+    const int requested = splits ? splits : knob(FP8_KNOB_SPLIT_K);
+    SplitPlan sp = plan_splitk(g, requested);
+    size_t need = splitk_workspace_bytes(g, sp);
+    if (need > kScratchBytes) {
+        const size_t fit = kScratchBytes / ((size_t)M * (size_t)N * sizeof(float));     // slices the array holds
+        if (requested > 0 || fit < 2)
+            return fail(FP8_ERR_UNSUPPORTED, "%s: %d slices of %lld x %lld fp32 sums need %zu bytes, the static scratch array holds %zu",
+                        who, sp.splits, (long long)M, (long long)N, need, kScratchBytes);
+        sp = plan_splitk(g, (int)fit);                       // the library's own choice is cut down to what fits
+        need = splitk_workspace_bytes(g, sp);
+    }
+    void* ws = nullptr;
+    if (need > 0)
+        if (int e = scratch_of_current_device(who, &ws)) return e;
+    return launch_gemm_splitk(g, sp, ws);
 }
 
 }  // extern "C"
