@@ -199,6 +199,37 @@ def run_workload(name, args, fp8, synth, torch, np, probes, steps, warmup, extra
     }
 
     if extras:
+        # The same launches recorded once into a HIP graph and replayed: what the step costs when the
+        # host does not have to issue five launches per step (on the small workload the eager step is
+        # bound by that, not by the GPU).  Three graphs: the whole step, the amax + cast chain, the GEMM.
+        def cast_chain():
+            for t, q, i, f in ((dA, qA, 0, fmtA), (dB, qB, 1, fmtB)):
+                fp8.fp8_amax_scale(t, f, amax[i:i + 1], scale[i:i + 1], ws)
+                fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
+        def replay_ms(fn, n):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn()
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            for _ in range(n):
+                g.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_start) / n * 1e3
+        n_g = max(10, steps)
+        g_step = replay_ms(step, n_g)
+        g_cast = replay_ms(cast_chain, n_g)
+        g_gemm = replay_ms(lambda: fp8.fp8_gemm_dscale(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C), n_g)
+        g_gemm8 = replay_ms(lambda: fp8.fp8_gemm_mfma8_dscale(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C), n_g)
+        res["graph_replay"] = {
+            "ms_per_step": round(g_step, 4), "value": round(flops / g_step * 1e-9, 2), "unit": "TFLOP/s",
+            "amax_scale_cast_ms": round(g_cast, 4), "cast_frac_of_hbm_peak": round(cast_bytes / g_cast * 1e-6 / PEAK_HBM_GBS, 4),
+            "gemm_ms": round(g_gemm, 4), "gemm_TFLOP/s": round(flops / g_gemm * 1e-9, 1),
+            "gemm_fp8_instr_ms": round(g_gemm8, 4), "gemm_fp8_instr_TFLOP/s": round(flops / g_gemm8 * 1e-9, 1),
+            "note": "wall time of back-to-back replays of a HIP graph of the step / of the chain / of one GEMM launch",
+        }
         # the same step with the FP8 matrix-core instructions (weaker error bound, see include/fp8mm.h)
         ms8, _, gemm8_ms = timed(fp8.fp8_gemm_mfma8_dscale, max(3, steps // 2), 2)
         sustained8 = sustained_mfma(torch, probes, qA, qB, 0) if probes else None
@@ -243,7 +274,7 @@ def main():
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
     }
-    for k in ("config", "breakdown_ms", "roofline", "roofline_cast", "algorithmic_bytes_gemm", "fp8_instruction_variant"):
+    for k in ("config", "breakdown_ms", "roofline", "roofline_cast", "algorithmic_bytes_gemm", "graph_replay", "fp8_instruction_variant"):
         if k in main_res:
             result[k] = main_res[k]
 

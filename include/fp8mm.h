@@ -76,13 +76,13 @@ int fp8_amax(const void* x, size_t n, int in_dtype, float* amax_out, void* strea
  * last one to finish reduces them and writes both results.  For the per-step path
  * amax -> scale -> cast, where two one-thread launches cost as much as casting a small tensor.
  *   amax_out   device, one fp32, overwritten;  scale_out  device, one fp32, or NULL (amax only)
- *   workspace  device, FP8_AMAX_WORKSPACE_BYTES bytes, 4-byte aligned.  Its first 4 bytes must be
- *              zero before the first call that uses it; every call leaves them zero again, so
- *              calls that follow one another on a stream can share one workspace.  Calls that may
- *              overlap (different streams) need a workspace each.
+ *   workspace  device, FP8_AMAX_WORKSPACE_BYTES bytes, 4-byte aligned.  It must be zero-filled
+ *              once, before the first call that uses it; every call leaves its counters zero
+ *              again, so calls that follow one another on a stream can share one workspace.
+ *              Calls that may overlap (different streams) need a workspace each.
  * n == 0 gives amax 0 and scale 1.  Errors as fp8_amax.
  */
-#define FP8_AMAX_WORKSPACE_BYTES 8192
+#define FP8_AMAX_WORKSPACE_BYTES 16384
 int fp8_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out,
                    void* workspace, void* stream);
 
@@ -376,9 +376,11 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
  *   FP8_KNOB_GROUP_M      tile rows per band of the tile order, 0 = default 8 (FP8MM_GROUP_M)
  *   FP8_KNOB_GEMM_KERNEL  0 the dispatcher chooses, 1 always the plain FMA kernel (FP8MM_GEMM=generic)
  *   FP8_KNOB_SPLIT_K      0 fp8_gemm_splitk chooses its number of K slices, n > 0 forces n (FP8MM_SPLIT_K)
+ *   FP8_KNOB_CAST_RUN     length of the contiguous run one workgroup of the cast kernel owns, in units
+ *                         of 4096 elements; 0 = default (4: 16 384 elements) (FP8MM_CAST_RUN)
  */
 typedef enum { FP8_KNOB_CAST_PATH = 0, FP8_KNOB_TILE_N = 1, FP8_KNOB_GROUP_M = 2, FP8_KNOB_GEMM_KERNEL = 3,
-               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_COUNT = 5 } fp8_knob_t;
+               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_CAST_RUN = 5, FP8_KNOB_COUNT = 6 } fp8_knob_t;
 int fp8_set_knob(int knob, int value);
 int fp8_get_knob(int knob);
 

@@ -12,13 +12,13 @@ FP8_E4M3, FP8_E5M2 = 0, 1
 FP8_F32, FP8_BF16 = 0, 1
 FP8_OK, FP8_ERR_INVALID_ARG, FP8_ERR_UNSUPPORTED, FP8_ERR_DEVICE = 0, 1, 2, 3
 FP8_QUANT_NOSAT = 1
-FP8_AMAX_WORKSPACE_BYTES = 8192
+FP8_AMAX_WORKSPACE_BYTES = 16384
 FP8_SPLITK_STATIC_BYTES = 64 << 20
 FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
 FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128 = 0, 1, 2, 3
 FP8_PLAN_ELEMENTWISE_STORES = 16
-FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K = 0, 1, 2, 3, 4
+FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN = 0, 1, 2, 3, 4, 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
@@ -154,7 +154,7 @@ def fp8_amax(x: torch.Tensor, amax_out: torch.Tensor, stream=None) -> None:
 
 def fp8_amax_scale(x: torch.Tensor, fmt: int, amax_out: torch.Tensor, scale_out, workspace: torch.Tensor, stream=None) -> None:
     """amax and scale = fmt_max / amax in one launch; workspace: device tensor of at least
-    FP8_AMAX_WORKSPACE_BYTES bytes whose first 4 bytes were zero before its first use."""
+    FP8_AMAX_WORKSPACE_BYTES bytes, zero-filled once before its first use."""
     if workspace.numel() * workspace.element_size() < FP8_AMAX_WORKSPACE_BYTES:
         raise ValueError("workspace must hold FP8_AMAX_WORKSPACE_BYTES bytes")
     _check(lib().fp8_amax_scale(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,

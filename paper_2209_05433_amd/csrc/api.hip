@@ -42,6 +42,7 @@ static void seed_knobs()
     if ((e = getenv("FP8MM_GROUP_M")) && atoi(e) > 0) g_knob[FP8_KNOB_GROUP_M] = atoi(e);
     if ((e = getenv("FP8MM_GEMM")) && e[0] == 'g') g_knob[FP8_KNOB_GEMM_KERNEL] = 1;
     if ((e = getenv("FP8MM_SPLIT_K")) && atoi(e) > 0) g_knob[FP8_KNOB_SPLIT_K] = atoi(e);
+    if ((e = getenv("FP8MM_CAST_RUN")) && atoi(e) > 0 && atoi(e) <= 64) g_knob[FP8_KNOB_CAST_RUN] = atoi(e);
 }
 
 int knob(int which)
@@ -109,6 +110,7 @@ int fp8_set_knob(int which, int value)
         case FP8_KNOB_GROUP_M: ok = value >= 0 && value <= 4096; break;
         case FP8_KNOB_GEMM_KERNEL: ok = value == 0 || value == 1; break;
         case FP8_KNOB_SPLIT_K: ok = value >= 0 && value <= 64; break;
+        case FP8_KNOB_CAST_RUN: ok = value >= 0 && value <= 64; break;
     }
     if (!ok) return -fail(FP8_ERR_INVALID_ARG, "fp8_set_knob: value %d is not valid for knob %d", value, which);
     const int old = knob(which);                    // seeds from the environment first

@@ -21,24 +21,49 @@ constexpr int kAmaxChunkVecs = kThreads * 8;
 
 // Last step of the amax kernels in their one-launch form (fp8_amax_scale): no cell has to be
 // cleared beforehand and the scale comes out of the same launch.  Every workgroup leaves its
-// maximum in ws[1 + blockIdx.x] and takes a ticket from ws[0]; the workgroup that draws the last
-// ticket reduces the gridDim.x partial maxima, writes amax and scale = fmt_max / amax, and puts the
-// ticket counter back to 0 for the next call.  r: the workgroup's maximum, valid in thread 0.
+// maximum in the workspace and takes a ticket; the workgroup that draws the last ticket reduces the
+// gridDim.x partial maxima, writes amax and scale = fmt_max / amax.  Tickets are drawn in two levels
+// (groups of kTicketGroup workgroups, then one ticket per group): a thousand workgroups that finish
+// together and draw from one counter queue up at that counter for longer than small tensors take
+// to read.  Every counter is put back to 0 by the workgroup that drew its last ticket.
+// Workspace words: [0] top counter; [32 (1 + g)] counter of group g (one 128-byte line each);
+// [kTicketPartials + b] partial maximum of workgroup b.
+// Ordering: the partial maximum is stored with an agent-scope atomic store (written through to where
+// every other workgroup sees it) and has been acknowledged (vmcnt) before the ticket is drawn; the
+// reader draws the last ticket before it loads, again with agent-scope atomic loads.  No other
+// data is exchanged, so no cache-wide write-back or invalidate is needed.
+// r: the workgroup's maximum, valid in thread 0.
+constexpr unsigned kTicketGroup = 32;
+constexpr unsigned kTicketPartials = 32 * (1 + kAmaxBlocks / kTicketGroup);
+
+__device__ __forceinline__ unsigned draw_ticket(unsigned* counter)
+{
+    return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ void amax_finish_ticket(unsigned r, unsigned* __restrict__ ws, int fmt,
                                                    float* __restrict__ amax_out, float* __restrict__ scale_out)
 {
     __shared__ bool last;
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&ws[1 + blockIdx.x], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();                                    // the partial maximum is visible before the ticket is
-        last = atomicAdd(&ws[0], 1u) == gridDim.x - 1;
+        __hip_atomic_store(&ws[kTicketPartials + blockIdx.x], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);            // (the compiler keeps the three steps in this order)
+        __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) (and lgkmcnt(0)): the store has been acknowledged
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        const unsigned g = blockIdx.x / kTicketGroup, groups = (gridDim.x + kTicketGroup - 1) / kTicketGroup;
+        const unsigned members = min(kTicketGroup, gridDim.x - g * kTicketGroup);
+        bool l = false;
+        if (draw_ticket(&ws[32 * (1 + g)]) == members - 1) {
+            __hip_atomic_store(&ws[32 * (1 + g)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            l = draw_ticket(&ws[0]) == groups - 1;
+        }
+        last = l;
     }
     __syncthreads();
     if (!last) return;
-    __threadfence();
     unsigned m = 0;
     for (unsigned i = threadIdx.x; i < gridDim.x; i += kThreads) {
-        const unsigned p = __hip_atomic_load(&ws[1 + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned p = __hip_atomic_load(&ws[kTicketPartials + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         m = m > p ? m : p;
     }
     m = block_max_u32(m);
@@ -217,7 +242,7 @@ int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStrea
 int launch_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out, void* workspace,
                       hipStream_t stream)
 {
-    static_assert((kAmaxBlocks + 1) * sizeof(unsigned) <= FP8_AMAX_WORKSPACE_BYTES, "ticket + one partial per workgroup");
+    static_assert((kTicketPartials + kAmaxBlocks) * sizeof(unsigned) <= FP8_AMAX_WORKSPACE_BYTES, "counters + one partial per workgroup");
     if (n == 0) hipLaunchKernelGGL(amax_empty_kernel, dim3(1), dim3(1), 0, stream, fmt, amax_out, scale_out);
     else launch_amax_kernels<true>(x, n, in_dtype, (unsigned*)amax_out, (unsigned*)workspace, fmt, scale_out, stream);
     return check_launch("amax_scale");
@@ -237,7 +262,8 @@ void launch_quantize_typed(const void* x, size_t n, float scale, const float* sc
                            uint8_t* q, bool saturate, hipStream_t stream)
 {
     if (aligned16(x) && aligned16(q)) {
-        const int grid = grid_for((n / 16 + 3) / 4, kCastBlocks);
+        const size_t per_lane = knob(FP8_KNOB_CAST_RUN) ? (size_t)knob(FP8_KNOB_CAST_RUN) : 4;    // items of 16 elements per lane
+        const int grid = grid_for((n / 16 + per_lane - 1) / per_lane, kCastBlocks);
         // An output that does not fit the memory-side cache (256 MB) is written past it.
         const bool nts = n >= kStreamingStoreBytes;
 #define FP8MM_LAUNCH_QV(PATH)                                                                                      \

@@ -29,6 +29,9 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     D = torch.empty((M, N), dtype=torch.uint8, device="cuda")
     W = torch.empty((K, N), dtype=torch.float32, device="cuda")       # A^T-shaped product: (K x M) x (M x N)
+    W2, W3 = torch.empty_like(W), torch.empty_like(W)
+    ws_amax = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    ws_k = torch.empty(fp8.fp8_gemm_splitk_workspace_size(K, N, M, 0, 0, 2), dtype=torch.uint8, device="cuda")
 
     def step():
         fp8.fp8_amax(dA, amax[0:1])
@@ -40,6 +43,9 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         fp8.fp8_gemm_fused(qA, E4M3, 0, qB, E4M3, 0, D, fp8.FP8_OUT_E5M2, scale[0:1], scale[1:2], None, amax[2:3],
                            fp8.FP8_GEMM_MFMA8)
         fp8.fp8_gemm_ex(qAt, E4M3, 0, D, E5M2, 0, W, 1.0, 1.0)          # a second GEMM fed by the first one's FP8 output
+        fp8.fp8_amax_scale(dB, E5M2, amax[1:2], scale[2:3], ws_amax)     # one-launch amax + scale (tickets in a workspace)
+        fp8.fp8_gemm_splitk(qAt, E4M3, 0, D, E5M2, 0, W2, 1.0, 1.0, ws_k, 0, 2)     # the same product in two K slices
+        fp8.fp8_gemm_splitk_static(qAt, E4M3, 0, D, E5M2, 0, W3, 1.0, 1.0, 0, 2)     # ... with the library's own scratch array
 
     def load(seed):
         a, b = synth.config3(M, N, K)
@@ -52,7 +58,7 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W)]
+        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W, W2, W3)]
 
     load(0)
     hist.zero_()
@@ -72,11 +78,12 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         hist.fill_(0.25 * (trial + 1))
         for t in (qA, qAt, qB, C, D):
             t.zero_()
-        W.zero_()
+        for t in (W, W2, W3):
+            t.zero_()
         amax.fill_(-1.0)
         graph.replay()
         replayed = snapshot()
-        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W".split()):
+        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W W2 W3".split()):
             assert torch.equal(e.view(torch.uint8), r.view(torch.uint8)), "replay %d differs from eager in %s" % (trial, name)
         if trial == 0:                       # and eager is what the oracle says
             sA = oracle.scale_from_amax(oracle.amax(a_bits), oracle.E4M3)
@@ -88,3 +95,5 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
             S, T = oracle.gemm_rows(Aq, oracle.E4M3, Bq, oracle.E4M3)
             c_ref, bound = oracle.gemm_bound(S, T, sA, sB, oracle.BF16)
             assert np.all(np.abs(out_to_f64(eager[6]) - c_ref) <= bound)
+            assert torch.equal(eager[9], eager[10]) and np.float32(eager[0][1].item()) == oracle.amax(b_bits)
+            assert np.float32(eager[1][2].item()) == oracle.scale_from_amax(oracle.amax(b_bits), oracle.E5M2)
