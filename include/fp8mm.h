@@ -354,12 +354,15 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * NULL.  Returns FP8_PLAN_NO_GEMM if M, N or K is 0, otherwise one of FP8_PLAN_TILED_256x256,
  * FP8_PLAN_TILED_256x128 (matrix-core kernel, tile chosen for how well it fills the chip) or
  * FP8_PLAN_FMA_KERNEL (any shape and alignment, far slower), ORed with
- * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries.
+ * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries, and
+ * with FP8_PLAN_PERSISTENT where the 256 x 128 kernel runs in its persistent form (answered for
+ * per-tensor factors, an fp32 output and the default accumulation mode; with a bf16 output or
+ * FP8_GEMM_MFMA8 the form is used over a narrower range of K, see FP8_KNOB_PERSIST).
  * A negative value is minus an fp8_status_t (bad arguments).  Section 2 fixes the arithmetic,
  * not the kernel: every plan computes the same product within the stated bounds.
  */
 typedef enum { FP8_PLAN_NO_GEMM = 0, FP8_PLAN_FMA_KERNEL = 1, FP8_PLAN_TILED_256x256 = 2,
-               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_ELEMENTWISE_STORES = 16 } fp8_plan_t;
+               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_ELEMENTWISE_STORES = 16, FP8_PLAN_PERSISTENT = 32 } fp8_plan_t;
 int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
                   int64_t M, int64_t N, int64_t K, const float* sB_per_column);
 
@@ -378,9 +381,12 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
  *   FP8_KNOB_SPLIT_K      0 fp8_gemm_splitk chooses its number of K slices, n > 0 forces n (FP8MM_SPLIT_K)
  *   FP8_KNOB_CAST_RUN     length of the contiguous run one workgroup of the cast kernel owns, in units
  *                         of 4096 elements; 0 = default (4: 16 384 elements) (FP8MM_CAST_RUN)
+ *   FP8_KNOB_PERSIST      the persistent form of the matrix-core kernel (one workgroup per compute unit
+ *                         walks several tiles as one K loop): 0 where the dispatcher finds it pays,
+ *                         1 never, 2 wherever its conditions hold (FP8MM_PERSIST)
  */
 typedef enum { FP8_KNOB_CAST_PATH = 0, FP8_KNOB_TILE_N = 1, FP8_KNOB_GROUP_M = 2, FP8_KNOB_GEMM_KERNEL = 3,
-               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_CAST_RUN = 5, FP8_KNOB_COUNT = 6 } fp8_knob_t;
+               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_CAST_RUN = 5, FP8_KNOB_PERSIST = 6, FP8_KNOB_COUNT = 7 } fp8_knob_t;
 int fp8_set_knob(int knob, int value);
 int fp8_get_knob(int knob);
 

@@ -116,7 +116,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 GemmPlan plan_gemm(const GemmArgs& g)
 {
     const int64_t M = g.M, N = g.N, K = g.K;
-    GemmPlan plan{GEMM_GENERIC, false};
+    GemmPlan plan{GEMM_GENERIC, false, false};
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
                         K < (1ll << 31) &&
@@ -147,6 +147,22 @@ GemmPlan plan_gemm(const GemmArgs& g)
     const bool narrow = tn ? tn == 128 : 0.88 * fill(128) > fill(256);
     plan.kernel = narrow ? GEMM_TILED_128 : GEMM_TILED_256;
     plan.elementwise_stores = !c_lines;
+    // The persistent form of the narrow tile (one workgroup per compute unit walks its tiles as one K
+    // loop, see gemm_tiled.hip): for problems of more than one round of tiles without edge tiles, with
+    // per-tensor factors and an fp32 / bf16 output.  It hides every tile's first loads and sends the
+    // outputs straight from the registers, but its workgroups cannot even out their speeds over the
+    // tiles as separately scheduled ones do.  Measured on 4096 x 6144 (768 tiles): with fp32 outputs
+    // 3 - 6 % faster up to K = 4096 in both accumulation modes (the LDS turn of an fp32 tile takes two
+    // passes); with bf16 outputs 2 % faster around K = 2048 in the fp16 mode, slower in the FP8 mode;
+    // 1 - 2 % slower at K = 8192 throughout.  Knob FP8_KNOB_PERSIST: 0 = where it pays (below),
+    // 1 = never, 2 = wherever it is possible.
+    const int pk = knob(FP8_KNOB_PERSIST);
+    const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + 127) / 128);
+    const bool possible = narrow && c_lines && M % TILE_M == 0 && N % 128 == 0 && K % (2 * TILE_K) == 0 && K >= 8 * TILE_K &&
+                          !g.ep.a_per_row && !g.ep.b_per_col && g.ep.out_kind <= OUT_BF16 && !g.ep.amax_out && g.splits <= 1;
+    const bool pays = tiles > 256 && (g.ep.out_kind == OUT_F32 ? K <= 64 * TILE_K
+                                                               : g.acc == ACC_F16 && K >= 16 * TILE_K && K <= 32 * TILE_K);
+    plan.persistent = possible && pk != 1 && (pk == 2 || pays);
     return plan;
 }
 
@@ -177,6 +193,7 @@ int launch_gemm(const GemmArgs& g)
         GemmArgs gt = g;
         gt.ep.ragged_n = plan.elementwise_stores ? 1 : 0;
         gt.tile_n = plan.kernel == GEMM_TILED_128 ? 128 : 256;
+        gt.persist = plan.persistent;
         gt.splits = 1;
         return launch_tiled(gt);
     }

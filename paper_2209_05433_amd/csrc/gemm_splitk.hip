@@ -106,6 +106,7 @@ int launch_gemm_splitk(const GemmArgs& g, const SplitPlan& sp, void* ws)
     part.ep.out_kind = OUT_F32;
     part.ep.ragged_n = (g.N % 4 != 0 || !aligned_to(ws, 16)) ? 1 : 0;
     part.tile_n = sp.tile_n;
+    part.persist = false;
     part.splits = sp.splits;
     part.pairs_per_split = sp.pairs_per_split;
     if (int e = launch_tiled(part)) return e;

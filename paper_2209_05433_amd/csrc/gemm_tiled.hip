@@ -166,6 +166,12 @@ struct Operand {
     unsigned off[8];         // per-lane offsets of this wave's direct loads (EXT/32 used by KC, EXT/64 by MC)
     unsigned region;         // LDS byte offset of the operand's ring
     unsigned rd;             // per-lane LDS offset of its first fragment read (region included)
+    // persistent form: where the next slab to be loaded starts (the loads run ahead of the products,
+    // into the next tile), how many slabs of its tile have been loaded, and the byte offset from
+    // `tile` of the rows / columns of the tile after the one that is being loaded
+    const uint8_t* ldp;
+    int ld_rel;
+    size_t nxt;
 };
 
 template <bool KC, int EXT>
@@ -384,7 +390,20 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
 // A_KC / B_KC: how the operand lies in memory (see Operand); NB: width of the tile in blocks of 32
 // columns per wave.  LDS: an MN-contiguous operand takes a ring of four stage slabs; a K-contiguous
 // one a ring of three stage-pair slabs, or of two for B when both operands are K-contiguous.
-template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB>
+//
+// PERSIST: the persistent form for problems of several rounds of small tiles.  The grid is one
+// workgroup per compute unit; a workgroup takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ... and
+// walks them as ONE long K loop: the stages of the next tile follow the last stage of the current
+// one in the ring, so the direct loads of a tile's first stages are issued (and its first
+// fragments read) while the previous tile is still being multiplied, and a tile ends with nothing
+// but its stores.  Since all of the LDS then holds operands of the next tile, the outputs leave
+// straight from the registers (8 or 16 bytes per lane, 32 rows per instruction) instead of being
+// turned around through LDS: more, smaller writes, which do not matter where the output is small.
+// The stores are vector-memory instructions like the direct loads and complete in order with
+// them: the waits of the three steps after a tile end leave room for them.  Conditions (checked by
+// the dispatcher): no edge tiles, K a multiple of 128 and at least 512, per-tensor factors, fp32 or
+// bf16 output with rows on 16-byte boundaries, no output maximum, no K slices.
+template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB, bool PERSIST>
 __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
     int M, int N, int K, EpilogueArgs ep, int group_m, int splits, int pairs_per_split)
@@ -409,21 +428,36 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // the last slice what is left) of its tile and writes the fp32 sums, without the scales, into
     // slice `split` of C, which is then a workspace of `splits` M x N matrices.
     int bid = blockIdx.x, split = 0;
-    if (splits > 1) { split = bid % splits; bid /= splits; }
-    const TileMap tile = map_tile(bid, (M + BM - 1) / BM, (N + BN - 1) / BN, group_m);
-    const int m0 = tile.tm * BM, n0 = tile.tn * BN;
+    if (!PERSIST && splits > 1) { split = bid % splits; bid /= splits; }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const TileMap tile = map_tile(bid, tiles_m, tiles_n, group_m);
+    int m0 = tile.tm * BM, n0 = tile.tn * BN;               // the tile whose products are being accumulated
     const int pair0 = split * pairs_per_split;
-    const int KT = 2 * min(pairs_per_split, (K + 2 * BK - 1) / (2 * BK) - pair0);
+    const int KT_TILE = 2 * min(pairs_per_split, (K + 2 * BK - 1) / (2 * BK) - pair0);     // stages of one tile
+    // PERSIST: `units` tiles in a row; every stage and pair index below is then a global one
+    const int units = PERSIST ? (tiles_m * tiles_n - bid + (int)gridDim.x - 1) / (int)gridDim.x : 1;
+    const int KT = units * KT_TILE;
     const int kend = K - pair0 * 2 * BK;                    // bytes of K from the start of the slice to the end of K
-    const bool ktail = kend < KT * BK;                      // the slice ends in a partly filled pair
+    const bool ktail = !PERSIST && kend < KT * BK;          // the slice ends in a partly filled pair
     const unsigned lds0 = (unsigned)(uintptr_t)LDS_PTR(void, smem);
     C = (uint8_t*)C + (size_t)split * (size_t)M * (size_t)N * 4;
 
     Operand opA, opB;
-    operand_setup<A_KC, BM>(opA, A + (size_t)pair0 * 2 * BK * (A_KC ? 1 : (size_t)M), A_KC ? (unsigned)K : (unsigned)M, m0,
-                            min(BM, M - m0), A_REGION, w, l, wm);
-    operand_setup<B_KC, BN>(opB, B + (size_t)pair0 * 2 * BK * (B_KC ? 1 : (size_t)N), B_KC ? (unsigned)K : (unsigned)N, n0,
-                            min(BN, N - n0), B_REGION, w, l, wn);
+    operand_setup<A_KC, BM>(opA, A + (size_t)pair0 * 2 * BK * (A_KC ? 1 : (size_t)M), A_KC ? (unsigned)K : (unsigned)M,
+                            PERSIST ? 0 : m0, PERSIST ? BM : min(BM, M - m0), A_REGION, w, l, wm);
+    operand_setup<B_KC, BN>(opB, B + (size_t)pair0 * 2 * BK * (B_KC ? 1 : (size_t)N), B_KC ? (unsigned)K : (unsigned)N,
+                            PERSIST ? 0 : n0, PERSIST ? BN : min(BN, N - n0), B_REGION, w, l, wn);
+    // persistent form: where the rows / columns of a tile start, relative to the operand's first byte
+    auto a_start = [&](int tm0) { return A_KC ? (size_t)tm0 * (size_t)K : (size_t)tm0; };
+    auto b_start = [&](int tn0) { return B_KC ? (size_t)tn0 * (size_t)K : (size_t)tn0; };
+    int unit = 0;                                           // index of the current tile in this workgroup's list
+    int nm0 = m0, nn0 = n0;                                 // the tile after the current one
+    if (PERSIST && units > 1) {
+        const TileMap t2 = map_tile(bid + (int)gridDim.x, tiles_m, tiles_n, group_m);
+        nm0 = t2.tm * BM; nn0 = t2.tn * BN;
+    }
+    opA.ldp = opA.tile + (PERSIST ? a_start(m0) : 0); opA.ld_rel = 0; opA.nxt = PERSIST ? a_start(nm0) : 0;
+    opB.ldp = opB.tile + (PERSIST ? b_start(n0) : 0); opB.ld_rel = 0; opB.nxt = PERSIST ? b_start(nn0) : 0;
 
     // ---- the schedule of direct loads, as a function of the step index s (the prologue plays
     // the steps -5 .. -1).  Step s issues, in this order:
@@ -459,9 +493,10 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     constexpr int STEADY_EVEN = HAS_MC ? (A_KC ? A_KC_LOADS : 2 * A_MC_LOADS) + (B_KC ? B_KC_LOADS : 2 * B_MC_LOADS)
                                        : A_KC_LOADS + B_KC_LOADS;
     constexpr int STEADY_ODD = HAS_MC ? STEADY_EVEN : A_KC_LOADS;
-    auto wait_stage = [&](int t, int upto) {
+    // extra: younger instructions that are not direct loads (the stores of a tile end, persistent form)
+    auto wait_stage = [&](int t, int upto, int extra = 0) {
         const int s_need = HAS_MC ? t - 4 : 2 * (t / 2) - 2 * B_RING + 1;
-        int allowed = 0;
+        int allowed = extra;
         for (int s = s_need + 1; s <= upto; ++s) allowed += count_step(s);
         switch (allowed >> 1) {                   // every count is even
             case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<2>(); break;   case 2: wait_vmcnt<4>(); break;
@@ -471,7 +506,11 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             case 12: wait_vmcnt<24>(); break; case 13: wait_vmcnt<26>(); break; case 14: wait_vmcnt<28>(); break;
             case 15: wait_vmcnt<30>(); break; case 16: wait_vmcnt<32>(); break; case 17: wait_vmcnt<34>(); break;
             case 18: wait_vmcnt<36>(); break; case 19: wait_vmcnt<38>(); break; case 20: wait_vmcnt<40>(); break;
-            default: wait_vmcnt<0>(); break;
+            case 21: wait_vmcnt<42>(); break; case 22: wait_vmcnt<44>(); break; case 23: wait_vmcnt<46>(); break;
+            case 24: wait_vmcnt<48>(); break; case 25: wait_vmcnt<50>(); break; case 26: wait_vmcnt<52>(); break;
+            case 27: wait_vmcnt<54>(); break; case 28: wait_vmcnt<56>(); break; case 29: wait_vmcnt<58>(); break;
+            case 30: wait_vmcnt<60>(); break;
+            default: if (allowed > 60) wait_vmcnt<62>(); else wait_vmcnt<0>(); break;   // the counter holds 63 at most
         }
     };
     // load t of this wave for a pair slab (loads-per-wave lw: the slab takes 4 lw KB) / a stage slab
@@ -479,7 +518,9 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // pair; then the lane's chunk is tested against the end of K (see direct_load_or_zero).
     auto issue_kc = [&](auto tail_tag, const Operand& op, int lw, int pair, int slot, int t) {
         const unsigned lds = lds0 + op.region + slot * (lw * 4096) + w * (lw * 1024) + t * 1024;
-        if (decltype(tail_tag)::value && ktail) {
+        if (PERSIST) {
+            direct_load(op.ldp, op.off[t], lds);             // the running pointer (see advance_loads)
+        } else if (decltype(tail_tag)::value && ktail) {
             // row of the slab = (w lw + t) 8 + l / 8, chunk = (l % 8) ^ swz_kc(row)
             const int chunk = (l & 7) ^ (((w * lw + t) * 4 + (l >> 4)) & 7);
             direct_load_or_zero(op.tile + (size_t)pair * 2 * BK, op.off[t], pair * 2 * BK + chunk * 16 < kend, lds);
@@ -489,7 +530,9 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     };
     auto issue_mc = [&](auto tail_tag, const Operand& op, int lw, int st, int t) {
         const unsigned lds = lds0 + op.region + (st & (MC_SLOTS - 1)) * (lw * 4096) + w * (lw * 1024) + t * 1024;
-        if (decltype(tail_tag)::value && ktail) {
+        if (PERSIST) {
+            direct_load(op.ldp, op.off[t], lds);
+        } else if (decltype(tail_tag)::value && ktail) {
             // K-row of the slab = (w lw + t) KR + l / CH with KR = 16 / lw rows per load, CH = 4 lw chunks per row
             const int krow = (w * lw + t) * (16 / lw) + l / (4 * lw);
             direct_load_or_zero(op.tile + (size_t)st * BK * op.ld, op.off[t], st * BK + krow < kend, lds);
@@ -548,6 +591,31 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
 #pragma unroll
                 for (int t = jj * (B_MC_LOADS / H); t < (jj + 1) * (B_MC_LOADS / H); ++t) issue_mc(tail, opB, B_MC_LOADS, s + 4, t);
             }
+        }
+    };
+
+    // Persistent form: after the loads of step s have been issued, the running pointers of the operands
+    // that loaded a slab in it move on by one slab (a pair of stages = 128 bytes along K for a
+    // K-contiguous operand, a stage = 64 K-rows for the other kind); after the last slab of a tile
+    // they jump to the first slab of the next tile.  The conditions are those of issue_part.
+    auto advance = [&](Operand& op, size_t inc, int slabs_per_tile) {
+        op.ldp += inc;
+        if (++op.ld_rel == slabs_per_tile) { op.ld_rel = 0; op.ldp = op.tile + op.nxt; }
+    };
+    auto advance_loads = [&](auto full_tag, int s, bool odd) {
+        constexpr bool FULL = decltype(full_tag)::value;    // every load of the step exists: no tests
+        if (A_KC) {
+            if (B_KC ? !odd : odd) {
+                const int p = B_KC ? s / 2 + A_RING - 1 : kc_pair_of(s, A_RING);
+                if (FULL || pair_valid(p)) advance(opA, 2 * BK, KT_TILE / 2);
+            }
+        } else if (FULL || stage_valid(s + 4)) {
+            advance(opA, (size_t)BK * opA.ld, KT_TILE);
+        }
+        if (B_KC) {
+            if (odd && (FULL || pair_valid(kc_pair_of(s, B_RING)))) advance(opB, 2 * BK, KT_TILE / 2);
+        } else if (FULL || stage_valid(s + 4)) {
+            advance(opB, (size_t)BK * opB.ld, KT_TILE);
         }
     };
 
@@ -634,16 +702,25 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // (af_n, bf_n).  Spreading matters: the four waves run in step, and a wave that issues its
     // loads in one burst waits for the address unit before it reaches its first MFMA.
     // (sa, sb) = ring slots of the pair of stage kt, (sa_n, sb_n) = of the pair of stage kt+1.
+    // after_tag (compile-time; persistent form): the stores of a tile end were issued within the last
+    // three steps, after the loads this step waits for
+    constexpr int TILE_STORES = 16 * NB;          // store instructions per wave at a tile end
     auto k_step = [&](auto full_tag, int kt, bool odd, int sa, int sb, int sa_n, int sb_n, v8i (&af)[4], v8i (&bf)[NB],
-                      v8i (&af_n)[4], v8i (&bf_n)[NB]) {
+                      v8i (&af_n)[4], v8i (&bf_n)[NB], auto after_tag) {
         constexpr bool FULL = decltype(full_tag)::value;
+        constexpr bool after_stores = decltype(after_tag)::value;
         // slot that A's loads of this step go to
         const int sa_ld = (A_KC && B_KC && !odd) ? (sa == 0 ? A_RING - 1 : sa - 1) : sa;
         const int sb_ld = sb;
         if (FULL || kt + 8 < KT) {
-            if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
+            if (PERSIST && after_stores) {
+                if (odd) wait_vmcnt<(STEADY_ODD + TILE_STORES < 62 ? STEADY_ODD + TILE_STORES : 62)>();
+                else wait_vmcnt<(STEADY_EVEN + TILE_STORES < 62 ? STEADY_EVEN + TILE_STORES : 62)>();
+            } else {
+                if (odd) wait_vmcnt<STEADY_ODD>(); else wait_vmcnt<STEADY_EVEN>();
+            }
         } else {
-            wait_stage(kt + 1, kt - 1);
+            wait_stage(kt + 1, kt - 1, PERSIST && after_stores ? TILE_STORES : 0);
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): this wave's LDS reads of stage kt are done
         __builtin_amdgcn_s_barrier();         // stage kt+1 is complete; nobody reads the slots of stage kt any more
@@ -659,6 +736,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             }
             sched_part();
         }
+        if (PERSIST) advance_loads(full_tag, kt, odd);
     };
 
     // Prologue: steps -5 .. -1 of the same schedule, then stage 0 visible and its frags read.
@@ -672,6 +750,7 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
         const int sb = !B_KC ? 0 : (s & 1) ? (s + 1) / 2 + B_RING - 1 : s / 2 + B_RING - 1;
 #pragma unroll
         for (int j = 0; j < P; ++j) issue_part(checked, s, s & 1, j, sa, sb);
+        if (PERSIST) advance_loads(checked, s, s & 1);
     }
     wait_stage(0, -1);
     __builtin_amdgcn_s_barrier();
@@ -680,23 +759,105 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     if (ACC == ACC_F16) convert_f16(0, af0, bf0);
     int sa = 0, sb = 0;                       // ring slots of the current stage pair
     int kt = 0;
-    // steps whose loads all exist (the last stage a step s touches is s + 6) and whose waits are
-    // the steady ones: no tests inside
-    for (; kt + 10 < KT; kt += 2) {
-        const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
-        const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
-        k_step(full, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
-        k_step(full, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
-        sa = sa_n; sb = sb_n;
+
+    // ---- persistent form: the end of a tile -----------------------------------------------------
+    // c = acc / (sA sB) straight from the registers: a lane holds 4 consecutive N of one row of C per
+    // accumulator quad; then the accumulators are cleared and the bookkeeping moves on to the next
+    // tile (whose first stages are in the ring already and whose first fragments are in registers).
+    const float ra_tile = PERSIST ? (float)(1.0 / ((double)scale_value(ep.sA_dev, ep.sA) * (double)scale_value(ep.sB_dev, ep.sB))) : 0.0f;
+    int next_end = KT_TILE;                   // global index of the first stage of the next tile
+    auto tile_end = [&](bool more) {
+        const int le = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        const size_t row = (size_t)(m0 + wm * 128 + (le & 31));
+        const int col = n0 + wn * (32 * NB) + 4 * (le >> 5);
+        if (ep.out_kind == OUT_BF16) {
+            unsigned short* c0 = (unsigned short*)C + row * (size_t)N + col;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v16f& a = acc[nb][mb];
+                        v2i o;
+                        o.x = (int)__builtin_bit_cast(unsigned, __builtin_convertvector((v2f){a[4 * q] * ra_tile, a[4 * q + 1] * ra_tile}, v2bf));
+                        o.y = (int)__builtin_bit_cast(unsigned, __builtin_convertvector((v2f){a[4 * q + 2] * ra_tile, a[4 * q + 3] * ra_tile}, v2bf));
+                        *(v2i*)(c0 + (size_t)(mb * 32) * N + nb * 32 + 8 * q) = o;
+                    }
+        } else {
+            float* c0 = (float*)C + row * (size_t)N + col;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v16f& a = acc[nb][mb];
+                        *(v4f*)(c0 + (size_t)(mb * 32) * N + nb * 32 + 8 * q) =
+                            (v4f){a[4 * q] * ra_tile, a[4 * q + 1] * ra_tile, a[4 * q + 2] * ra_tile, a[4 * q + 3] * ra_tile};
+                    }
+        }
+        if (!more) return;
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        ++unit;
+        m0 = nm0; n0 = nn0;
+        if (unit + 1 < units) {
+            const TileMap t2 = map_tile(bid + (unit + 1) * (int)gridDim.x, tiles_m, tiles_n, group_m);
+            nm0 = t2.tm * BM; nn0 = t2.tn * BN;
+            opA.nxt = a_start(nm0); opB.nxt = b_start(nn0);
+        }
+        next_end += KT_TILE;
+    };
+    const std::integral_constant<bool, true> yes;
+    const std::integral_constant<bool, false> no;
+
+    // One round of the outer loop per tile (a single one unless PERSIST).  The tile end sits between
+    // the inner loops, not inside them: inside, the accumulators would have to change register
+    // class (the stores read them as vector registers, the matrix instructions keep them in the
+    // accumulation registers) on every trip.
+    for (;;) {
+        const int tile_stop = next_end < KT ? next_end : KT - 2;     // the last pair of the last tile is peeled below
+        // steps whose loads all exist (the last stage a step s touches is s + 6) and whose waits are
+        // the steady ones: no tests inside
+        for (; kt + 10 < KT && kt < tile_stop; kt += 2) {
+            const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+            const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+            k_step(full, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1, no);
+            k_step(full, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0, no);
+            sa = sa_n; sb = sb_n;
+        }
+        for (; kt < tile_stop; kt += 2) {
+            const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+            const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+            k_step(checked, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1, no);
+            k_step(checked, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0, no);
+            sa = sa_n; sb = sb_n;
+        }
+        if (!PERSIST || next_end >= KT) break;
+        tile_end(true);
+        // The first three steps of the next tile wait for loads that are older than these stores:
+        // two pairs of steps (a tile has at least four) with the stores counted in, in the tested form.
+        {
+            const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+            const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+            k_step(checked, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1, yes);
+            k_step(checked, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0, yes);
+            sa = sa_n; sb = sb_n; kt += 2;
+        }
+        {
+            const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
+            const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
+            k_step(checked, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1, yes);
+            k_step(checked, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0, no);
+            sa = sa_n; sb = sb_n; kt += 2;
+        }
     }
-    for (; kt < KT - 2; kt += 2) {
-        const int sa_n = A_KC ? (sa == A_RING - 1 ? 0 : sa + 1) : 0;
-        const int sb_n = B_KC ? (sb == B_RING - 1 ? 0 : sb + 1) : 0;
-        k_step(checked, kt, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
-        k_step(checked, kt + 1, true, sa, sb, sa_n, sb_n, af1, bf1, af0, bf0);
-        sa = sa_n; sb = sb_n;
-    }
-    k_step(checked, KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1);
+    k_step(checked, KT - 2, false, sa, sb, sa, sb, af0, bf0, af1, bf1, no);
 #pragma unroll
     for (int j = 0; j < P; ++j) {
         if (ACC == ACC_FP8) {
@@ -705,6 +866,10 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
             compute_f16(j);
             if (j + 1 < P) convert_f16(j + 1, af1, bf1);
         }
+    }
+    if (PERSIST) {
+        tile_end(false);
+        return;
     }
 
     // ---- epilogue (wave-uniform choice of the output kind and of the scale granularity) --------
@@ -739,12 +904,24 @@ int group_m_setting()
     return v > 0 ? v : GROUP_M;
 }
 
-template <int FA, int FB, int ACC, bool A_KC, bool B_KC, int NB>
+// Compute units of the current device (the persistent form runs one workgroup on each).
+int compute_units()
+{
+    static std::atomic<int> cached[64];
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return 256;
+    if (dev < 64 && (n = cached[dev].load(std::memory_order_relaxed)) > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    if (dev < 64) cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
+template <int FA, int FB, int ACC, bool A_KC, bool B_KC, int NB, bool PERSIST = false>
 int launch_fast(const GemmArgs& g)
 {
     // the kernel needs more dynamic LDS than the default limit: raised once per device
     static std::atomic<unsigned long long> attr_set{0ull};
-    auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC, NB>;
+    auto kern = gemm_fast_kernel<FA, FB, ACC, A_KC, B_KC, NB, PERSIST>;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(FP8_ERR_DEVICE, "hipGetDevice failed");
     const unsigned long long bit = 1ull << (dev & 63);
@@ -757,11 +934,12 @@ int launch_fast(const GemmArgs& g)
     constexpr int BN = 64 * NB;
     const int tiles = (int)(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN));
     const int pairs = (int)((g.K + 2 * BK - 1) / (2 * BK));
-    const int splits = g.splits > 1 ? g.splits : 1;
-    hipLaunchKernelGGL(kern, dim3(tiles * splits), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
+    const int splits = !PERSIST && g.splits > 1 ? g.splits : 1;
+    const int grid = PERSIST ? min(tiles, compute_units()) : tiles * splits;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
                        (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting(), splits,
                        splits > 1 ? g.pairs_per_split : pairs);
-    return check_launch("gemm (tiled kernel)");
+    return check_launch(PERSIST ? "gemm (tiled kernel, persistent form)" : "gemm (tiled kernel)");
 }
 
 }  // namespace
@@ -776,6 +954,13 @@ static int launch_formats(const GemmArgs& g)
     constexpr bool A_KC = (FP8MM_LAYOUT & 2) == 0;   // A row-major M x K is K-contiguous
     constexpr bool B_KC = (FP8MM_LAYOUT & 1) != 0;   // B stored N x K is K-contiguous
     constexpr int ACC = FP8MM_ACC;
+    if (NB == 2 && g.persist) {                      // the persistent form exists for the narrow tile
+        if (g.fmtA == FP8_E4M3)
+            return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC, 2, true>(g)
+                                      : launch_fast<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC, 2, true>(g);
+        return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E5M2, FP8_E4M3, ACC, A_KC, B_KC, 2, true>(g)
+                                  : launch_fast<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC, 2, true>(g);
+    }
     if (g.fmtA == FP8_E4M3)
         return g.fmtB == FP8_E4M3 ? launch_fast<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC, NB>(g)
                                   : launch_fast<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC, NB>(g);

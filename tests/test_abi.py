@@ -75,7 +75,10 @@ def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
     plan = lambda ta, tb, M, N, K, a=A, b=B, c=C, sb=None: L.fp8_gemm_plan(a, ta, b, tb, c, M, N, K, sb)
     assert plan(0, 0, 8192, 49152, 12288) == T256                # config 4
     assert plan(1, 0, 8192, 12288, 49152) == T256                # config 5 with A stored K x M
-    assert plan(0, 0, 4096, 6144, 2048) == T128                  # config 3: 384 wide tiles would leave half a round empty
+    assert plan(0, 0, 4096, 6144, 2048) == T128 | fp8.FP8_PLAN_PERSISTENT   # config 3: 384 wide tiles would leave half a round empty;
+                                                                            # 768 narrow ones = 3 per compute unit, walked as one K loop
+    assert not plan(0, 0, 4096, 6144 + 16, 2048) & fp8.FP8_PLAN_PERSISTENT   # an edge tile: one workgroup per tile
+    assert plan(0, 0, 4096, 6144, 2048 + 64) == T128             # K not in whole stage pairs
     assert plan(0, 0, 256, 256, 256) in (T256, T128)             # config 1
     for ta in (0, 1):
         for tb in (0, 1):

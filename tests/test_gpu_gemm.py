@@ -248,7 +248,7 @@ def run_config(A_bits, B_bits, fmtA, fmtB, out_dtype, npts, nrows, label, full=F
         fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
     fp8.fp8_gemm_dscale(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C)
     torch.cuda.synchronize()
-    assert fp8.fp8_gemm_plan(qA, 0, qB, 0, C) in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), label
+    assert fp8.fp8_gemm_plan(qA, 0, qB, 0, C) & ~fp8.FP8_PLAN_PERSISTENT in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), label
     del dA, dB
     Aq, sA, Bq, sB = quantize_pair(A_bits, B_bits, fmtA, fmtB)
     assert np.float32(scale[0].item()) == sA and np.float32(scale[1].item()) == sB, label
@@ -497,3 +497,61 @@ def test_repeated_launches_give_identical_bits_while_memory_is_busy(transA, tran
         fp8.fp8_gemm_ex(dA, E5M2, transA, dB, E4M3, transB, C, 1.0, 1.0, flags)
         torch.cuda.synchronize()
         assert torch.equal(C, C0), "launch %d differs from the first in %d outputs" % (rep, int((C != C0).sum()))
+
+
+# ---- the persistent form of the narrow tile ---------------------------------------------------------
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_persistent_form_exact_integers_over_tile_sequences(transA, transB, mode):
+    """One workgroup per compute unit walks several 256 x 128 tiles as one K loop (loads of the next
+    tile issued during the current one, outputs stored straight from the registers).  Integer
+    operands (exact sums) over shapes that give the workgroups one, two and three tiles each, from the
+    shortest K the form takes (8 stages) on, fp32 and bf16 outputs; the result must also equal the
+    one-workgroup-per-tile kernel's bit for bit."""
+    rng = np.random.default_rng(300 + 2 * transA + transB)
+    flags = fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0
+    for (M, N, K) in [(1024, 9216, 512), (2048, 5120, 640), (4096, 6144, 512), (1024, 9216, 1152), (256, 128 * 5, 2048)]:
+        ai = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        bi = rng.integers(-4, 5, (K, N)).astype(np.float32)
+        Aq, Bq = oracle.quantize(ai, E4M3, 1.0), oracle.quantize(bi, E4M3, 1.0)
+        want = (ai.astype(np.float64) @ bi.astype(np.float64)) * 0.5
+        dA = to_dev(np.ascontiguousarray(Aq.T) if transA else Aq)
+        dB = to_dev(np.ascontiguousarray(Bq.T) if transB else Bq)
+        for out_dtype in (fp8.FP8_F32, fp8.FP8_BF16):
+            C = torch.full((M, N), 7.0, dtype=OUT[out_dtype], device="cuda")
+            with knob(fp8.FP8_KNOB_PERSIST, 2), knob(fp8.FP8_KNOB_TILE_N, 128):
+                assert fp8.fp8_gemm_plan(dA, transA, dB, transB, C) == fp8.FP8_PLAN_TILED_256x128 | fp8.FP8_PLAN_PERSISTENT
+                fp8.fp8_gemm_ex(dA, E4M3, transA, dB, E4M3, transB, C, 2.0, 1.0, flags)
+            C1 = torch.full((M, N), 8.0, dtype=OUT[out_dtype], device="cuda")
+            with knob(fp8.FP8_KNOB_PERSIST, 1), knob(fp8.FP8_KNOB_TILE_N, 128):
+                assert fp8.fp8_gemm_plan(dA, transA, dB, transB, C1) == fp8.FP8_PLAN_TILED_256x128
+                fp8.fp8_gemm_ex(dA, E4M3, transA, dB, E4M3, transB, C1, 2.0, 1.0, flags)
+            torch.cuda.synchronize()
+            assert torch.equal(C, C1), "persistent and per-tile kernels differ: %s" % ((M, N, K, out_dtype),)
+            got = out_to_f64(C)
+            ref = want if out_dtype == fp8.FP8_F32 else torch.from_numpy(want).to(torch.bfloat16).double().numpy()
+            assert np.array_equal(got, ref), "%s layout %d%d %s: %d outputs differ" % (
+                (M, N, K), transA, transB, mode, np.count_nonzero(got != ref))
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_persistent_form_random_codes_within_the_bound_and_repeatable(mode):
+    rng = np.random.default_rng(311)
+    M, N, K = 2048, 5120, 1024
+    A, B = random_codes(rng, (M, K), E5M2, 0x5F), random_codes(rng, (K, N), E4M3)
+    dA, dB = to_dev(A), to_dev(B)
+    flags = fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0
+    sA, sB = np.float32(2.5), np.float32(0.125)
+    with knob(fp8.FP8_KNOB_PERSIST, 2), knob(fp8.FP8_KNOB_TILE_N, 128):
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        fp8.fp8_gemm_ex(dA, E5M2, 0, dB, E4M3, 0, C, float(sA), float(sB), flags)
+        C2 = torch.empty_like(C)
+        fp8.fp8_gemm_ex(dA, E5M2, 0, dB, E4M3, 0, C2, torch.tensor([sA], device="cuda"), torch.tensor([sB], device="cuda"), flags)
+    torch.cuda.synchronize()
+    assert torch.equal(C, C2)
+    rows = np.array([0, 255, 256, 1000, M - 1])
+    S, T = oracle.gemm_rows(A, E5M2, B, E4M3, rows)
+    check(out_to_f64(C[torch.from_numpy(rows).cuda()]), S, T, sA, sB, fp8.FP8_F32, "persistent form", mode=mode)
+    w = freivalds_blocks(C, A, E5M2, B, E4M3, sA, sB, oracle.F32, rel=REL[mode], block=128, label="persistent form")
+    print("persistent form %s: block sums worst err/bound %.3f" % (mode, w), flush=True)
