@@ -435,8 +435,11 @@ def quantize_only(fp8, synth, torch, np, probes, args):
         sink = torch.zeros(32768 * 4, dtype=torch.int32, device="cuda")
         stream_rate(0, "streaming_read_cold", 2.0 * n, lambda i: xs[i].data_ptr(), lambda i: sink.data_ptr(), n16_in)
         stream_rate(3, "streaming_2reads_1write_cold", 3.0 * n, lambda i: xs[i].data_ptr(), lambda i: qs[i].data_ptr(), n // 16)
+        stream_rate(1, "streaming_write_cold", 1.0 * n, lambda i: None, lambda i: qs[i].data_ptr(), n // 16)
+        stream_rate(2, "streaming_copy_cold", 2.0 * n, lambda i: xs[i].data_ptr(), lambda i: qs[i].data_ptr(), n // 16)
         out["streaming_note"] = "plain kernels of libfp8probes.so (non-temporal 16-byte loads / stores, best of three grid sizes) " \
-                                "on the same rotating buffers: the board's ceiling for the amax and the cast access mix"
+                                "on the same rotating buffers: the board's ceiling for the access mix of the amax (read), the cast " \
+                                "(2 reads per write), the dequantize kernels (write-heavy: between write and copy)"
     del xs[1:], qs[1:]
     torch.cuda.empty_cache()
 
@@ -448,6 +451,14 @@ def quantize_only(fp8, synth, torch, np, probes, args):
     qt = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
     rate("cast_transpose_e4m3_16384x16384_both_orders", event_ms(torch, lambda: fp8.fp8_quantize_transpose(xm, 0, scale, qm, qt), iters, 3), 4.0)
     del qt
+    # the weight of the FFN-up layer (config 4), as the weight-gradient and data-gradient GEMMs want it in both orders
+    wr, wc = 12288, 49152
+    xw = torch.from_numpy(synth.config2(wr * wc).view(np.int16)).view(torch.bfloat16).cuda().view(wr, wc)
+    qw, qwt = torch.empty((wr, wc), dtype=torch.uint8, device="cuda"), torch.empty((wc, wr), dtype=torch.uint8, device="cuda")
+    ms = event_ms(torch, lambda: fp8.fp8_quantize_transpose(xw, 0, scale, qw, qwt), iters, 3)
+    out["cast_transpose_e4m3_12288x49152_both_orders"] = {"us": round(ms * 1e3, 1), "GB/s": round(4.0 * wr * wc / ms * 1e-6, 1),
+                                                          "frac_of_hbm_peak": round(4.0 * wr * wc / ms * 1e-6 / PEAK_HBM_GBS, 4)}
+    del xw, qw, qwt
     ar, sr = torch.zeros(rows, device="cuda"), torch.ones(rows, device="cuda")
     rate("amax_rows_16384x16384", event_ms(torch, lambda: fp8.fp8_amax_rows(xm, ar), iters, 3), 2.0)
     rate("cast_rows_e4m3_16384x16384", event_ms(torch, lambda: fp8.fp8_quantize_rows(xm, 0, sr, qm), iters, 3), 3.0)

@@ -143,21 +143,35 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_kernel(const void* __r
 }
 
 // ------------------------------------------------------------------------------------------
-// cast + transpose.  One workgroup per 128 x 128 tile of x.  A lane converts 8 (bf16) or 4 (fp32)
-// consecutive elements of a row; the bytes go out to q straight from the registers (the lanes of a
-// tile row cover its 128 bytes) and into an LDS copy of the tile.  The transposed tile comes out of
-// that copy through the transposing LDS read of gfx950 (ds_read_b64_tr_b8: 16 lanes read an 8 x 16
-// byte block and each receives one column of it), two per lane = 16 consecutive bytes of a row of
-// q^T; the pieces are put back into the buffer as the tile of q^T and stored 16 bytes per lane, 8
-// lanes per row: whole 128-byte lines (written as they come out of the transposing reads, every
-// store instruction would touch 16 lines for a half each: 3-14 % slower, measured).
-// Non-temporal stores change nothing here (measured on four shapes).
+// cast + transpose.  One workgroup per tile of 128 rows x 512 bytes of x (256 bf16 or 128 fp32
+// columns).  A lane converts 8 (bf16) or 4 (fp32) consecutive elements of a row; the bytes go out to q
+// straight from the registers (the lanes of a tile row cover its 256 or 128 bytes) and into an LDS
+// copy of the tile.  The transposed tile comes out of that copy through the transposing LDS read of
+// gfx950 (ds_read_b64_tr_b8: 16 lanes read an 8 x 16 byte block and each receives one column of it),
+// two per lane = 16 consecutive bytes of a row of q^T; the pieces are put back into the buffer as the
+// tile of q^T and stored 16 bytes per lane, 8 lanes per row: whole 128-byte lines (written as they
+// come out of the transposing reads, every store instruction would touch 16 lines for a half each:
+// 3-14 % slower, measured).  Non-temporal stores change nothing here (measured on four shapes).
+//
+// Tile order.  A tile's 128-byte pieces of q^T lie `rows` bytes apart.  Where that distance is a
+// power of two (4 KB and up) they all fall on the same few memory channels, and so do those of every
+// tile of the same tile row: walking the tiles along the rows of x then loses 15-20 % of the rate
+// (measured on 16384 x 16384 against 16640 x 16640).  There the tiles are walked diagonally instead
+// (tile row and tile column both change from one workgroup to the next); elsewhere along the rows of
+// x, which keeps the pieces of neighbouring tiles together in time and is 3-12 % faster than the
+// diagonal walk on such shapes (3 x 2^k rows included: 49152 x 12288 5.1 against 4.8 TB/s).
+// Measured, bf16 -> E4M3 with both outputs, bytes moved / time: 16384 x 16384 4.2 -> 5.2 TB/s with
+// the diagonal walk and the 256-column tile, 18432 x 16384 5.1 -> 5.4, 12288 x 49152 4.8 -> 5.0;
+// with q^T written to the places of q (no scatter) the same
+// kernel reaches 5.4, the plain cast 5.9 (cold).
 // ------------------------------------------------------------------------------------------
-constexpr int TT = 128;                       // tile edge
-constexpr int TT_PITCH = TT + 16;             // LDS row pitch in bytes (16-byte pad spreads the rows over the banks)
+constexpr int TT = 128;                       // tile rows; also the tile columns of the fp32 form
+constexpr int QT_PITCH = TT + 16;             // LDS row pitch of the q^T tile (16-byte pad spreads the rows over the banks)
 
 typedef int v2i __attribute__((ext_vector_type(2)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+
+template <int DT> struct TransposeTile { static constexpr int cols = DT == FP8_BF16 ? 256 : 128; };
 
 // Four scaled values -> 4 FP8 bytes, converter path with the special values routed to the integer path.
 template <int FMT>
@@ -171,17 +185,23 @@ __device__ __forceinline__ unsigned encode4(float y0, float y1, float y2, float 
 template <int DT, int FMT>
 __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
                                                                      const float* __restrict__ scale_dev,
-                                                                     uint8_t* __restrict__ q, uint8_t* __restrict__ qt)
+                                                                     uint8_t* __restrict__ q, uint8_t* __restrict__ qt,
+                                                                     int tiles_r, int tiles_c, bool diagonal)
 {
+    constexpr int TC = TransposeTile<DT>::cols;          // tile columns
+    constexpr int PITCH = TC + 16;                       // LDS row pitch of the tile of q
     constexpr int EPL = DT == FP8_BF16 ? 8 : 4;          // elements per lane per load (16 bytes)
-    constexpr int LPR = TT / EPL;                        // lanes per tile row
+    constexpr int LPR = TC / EPL;                        // lanes per tile row
     constexpr int RPP = kThreads / LPR;                  // tile rows per pass of the workgroup
     constexpr int PASSES = TT / RPP;
-    __shared__ __attribute__((aligned(16))) uint8_t tile[TT * TT_PITCH];
+    constexpr int LDS_BYTES = TT * PITCH > TC * QT_PITCH ? TT * PITCH : TC * QT_PITCH;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[LDS_BYTES];
     const float s = *scale_dev;
-    // tile order: along the rows of x (measured: square super-tiles of 4 .. 32 tiles change the rate by
-    // a few per cent in either direction depending on the shape)
-    const int64_t r0 = (int64_t)blockIdx.y * TT, c0 = (int64_t)blockIdx.x * TT;
+    const int b = blockIdx.x;
+    int ti, tj;
+    if (diagonal) { ti = b % tiles_r; tj = (b / tiles_r + ti) % tiles_c; }
+    else { ti = b / tiles_c; tj = b % tiles_c; }
+    const int64_t r0 = (int64_t)ti * TT, c0 = (int64_t)tj * TC;
     const int tid = threadIdx.x;
     const int lr = tid / LPR, lc = (tid % LPR) * EPL;    // lane's row within a pass, first column
 
@@ -203,12 +223,12 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
                               as_f32(v[p].y << 16) * s, as_f32(v[p].y & 0xffff0000u) * s);
             b1 = encode4<FMT>(as_f32(v[p].z << 16) * s, as_f32(v[p].z & 0xffff0000u) * s,
                               as_f32(v[p].w << 16) * s, as_f32(v[p].w & 0xffff0000u) * s);
-            *LDS_PTR(v2i, tile + tr * TT_PITCH + lc) = (v2i){(int)b0, (int)b1};
+            *LDS_PTR(v2i, tile + tr * PITCH + lc) = (v2i){(int)b0, (int)b1};
         } else {
             b0 = encode4<FMT>(as_f32(v[p].x) * s, as_f32(v[p].y) * s, as_f32(v[p].z) * s, as_f32(v[p].w) * s);
-            *LDS_PTR(unsigned, tile + tr * TT_PITCH + lc) = b0;
+            *LDS_PTR(unsigned, tile + tr * PITCH + lc) = b0;
         }
-        // q straight from the registers: the lanes of one tile row cover its 128 bytes
+        // q straight from the registers: the lanes of one tile row cover its bytes
         const int64_t r = r0 + tr, c = c0 + lc;
         if (q && r < rows && c < cols) {
             uint8_t* dst = q + (size_t)r * (size_t)cols + (size_t)c;
@@ -217,38 +237,39 @@ __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void
     }
     __syncthreads();
     // q^T: the transposing reads hand a lane 16 consecutive tile rows of one tile column = 16 bytes of
-    // a row of q^T; a wave instruction covers 16 columns x 64 rows, wave w owns the columns 32 w .. 32 w + 31.
-    // Stored like that a wave instruction would write 64-byte halves of 16 different lines; instead the
-    // pieces go back into the (by then idle) tile buffer as the tile of q^T and leave 16 bytes per lane,
-    // 8 lanes per 128-byte row.
+    // a row of q^T; a wave instruction covers 16 columns x 64 rows, wave w owns the columns
+    // (TC / 4) w .. (TC / 4) (w + 1) - 1.  Stored like that a wave instruction would write 64-byte
+    // halves of 16 different lines; instead the pieces go back into the (by then idle) buffer as the
+    // tile of q^T and leave 16 bytes per lane, 8 lanes per 128-byte row.
     const int w = tid >> 6, l = tid & 63;
     const int g = l >> 4, t16 = l & 15;
-    u32x4 piece[2][2];
+    constexpr int CBW = TC / 64;                                  // blocks of 16 columns per wave
+    u32x4 piece[CBW][2];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            const int tc0 = w * 32 + cb * 16;                 // first tile column of the 16-lane group's block
+            const int tc0 = w * (TC / 4) + cb * 16;           // first tile column of the 16-lane group's block
             const int tr0 = half * 64 + g * 16;               // first tile row of the lane's 16 bytes
             // lanes 2 k and 2 k + 1 of a group address the two 8-byte halves of tile row tr0 + k (+ 8)
-            const uint8_t* src = tile + (tr0 + (t16 >> 1)) * TT_PITCH + tc0 + (t16 & 1) * 8;
+            const uint8_t* src = tile + (tr0 + (t16 >> 1)) * PITCH + tc0 + (t16 & 1) * 8;
             const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, src));
-            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, src + 8 * TT_PITCH));
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(LDS_PTR(v2i, src + 8 * PITCH));
             piece[cb][half] = (u32x4){(unsigned)lo.x, (unsigned)lo.y, (unsigned)hi.x, (unsigned)hi.y};
         }
     __syncthreads();                                          // every wave has read what it needs of the tile
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < CBW; ++cb)
 #pragma unroll
         for (int half = 0; half < 2; ++half)
-            *LDS_PTR(u32x4, tile + (w * 32 + cb * 16 + t16) * TT_PITCH + half * 64 + g * 16) = piece[cb][half];
+            *LDS_PTR(u32x4, tile + (w * (TC / 4) + cb * 16 + t16) * QT_PITCH + half * 64 + g * 16) = piece[cb][half];
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < TT / 32; ++p) {
+    for (int p = 0; p < TC / 32; ++p) {
         const int tc = p * 32 + (tid >> 3), trc = (tid & 7) * 16;         // row of the q^T tile, first byte in it
         const int64_t orow = c0 + tc, ocol = r0 + trc;                    // position in q^T (cols x rows)
         if (orow < cols && ocol < rows)
-            *(u32x4*)(qt + (size_t)orow * (size_t)rows + (size_t)ocol) = *LDS_PTR(u32x4, tile + tc * TT_PITCH + trc);
+            *(u32x4*)(qt + (size_t)orow * (size_t)rows + (size_t)ocol) = *LDS_PTR(u32x4, tile + tc * QT_PITCH + trc);
     }
 }
 
@@ -499,12 +520,14 @@ int launch_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_
                               uint8_t* q_out, uint8_t* qt_out, hipStream_t stream)
 {
     if (rows == 0 || cols == 0) return FP8_OK;
-    const int64_t tiles_r = (rows + TT - 1) / TT, tiles_c = (cols + TT - 1) / TT;
+    const int tcols = in_dtype == FP8_BF16 ? TransposeTile<FP8_BF16>::cols : TransposeTile<FP8_F32>::cols;
+    const int64_t tiles_r = (rows + TT - 1) / TT, tiles_c = (cols + tcols - 1) / tcols;
     const bool vec = aligned16(x) && aligned16(qt_out) && (!q_out || aligned16(q_out)) && rows % 16 == 0 && cols % 16 == 0 &&
-                     tiles_r < 65536 && tiles_c < (1ll << 31);
+                     tiles_r * tiles_c < (1ll << 31);
     if (vec) {
-        const dim3 grid((unsigned)tiles_c, (unsigned)tiles_r);
-        FP8MM_DISPATCH_DT_FMT(quantize_transpose_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);
+        const dim3 grid((unsigned)(tiles_r * tiles_c));
+        const bool diagonal = rows >= 4096 && (rows & (rows - 1)) == 0;      // see "Tile order" at the kernel
+        FP8MM_DISPATCH_DT_FMT(quantize_transpose_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out, (int)tiles_r, (int)tiles_c, diagonal);
     } else {
         const dim3 grid(grid_for((size_t)rows * (size_t)cols, 4096));
         FP8MM_DISPATCH_DT_FMT(quantize_transpose_scalar_kernel, grid, x, rows, cols, scale_dev, q_out, qt_out);

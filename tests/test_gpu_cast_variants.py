@@ -107,7 +107,8 @@ def test_per_row_amax_scale_and_cast(dtype):
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("fmt", FMTS)
 def test_quantize_transpose(fmt, dtype):
-    for rows, cols in ((512, 384), (128, 128), (144, 1040), (16, 16), (33, 20), (1, 7), (300, 128)):
+    # (the last two: rows a power of two, where the tiles are walked diagonally, with ragged tiles)
+    for rows, cols in ((512, 384), (128, 128), (144, 1040), (16, 16), (33, 20), (1, 7), (300, 128), (4096, 272), (8192, 528)):
         x = tensor(rows * cols, 7 * rows + cols, dtype, specials=rows * cols >= 64).reshape(rows, cols)
         dx = to_dev(x)
         scale = np.float32(11.0)
