@@ -92,12 +92,16 @@ def main():
         amax = torch.zeros(1, device="cuda")
         scale = torch.ones(1, device="cuda")
         row_amax, row_scale = torch.zeros(rows, device="cuda"), torch.ones(rows, device="cuda")
+        yb = torch.empty(rows * cols, dtype=torch.bfloat16, device="cuda")
+        yf = torch.empty(rows * cols, dtype=torch.float32, device="cuda")
         for _ in range(args.iters):
             fp8.fp8_quantize_amax(x.view(-1), fp8.FP8_E4M3, scale, q.view(-1), amax)
             fp8.fp8_quantize_sr(x.view(-1), fp8.FP8_E4M3, scale, 1234, q.view(-1))
             fp8.fp8_quantize_transpose(x, fp8.FP8_E4M3, scale, q, qt)
             fp8.fp8_amax_rows(x, row_amax)
             fp8.fp8_quantize_rows(x, fp8.FP8_E4M3, row_scale, q)
+            fp8.fp8_dequantize(q.view(-1), fp8.FP8_E4M3, scale, yb)
+            fp8.fp8_dequantize(q.view(-1), fp8.FP8_E4M3, scale, yf)
     else:
         M, N, K, fmtA, out, gen = SHAPES[args.workload]
         if args.mnk:
