@@ -301,6 +301,8 @@ def main():
             others[name] = r
         result["other_workloads"] = others
         result["wgrad_split_k"] = split_k_leg(fp8, torch, args)
+        result["any_shape_kernel"] = any_shape_leg(fp8, torch, args)
+        torch.cuda.empty_cache()
         result["quantize_only"] = quantize_only(fp8, synth, torch, np, probes, args)
 
     print(json.dumps(result))
@@ -373,6 +375,25 @@ def split_k_leg(fp8, torch, args):
         out[mode] = {"one_workgroup_per_tile_ms": round(ms0, 4), "split_k_ms": round(ms1, 4),
                      "split_k_static_scratch_ms": None if ms2 is None else round(ms2, 4),
                      "speedup": round(ms0 / ms1, 2), "TFLOP/s": round(flops / ms1 * 1e-9, 1)}
+    return out
+
+
+def any_shape_leg(fp8, torch, args):
+    """A vocabulary projection with the weight stored [in, out] and an odd vocabulary size
+    (8192 x 50257 x 12288, B stored K x N): rows of B start anywhere, so the tiled kernel's direct loads
+    cannot take it and the any-shape matrix-core kernel runs; beside it the same product with N
+    padded to a multiple of 16 (tiled kernel)."""
+    M, K = 8192, 12288
+    g = torch.Generator(device="cuda").manual_seed(11)
+    A = torch.randint(0, 0x60, (M, K), dtype=torch.uint8, device="cuda", generator=g)
+    out = {}
+    for N, label in ((50257, "N_50257"), (50272, "N_50272_padded")):
+        B = torch.randint(0, 0x60, (K, N), dtype=torch.uint8, device="cuda", generator=g)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        plan = fp8.fp8_gemm_plan(A, 0, B, 0, C)
+        ms = event_ms(torch, lambda: fp8.fp8_gemm_ex(A, fp8.FP8_E4M3, 0, B, fp8.FP8_E4M3, 0, C, 1.0, 1.0, 0), 4, 2)
+        out[label] = {"plan": plan, "ms": round(ms, 3), "TFLOP/s": round(2.0 * M * N * K / ms * 1e-9, 1)}
+        del B, C
     return out
 
 

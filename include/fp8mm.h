@@ -221,8 +221,9 @@ int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dty
  * boundaries: N a multiple of 16 where B is given as K x N, M a multiple of 16 where A is
  * given as K x M (see fp8_gemm_ex); with B given as N x K any N goes.  A C that is not
  * 16-byte aligned, or whose rows are not (N not a multiple of 16), is stored element by
- * element.  The other shapes take a plain FMA kernel.  fp8_gemm_dscale reads the two
- * scales from device memory instead.
+ * element.  The other shapes and alignments take a second matrix-core kernel (register-staged
+ * loads, 128 x 128 tiles, the same arithmetic and bound, about a third of the rate; see
+ * fp8_gemm_plan).  fp8_gemm_dscale reads the two scales from device memory instead.
  */
 int fp8_gemm(const uint8_t* A, int fmtA, float sA,
              const uint8_t* B, int fmtB, float sB,
@@ -352,8 +353,12 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * no pointer is dereferenced: only shapes, storage orders and pointer alignment decide).  Pass the
  * pointers of the intended call; sB_per_column is the per-column factor vector of fp8_gemm_fused or
  * NULL.  Returns FP8_PLAN_NO_GEMM if M, N or K is 0, otherwise one of FP8_PLAN_TILED_256x256,
- * FP8_PLAN_TILED_256x128 (matrix-core kernel, tile chosen for how well it fills the chip) or
- * FP8_PLAN_FMA_KERNEL (any shape and alignment, far slower), ORed with
+ * FP8_PLAN_TILED_256x128 (the tiled matrix-core kernel, tile chosen for how well it fills the chip),
+ * FP8_PLAN_MFMA_ANY (the matrix-core kernel for every other shape and alignment: an odd K, operand
+ * rows that do not start on 16-byte boundaries, unaligned pointers; about a third of the tiled
+ * kernel's rate, ten times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
+ * meets that flag's bound a fortiori) or FP8_PLAN_FMA_KERNEL (plain FMAs: only when forced by
+ * FP8_KNOB_GEMM_KERNEL or for outputs of more than 2^31 - 1 tiles of 128 x 128), ORed with
  * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries, and
  * with FP8_PLAN_PERSISTENT where the 256 x 128 kernel runs in its persistent form (answered for
  * per-tensor factors, an fp32 output and the default accumulation mode; with a bf16 output or
@@ -362,7 +367,8 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * not the kernel: every plan computes the same product within the stated bounds.
  */
 typedef enum { FP8_PLAN_NO_GEMM = 0, FP8_PLAN_FMA_KERNEL = 1, FP8_PLAN_TILED_256x256 = 2,
-               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_ELEMENTWISE_STORES = 16, FP8_PLAN_PERSISTENT = 32 } fp8_plan_t;
+               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_MFMA_ANY = 4, FP8_PLAN_ELEMENTWISE_STORES = 16,
+               FP8_PLAN_PERSISTENT = 32 } fp8_plan_t;
 int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
                   int64_t M, int64_t N, int64_t K, const float* sB_per_column);
 
@@ -377,7 +383,8 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
  *   FP8_KNOB_TILE_N       0 the dispatcher chooses, 128 or 256 forces the tile width of the
  *                         matrix-core kernel (FP8MM_TILE_N)
  *   FP8_KNOB_GROUP_M      tile rows per band of the tile order, 0 = default 8 (FP8MM_GROUP_M)
- *   FP8_KNOB_GEMM_KERNEL  0 the dispatcher chooses, 1 always the plain FMA kernel (FP8MM_GEMM=generic)
+ *   FP8_KNOB_GEMM_KERNEL  0 the dispatcher chooses, 1 always the plain FMA kernel (FP8MM_GEMM=generic),
+ *                         2 always the any-shape matrix-core kernel (FP8MM_GEMM=any)
  *   FP8_KNOB_SPLIT_K      0 fp8_gemm_splitk chooses its number of K slices, n > 0 forces n (FP8MM_SPLIT_K)
  *   FP8_KNOB_CAST_RUN     length of the contiguous run one workgroup of the cast kernel owns, in units
  *                         of 4096 elements; 0 = default (4: 16 384 elements) (FP8MM_CAST_RUN)

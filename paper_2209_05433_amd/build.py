@@ -21,7 +21,7 @@ PROBES_LIB = os.path.join(PKG, "libfp8probes.so")     # measurement probes for b
 # (source, extra defines, object name)
 UNITS = [("gemm_tiled.hip", ["-DFP8MM_LAYOUT=%d" % k, "-DFP8MM_ACC=%d" % a], "gemm_tiled_l%d_a%d.o" % (k, a))
          for k in range(4) for a in range(2)] + \
-        [("gemm_dispatch.hip", [], "gemm_dispatch.o"), ("gemm_splitk.hip", [], "gemm_splitk.o"),
+        [("gemm_dispatch.hip", [], "gemm_dispatch.o"), ("gemm_splitk.hip", [], "gemm_splitk.o"), ("gemm_mfma_any.hip", [], "gemm_mfma_any.o"),
          ("cast_kernels.hip", [], "cast_kernels.o"),
          ("cast_variants.hip", [], "cast_variants.o"),
          ("api.hip", [], "api.o")]

@@ -41,6 +41,7 @@ static void seed_knobs()
     if ((e = getenv("FP8MM_TILE_N")) && (atoi(e) == 128 || atoi(e) == 256)) g_knob[FP8_KNOB_TILE_N] = atoi(e);
     if ((e = getenv("FP8MM_GROUP_M")) && atoi(e) > 0) g_knob[FP8_KNOB_GROUP_M] = atoi(e);
     if ((e = getenv("FP8MM_GEMM")) && e[0] == 'g') g_knob[FP8_KNOB_GEMM_KERNEL] = 1;
+    if (e && e[0] == 'a') g_knob[FP8_KNOB_GEMM_KERNEL] = 2;
     if ((e = getenv("FP8MM_SPLIT_K")) && atoi(e) > 0) g_knob[FP8_KNOB_SPLIT_K] = atoi(e);
     if ((e = getenv("FP8MM_CAST_RUN")) && atoi(e) > 0 && atoi(e) <= 64) g_knob[FP8_KNOB_CAST_RUN] = atoi(e);
     if ((e = getenv("FP8MM_PERSIST")) && atoi(e) >= 0 && atoi(e) <= 2) g_knob[FP8_KNOB_PERSIST] = atoi(e);
@@ -109,7 +110,7 @@ int fp8_set_knob(int which, int value)
         case FP8_KNOB_CAST_PATH: ok = value == 0 || value == 1; break;
         case FP8_KNOB_TILE_N: ok = value == 0 || value == 128 || value == 256; break;
         case FP8_KNOB_GROUP_M: ok = value >= 0 && value <= 4096; break;
-        case FP8_KNOB_GEMM_KERNEL: ok = value == 0 || value == 1; break;
+        case FP8_KNOB_GEMM_KERNEL: ok = value >= 0 && value <= 2; break;
         case FP8_KNOB_SPLIT_K: ok = value >= 0 && value <= 64; break;
         case FP8_KNOB_CAST_RUN: ok = value >= 0 && value <= 64; break;
         case FP8_KNOB_PERSIST: ok = value >= 0 && value <= 2; break;
@@ -424,6 +425,7 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
     g.ep.sB_dev = sB_per_column; g.ep.b_per_col = sB_per_column != nullptr;
     const GemmPlan plan = plan_gemm(g);
     const int kernel = plan.kernel == GEMM_GENERIC ? FP8_PLAN_FMA_KERNEL
+                     : plan.kernel == GEMM_MFMA_ANY ? FP8_PLAN_MFMA_ANY
                      : plan.kernel == GEMM_TILED_128 ? FP8_PLAN_TILED_256x128 : FP8_PLAN_TILED_256x256;
     return kernel | (plan.elementwise_stores ? FP8_PLAN_ELEMENTWISE_STORES : 0) | (plan.persistent ? FP8_PLAN_PERSISTENT : 0);
 }

@@ -71,6 +71,11 @@ constexpr int TILE_M = 256, TILE_N = 256, TILE_K = 64;
 
 int launch_gemm(const GemmArgs& g);
 
+// The matrix-core kernel for any shape and alignment (gemm_mfma_any.hip): 128 x 128 tiles, operands
+// staged through registers.  Takes every problem with M, N, K > 0 whose tile count fits the grid.
+bool mfma_any_takes(const GemmArgs& g);
+int launch_mfma_any(const GemmArgs& g);
+
 // The tiled kernel instance for g's storage orders and accumulation mode, with g.tile_n, g.splits,
 // g.pairs_per_split and g.ep.ragged_n as given (the caller has checked that the tiled kernel takes
 // the problem).
@@ -90,11 +95,33 @@ int fill_gemm_args(const char* who, GemmArgs& g, const uint8_t* A, int fmtA, int
                    const float* sA_dev, const float* sB_dev, int flags, void* stream);
 
 // The dispatcher's decision for a problem with M, N, K > 0 (what launch_gemm acts on).
-enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3 };
+enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3, GEMM_MFMA_ANY = 4 };
 struct GemmPlan { int kernel; bool elementwise_stores; bool persistent; };
 GemmPlan plan_gemm(const GemmArgs& g);
 
-// ---- small device helpers used by both kernels ----------------------------------------------
+// ---- small device helpers used by the kernels -------------------------------------------------
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+// 8 FP8 bytes (two dwords) -> 8 fp16 values, exact (both formats embed in fp16; E4M3's NaN becomes NaN).
+template <int FMT>
+__device__ __forceinline__ v8h widen8(int lo, int hi)
+{
+    v2h p0, p1, p2, p3;
+    if (FMT == FP8_E4M3) {
+        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, false);
+        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, true);
+        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, false);
+        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, true);
+    } else {
+        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, false);
+        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, true);
+        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, false);
+        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, true);
+    }
+    return (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
+}
+
 __device__ __forceinline__ float scale_value(const float* dev, float host) { return dev ? *dev : host; }
 
 // Largest of `bits` (sign-stripped fp32 patterns; NaN patterns sort above infinity) over the wave,

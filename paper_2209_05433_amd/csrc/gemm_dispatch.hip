@@ -1,8 +1,10 @@
 // GEMM dispatcher and the generic kernel for gfx950 (MI355X).
 //
 // Shapes and pointers that meet the tiled kernel's conditions (K a multiple of 16, 16-byte aligned
-// operands whose rows start on 16-byte boundaries) go to one of its instances; everything else is
-// computed by the generic kernel below: any shape, any alignment, every storage order, the same epilogue
+// operands whose rows start on 16-byte boundaries) go to one of its instances; everything else to the
+// matrix-core kernel for any shape (gemm_mfma_any.hip).  The generic kernel below (plain FMAs: any
+// shape, any alignment, every storage order, the same epilogue) remains as the independent
+// cross-check the tests force through a knob, and for outputs with more tiles than a grid holds
 // (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
 #include "gemm_common.hpp"
 
@@ -105,8 +107,9 @@ __global__ void zero_fill_kernel(unsigned char* p, size_t nbytes)
 
 __global__ void zero_cell_kernel(unsigned* p) { *p = 0u; }
 
-// The knob FP8_KNOB_GEMM_KERNEL = 1 forces the generic kernel.
+// The knob FP8_KNOB_GEMM_KERNEL = 1 forces the generic kernel, = 2 the any-shape matrix-core kernel.
 bool force_generic() { return knob(FP8_KNOB_GEMM_KERNEL) == 1; }
+bool force_mfma_any() { return knob(FP8_KNOB_GEMM_KERNEL) == 2; }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -116,7 +119,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 GemmPlan plan_gemm(const GemmArgs& g)
 {
     const int64_t M = g.M, N = g.N, K = g.K;
-    GemmPlan plan{GEMM_GENERIC, false, false};
+    GemmPlan plan{!force_generic() && mfma_any_takes(g) ? GEMM_MFMA_ANY : GEMM_GENERIC, false, false};
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
                         K < (1ll << 31) &&
@@ -131,7 +134,7 @@ GemmPlan plan_gemm(const GemmArgs& g)
     // element-wise stores of the epilogue: with B stored N x K any N goes (a vocabulary-sized
     // output layer, weights stored [out, in]).
     const bool c_lines = N % 16 == 0 && aligned16(g.C) && (!g.ep.b_per_col || aligned16(g.ep.sB_dev));
-    const bool fast = !force_generic() && aligned16(g.A) && aligned16(g.B) && fits32 && K % 16 == 0 &&
+    const bool fast = !force_generic() && !force_mfma_any() && aligned16(g.A) && aligned16(g.B) && fits32 && K % 16 == 0 &&
                       (g.transB || N % 16 == 0) && (!g.transA || M % 16 == 0);
     if (!fast) return plan;
     // Tile width.  One workgroup per compute unit (256 of them) runs at a time.  The 256 x 128
@@ -189,6 +192,7 @@ int launch_gemm(const GemmArgs& g)
         return check_launch("gemm (K = 0 fill)");
     }
     const GemmPlan plan = plan_gemm(g);
+    if (plan.kernel == GEMM_MFMA_ANY) return launch_mfma_any(g);
     if (plan.kernel != GEMM_GENERIC) {
         GemmArgs gt = g;
         gt.ep.ragged_n = plan.elementwise_stores ? 1 : 0;

@@ -59,8 +59,6 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -136,25 +134,6 @@ __device__ __forceinline__ TileMap map_tile(int bid, int tiles_m, int tiles_n, i
     t.tm = band * group_m + q % rows;
     t.tn = q / rows;
     return t;
-}
-
-// 8 FP8 bytes (two dwords) -> 8 fp16 values, exact.
-template <int FMT>
-__device__ __forceinline__ v8h widen8(int lo, int hi)
-{
-    v2h p0, p1, p2, p3;
-    if (FMT == FP8_E4M3) {
-        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, false);
-        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)lo, 1.0f, true);
-        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, false);
-        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8((unsigned)hi, 1.0f, true);
-    } else {
-        p0 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, false);
-        p1 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)lo, 1.0f, true);
-        p2 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, false);
-        p3 = __builtin_amdgcn_cvt_scalef32_pk_f16_bf8((unsigned)hi, 1.0f, true);
-    }
-    return (v8h){p0.x, p0.y, p1.x, p1.y, p2.x, p2.y, p3.x, p3.y};
 }
 
 // One operand of the tile as the kernel sees it.  r = row of A / column of B inside the EXT-wide

@@ -68,10 +68,10 @@ def test_header_is_plain_c_and_a_c_program_links(tmp_path):
 def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
     """fp8_gemm_plan is host logic over shapes, storage orders and pointer alignment (no pointer is
     dereferenced, so made-up aligned addresses do): the five workloads and the layer GEMMs around them
-    must land on the matrix-core kernel, and only shapes it cannot take on the FMA kernel."""
+    must land on the tiled matrix-core kernel, and only shapes it cannot take on the any-shape one."""
     L = fp8.lib()
     A, B, C = 1 << 20, 1 << 24, 1 << 28                         # 16-byte aligned stand-ins
-    T256, T128, FMA, EW = fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_FMA_KERNEL, fp8.FP8_PLAN_ELEMENTWISE_STORES
+    T256, T128, ANY, EW = fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_MFMA_ANY, fp8.FP8_PLAN_ELEMENTWISE_STORES
     plan = lambda ta, tb, M, N, K, a=A, b=B, c=C, sb=None: L.fp8_gemm_plan(a, ta, b, tb, c, M, N, K, sb)
     assert plan(0, 0, 8192, 49152, 12288) == T256                # config 4
     assert plan(1, 0, 8192, 12288, 49152) == T256                # config 5 with A stored K x M
@@ -84,13 +84,13 @@ def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
         for tb in (0, 1):
             assert plan(ta, tb, 12288, 49152, 8192) == T256      # weight gradient of the FFN-up layer, any storage order
     assert plan(0, 1, 8192, 50257, 12288) == T256 | EW           # vocabulary-sized N with weights stored [out, in]
-    assert plan(0, 0, 8192, 50257, 12288) == FMA                 # ... stored [in, out]: rows of B start anywhere
-    assert plan(1, 0, 50257, 12288, 8192) == FMA                 # rows of an M-contiguous A start anywhere
+    assert plan(0, 0, 8192, 50257, 12288) == ANY                 # ... stored [in, out]: rows of B start anywhere: the any-shape matrix-core kernel
+    assert plan(1, 0, 50257, 12288, 8192) == ANY                 # rows of an M-contiguous A start anywhere
     assert plan(0, 0, 512, 512, 448) in (T256, T128)             # K = 7 stages of 64: the last stage pair is half zeros
     assert plan(0, 0, 8192, 12288, 12352) == T256                # K = 64 x odd
     assert plan(0, 1, 8192, 12288, 12304) == T256                # K a multiple of 16 only
-    assert plan(0, 0, 512, 512, 440) == FMA                      # K not a multiple of 16: rows of A start anywhere
-    assert plan(0, 0, 512, 512, 512, a=A + 4) == FMA             # operand not 16-byte aligned
+    assert plan(0, 0, 512, 512, 440) == ANY                      # K not a multiple of 16: rows of A start anywhere
+    assert plan(0, 0, 512, 512, 512, a=A + 4) == ANY             # operand not 16-byte aligned
     assert plan(0, 0, 4096, 4096, 512, c=C + 2) == T256 | EW     # output not 16-byte aligned
     assert plan(0, 0, 4096, 4096, 512, sb=C + 4) == T256 | EW    # per-column factors not 16-byte aligned
     assert plan(0, 0, 0, 5, 5) == fp8.FP8_PLAN_NO_GEMM and plan(0, 0, 5, 5, 0) == fp8.FP8_PLAN_NO_GEMM
@@ -108,8 +108,12 @@ def test_knobs_round_trip_and_reject_bad_values():
     assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_TILED_256x256
     assert fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 1) == 0
     assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_FMA_KERNEL
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 512, 500, 77, None) == fp8.FP8_PLAN_FMA_KERNEL
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 2) == 1
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_MFMA_ANY
     fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 0)
-    for knob, bad in ((fp8.FP8_KNOB_TILE_N, 64), (fp8.FP8_KNOB_CAST_PATH, 2), (fp8.FP8_KNOB_SPLIT_K, 65), (99, 0)):
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, (1 << 31) * 128, 128 * 3, 77, None) == fp8.FP8_PLAN_FMA_KERNEL   # more 128 x 128 tiles than a grid holds
+    for knob, bad in ((fp8.FP8_KNOB_TILE_N, 64), (fp8.FP8_KNOB_CAST_PATH, 2), (fp8.FP8_KNOB_SPLIT_K, 65), (fp8.FP8_KNOB_GEMM_KERNEL, 3), (99, 0)):
         with pytest.raises(fp8.Fp8Error):
             fp8.fp8_set_knob(knob, bad)
 
