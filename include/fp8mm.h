@@ -222,7 +222,7 @@ int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dty
  * given as K x M (see fp8_gemm_ex); with B given as N x K any N goes.  A C that is not
  * 16-byte aligned, or whose rows are not (N not a multiple of 16), is stored element by
  * element.  The other shapes and alignments take a second matrix-core kernel (register-staged
- * loads, 128 x 128 tiles, the same arithmetic and bound, about a third of the rate; see
+ * loads, 128 x 128 tiles, the same arithmetic and bound, about half the rate; see
  * fp8_gemm_plan).  fp8_gemm_dscale reads the two scales from device memory instead.
  */
 int fp8_gemm(const uint8_t* A, int fmtA, float sA,
@@ -355,8 +355,8 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * NULL.  Returns FP8_PLAN_NO_GEMM if M, N or K is 0, otherwise one of FP8_PLAN_TILED_256x256,
  * FP8_PLAN_TILED_256x128 (the tiled matrix-core kernel, tile chosen for how well it fills the chip),
  * FP8_PLAN_MFMA_ANY (the matrix-core kernel for every other shape and alignment: an odd K, operand
- * rows that do not start on 16-byte boundaries, unaligned pointers; about a third of the tiled
- * kernel's rate, ten times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
+ * rows that do not start on 16-byte boundaries, unaligned pointers; about half of the tiled
+ * kernel's rate, fifteen times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
  * meets that flag's bound a fortiori) or FP8_PLAN_FMA_KERNEL (plain FMAs: only when forced by
  * FP8_KNOB_GEMM_KERNEL or for outputs of more than 2^31 - 1 tiles of 128 x 128), ORed with
  * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries, and

@@ -20,7 +20,7 @@
 //     holds (arXiv 2209.05433, Section 2: FP8 operands, single-precision accumulation, factors
 //     taken out once per output);
 //   - the epilogue is that of the generic kernel, element by element (any N, any output alignment).
-// 36 KB of LDS and about 160 registers per lane: several workgroups share a compute unit and hide
+// 32 KB of LDS and about 150 registers per lane: several workgroups share a compute unit and hide
 // each other's barriers and load latencies; nothing here is pipelined by hand.
 #include "gemm_common.hpp"
 
@@ -37,7 +37,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int FT = 128;                 // tile edge
 constexpr int FK = 64;                  // K per stage
 constexpr int NV = FK / 32;             // 16-byte vectors per thread, operand and stage
-constexpr int FPITCH = 2 * FK + 16;     // bytes per LDS row: FK halves and a pad (keeps 16-byte alignment, spreads the banks)
+constexpr int FPITCH = 2 * FK;          // bytes per LDS row: FK halves = 8 chunks of 16 bytes
 constexpr int FGROUP = 8;               // tile rows per band of the tile order
 
 // fp32 -> bf16 bits, round to nearest even; NaN stays NaN.
@@ -64,13 +64,14 @@ __device__ __forceinline__ u32x4 load16_guarded(const uint8_t* p, bool whole, in
 
 // Vector v (of NV) of the thread's bytes of one operand for the stage that starts at k0.  `ext` = rows
 // of op(A) / columns of op(B), t0 = first one of the tile.
-//   KC (contiguous along K: element (r, k) at base[r K + k]): row tid / 2, K bytes 32 v + 16 (tid % 2) ..
+//   KC (contiguous along K: element (r, k) at base[r K + k]): row 64 v + tid / 4, K bytes 16 (tid % 4) ..
+//      (four lanes cover the 64 bytes of a row: a wave's load touches 16 rows, not 32)
 //   MC (contiguous along M / N: element (r, k) at base[k ext + r]): K-row 32 v + tid / 8, rows 16 (tid % 8) ..
 template <bool KC>
 __device__ __forceinline__ u32x4 fetch_stage(const uint8_t* base, int64_t ext, int64_t K, int64_t t0, int64_t k0, int tid, int v)
 {
     if (KC) {
-        const int64_t r = t0 + (tid >> 1), k = k0 + 32 * v + (tid & 1) * 16;
+        const int64_t r = t0 + 64 * v + (tid >> 2), k = k0 + (tid & 3) * 16;
         if (r >= ext) return (u32x4){0u, 0u, 0u, 0u};
         return load16_guarded(base + r * K + k, k + 16 <= K, K - k);
     }
@@ -79,24 +80,50 @@ __device__ __forceinline__ u32x4 fetch_stage(const uint8_t* base, int64_t ext, i
     return load16_guarded(base + k * ext + r, r + 16 <= ext, ext - r);
 }
 
-// The same 16 bytes, widened, into the operand's LDS image (row = row of op(A) / column of op(B)
-// inside the tile, FK halves along K per row).
+// LDS image of an operand: row = row of op(A) / column of op(B) inside the tile, FK halves along K
+// per row as 8 chunks of 16 bytes; chunk c of row `row` sits at position c ^ swz(row).  The first
+// term of swz is the swizzle of the tiled kernel's K-contiguous slabs (same row length, same
+// 16-byte fragment reads: conflict-free there); the second spreads the 8 column groups of a
+// transposing write (rows 16 apart, which otherwise meet in one bank: measured, 75 % of the active
+// LDS cycles were conflict cycles and the LDS was busy 90 % of the time) and is constant over the
+// 16 rows that one pass of a fragment read covers.
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 4)) & 7; }
+
+// The thread's 16 bytes, widened, into the image.
 template <int FMT, bool KC>
 __device__ __forceinline__ void store_stage(uint8_t* img, u32x4 x, int tid, int v)
 {
     const v8h lo = widen8<FMT>((int)x.x, (int)x.y), hi = widen8<FMT>((int)x.z, (int)x.w);
     if (KC) {
-        uint8_t* dst = img + (tid >> 1) * FPITCH + (32 * v + (tid & 1) * 16) * 2;
-        *LDS_PTR(v8h, dst) = lo;
-        *LDS_PTR(v8h, dst + 16) = hi;
+        const int row = 64 * v + (tid >> 2), c = 2 * (tid & 3);   // chunks c, c + 1
+        uint8_t* dst = img + row * FPITCH;
+        *LDS_PTR(v8h, dst + ((c ^ swz(row)) * 16)) = lo;
+        *LDS_PTR(v8h, dst + (((c + 1) ^ swz(row)) * 16)) = hi;
     } else {
-        uint8_t* dst = img + ((tid & 7) * 16) * FPITCH + (32 * v + (tid >> 3)) * 2;
+        const int k = 32 * v + (tid >> 3), row0 = (tid & 7) * 16;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            *LDS_PTR(_Float16, dst + j * FPITCH) = lo[j];
-            *LDS_PTR(_Float16, dst + (8 + j) * FPITCH) = hi[j];
+        for (int j = 0; j < 16; ++j) {
+            const int row = row0 + j;
+            *LDS_PTR(_Float16, img + row * FPITCH + (((k >> 3) ^ swz(row)) * 16) + (k & 7) * 2) = j < 8 ? lo[j] : hi[j - 8];
         }
     }
+}
+
+// Workgroup id -> tile.  Ids go round-robin over the 8 XCDs (each with its own L2); XCD x gets one
+// contiguous run of the order below, so that the tiles it works on at a time share a few row slabs
+// of A and column slabs of B in its L2 (dealt out id by id, every XCD streamed all of B once per
+// band: 47 GB of L2 fills for 0.7 GB of operands, measured).  Order: bands of FGROUP tile rows,
+// down the rows of a band first, then to the next tile column.
+__device__ __forceinline__ void tile_of(int64_t bid, int64_t tiles_m, int64_t tiles_n, int64_t& tm, int64_t& tn)
+{
+    const int64_t total = tiles_m * tiles_n;
+    const int64_t x = bid % 8, idx = bid / 8, base = total / 8, rem = total % 8;
+    const int64_t p = x * base + (x < rem ? x : rem) + idx;
+    const int64_t band_tiles = FGROUP * tiles_n;
+    const int64_t band = p / band_tiles, q = p - band * band_tiles;
+    const int64_t rows = tiles_m - band * FGROUP < FGROUP ? tiles_m - band * FGROUP : FGROUP;
+    tm = band * FGROUP + q % rows;
+    tn = q / rows;
 }
 
 template <int FMT_A, int FMT_B, bool A_KC, bool B_KC>
@@ -109,13 +136,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63;
     const int wm = w >> 1, wn = w & 1, r = l & 31, h = l >> 5;
-    // tile order: bands of FGROUP tile rows, down the rows of a band first, then to the next tile
-    // column (the workgroups in flight then share a few row slabs of A and column slabs of B)
     const int64_t tiles_m = (M + FT - 1) / FT, tiles_n = (N + FT - 1) / FT;
-    const int64_t bid = blockIdx.x, band_tiles = FGROUP * tiles_n;
-    const int64_t band = bid / band_tiles, q = bid - band * band_tiles;
-    const int64_t rows = tiles_m - band * FGROUP < FGROUP ? tiles_m - band * FGROUP : FGROUP;
-    const int64_t m0 = (band * FGROUP + q % rows) * FT, n0 = (q / rows) * FT;
+    int64_t tm, tn;
+    tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = tm * FT, n0 = tn * FT;
 
     v16f acc[2][2];                                   // [block of 32 columns][block of 32 rows]
 #pragma unroll
@@ -139,8 +163,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
         }
         __syncthreads();
         if (k0 + FK < K) {                            // the next stage's bytes travel while this one is multiplied
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
+#pragma unroll                                        // (a second register set, two stages ahead, cost a wave of
+            for (int v = 0; v < NV; ++v) {            // occupancy and measured 4 % slower)
                 ra[v] = fetch_stage<A_KC>(A, M, K, m0, k0 + FK, tid, v);
                 rb[v] = fetch_stage<B_KC>(B, N, K, n0, k0 + FK, tid, v);
             }
@@ -153,8 +177,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
             v8h af[2], bf[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                af[i] = *LDS_PTR(v8h, As + (wm * 64 + i * 32 + r) * FPITCH + (16 * s + 8 * h) * 2);
-                bf[i] = *LDS_PTR(v8h, Bs + (wn * 64 + i * 32 + r) * FPITCH + (16 * s + 8 * h) * 2);
+                const int ra_ = wm * 64 + i * 32 + r, rb_ = wn * 64 + i * 32 + r;
+                const int c = 2 * h + (s & 1) + 4 * (s >> 1);      // which 8 of the 64 halves: any assignment that is
+                af[i] = *LDS_PTR(v8h, As + ra_ * FPITCH + ((c ^ swz(ra_)) * 16));    // the same for A and B will do;
+                bf[i] = *LDS_PTR(v8h, Bs + rb_ * FPITCH + ((c ^ swz(rb_)) * 16));    // this one is the tiled kernel's
             }
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
