@@ -354,6 +354,9 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * pointers of the intended call; sB_per_column is the per-column factor vector of fp8_gemm_fused or
  * NULL.  Returns FP8_PLAN_NO_GEMM if M, N or K is 0, otherwise one of FP8_PLAN_TILED_256x256,
  * FP8_PLAN_TILED_256x128 (the tiled matrix-core kernel, tile chosen for how well it fills the chip),
+ * FP8_PLAN_TILED_MIXED (the same kernel with both tile widths in one launch: 256-wide tiles for the
+ * first columns of the output, 128-wide ones for the rest, where that fills the rounds of workgroups
+ * better than either width alone),
  * FP8_PLAN_MFMA_ANY (the matrix-core kernel for every other shape and alignment: an odd K, operand
  * rows that do not start on 16-byte boundaries, unaligned pointers; about half of the tiled
  * kernel's rate, fifteen times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
@@ -367,7 +370,8 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * not the kernel: every plan computes the same product within the stated bounds.
  */
 typedef enum { FP8_PLAN_NO_GEMM = 0, FP8_PLAN_FMA_KERNEL = 1, FP8_PLAN_TILED_256x256 = 2,
-               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_MFMA_ANY = 4, FP8_PLAN_ELEMENTWISE_STORES = 16,
+               FP8_PLAN_TILED_256x128 = 3, FP8_PLAN_MFMA_ANY = 4, FP8_PLAN_TILED_MIXED = 5,
+               FP8_PLAN_ELEMENTWISE_STORES = 16,
                FP8_PLAN_PERSISTENT = 32 } fp8_plan_t;
 int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
                   int64_t M, int64_t N, int64_t K, const float* sB_per_column);
@@ -391,9 +395,12 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
  *   FP8_KNOB_PERSIST      the persistent form of the matrix-core kernel (one workgroup per compute unit
  *                         walks several tiles as one K loop): 0 where the dispatcher finds it pays,
  *                         1 never, 2 wherever its conditions hold (FP8MM_PERSIST)
+ *   FP8_KNOB_MIXED        both tile widths in one launch (FP8_PLAN_TILED_MIXED): 0 where the dispatcher's
+ *                         model of the run time prefers it, 1 never, 2 wherever it is possible (FP8MM_MIXED)
  */
 typedef enum { FP8_KNOB_CAST_PATH = 0, FP8_KNOB_TILE_N = 1, FP8_KNOB_GROUP_M = 2, FP8_KNOB_GEMM_KERNEL = 3,
-               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_CAST_RUN = 5, FP8_KNOB_PERSIST = 6, FP8_KNOB_COUNT = 7 } fp8_knob_t;
+               FP8_KNOB_SPLIT_K = 4, FP8_KNOB_CAST_RUN = 5, FP8_KNOB_PERSIST = 6, FP8_KNOB_MIXED = 7,
+               FP8_KNOB_COUNT = 8 } fp8_knob_t;
 int fp8_set_knob(int knob, int value);
 int fp8_get_knob(int knob);
 

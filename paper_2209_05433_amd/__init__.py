@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     fp8_gemm_mfma8, fp8_gemm_mfma8_dscale, fp8_gemm_ex, fp8_gemm_splitk, fp8_gemm_splitk_workspace_size, fp8_gemm_splitk_static, FP8_SPLITK_STATIC_BYTES, FP8_GEMM_MFMA8, fp8_gemm_fused, fp8_quantize_amax, fp8_quantize_sr, fp8_scale_from_amax_history, fp8_scale_from_amax_n,
     fp8_amax_rows, fp8_quantize_rows, fp8_quantize_transpose,
     FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2, fp8_gemm_plan,
-    FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128, FP8_PLAN_MFMA_ANY, FP8_PLAN_ELEMENTWISE_STORES,
-    fp8_set_knob, fp8_get_knob, FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN, FP8_KNOB_PERSIST, FP8_PLAN_PERSISTENT,
+    FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128, FP8_PLAN_MFMA_ANY, FP8_PLAN_TILED_MIXED, FP8_PLAN_ELEMENTWISE_STORES,
+    fp8_set_knob, fp8_get_knob, FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN, FP8_KNOB_PERSIST, FP8_KNOB_MIXED, FP8_PLAN_PERSISTENT,
     fp8_last_error, fp8_version,
 )

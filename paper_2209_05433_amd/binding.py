@@ -16,10 +16,10 @@ FP8_AMAX_WORKSPACE_BYTES = 16384
 FP8_SPLITK_STATIC_BYTES = 64 << 20
 FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
-FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128, FP8_PLAN_MFMA_ANY = 0, 1, 2, 3, 4
+FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128, FP8_PLAN_MFMA_ANY, FP8_PLAN_TILED_MIXED = 0, 1, 2, 3, 4, 5
 FP8_PLAN_ELEMENTWISE_STORES = 16
 FP8_PLAN_PERSISTENT = 32
-FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN, FP8_KNOB_PERSIST = 0, 1, 2, 3, 4, 5, 6
+FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN, FP8_KNOB_PERSIST, FP8_KNOB_MIXED = 0, 1, 2, 3, 4, 5, 6, 7
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 

@@ -45,6 +45,7 @@ static void seed_knobs()
     if ((e = getenv("FP8MM_SPLIT_K")) && atoi(e) > 0) g_knob[FP8_KNOB_SPLIT_K] = atoi(e);
     if ((e = getenv("FP8MM_CAST_RUN")) && atoi(e) > 0 && atoi(e) <= 64) g_knob[FP8_KNOB_CAST_RUN] = atoi(e);
     if ((e = getenv("FP8MM_PERSIST")) && atoi(e) >= 0 && atoi(e) <= 2) g_knob[FP8_KNOB_PERSIST] = atoi(e);
+    if ((e = getenv("FP8MM_MIXED")) && atoi(e) >= 0 && atoi(e) <= 2) g_knob[FP8_KNOB_MIXED] = atoi(e);
 }
 
 int knob(int which)
@@ -114,6 +115,7 @@ int fp8_set_knob(int which, int value)
         case FP8_KNOB_SPLIT_K: ok = value >= 0 && value <= 64; break;
         case FP8_KNOB_CAST_RUN: ok = value >= 0 && value <= 64; break;
         case FP8_KNOB_PERSIST: ok = value >= 0 && value <= 2; break;
+        case FP8_KNOB_MIXED: ok = value >= 0 && value <= 2; break;
     }
     if (!ok) return -fail(FP8_ERR_INVALID_ARG, "fp8_set_knob: value %d is not valid for knob %d", value, which);
     const int old = knob(which);                    // seeds from the environment first
@@ -426,6 +428,7 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
     const GemmPlan plan = plan_gemm(g);
     const int kernel = plan.kernel == GEMM_GENERIC ? FP8_PLAN_FMA_KERNEL
                      : plan.kernel == GEMM_MFMA_ANY ? FP8_PLAN_MFMA_ANY
+                     : plan.kernel == GEMM_TILED_MIXED ? FP8_PLAN_TILED_MIXED
                      : plan.kernel == GEMM_TILED_128 ? FP8_PLAN_TILED_256x128 : FP8_PLAN_TILED_256x256;
     return kernel | (plan.elementwise_stores ? FP8_PLAN_ELEMENTWISE_STORES : 0) | (plan.persistent ? FP8_PLAN_PERSISTENT : 0);
 }

@@ -46,6 +46,8 @@ struct GemmArgs {
     bool transA, transB;          // A stored K x M / B stored N x K
     int acc;                      // ACC_*
     int tile_n;                   // width of the tiled kernel's tile: 256, or 128 (chosen by the dispatcher)
+    int wide_cols;                // tiled kernel: > 0 = both widths in one launch, this many tile columns of 256 first,
+                                  // 128-wide tiles for the rest of N (chosen by the dispatcher)
     bool persist;                 // tiled kernel, narrow tile: the persistent form (one workgroup per compute unit walks
                                   // several tiles as one K loop); set by the dispatcher where its conditions hold
     int splits, pairs_per_split;  // tiled kernel only: splits > 1 cuts K into slices of pairs_per_split stage pairs
@@ -95,8 +97,8 @@ int fill_gemm_args(const char* who, GemmArgs& g, const uint8_t* A, int fmtA, int
                    const float* sA_dev, const float* sB_dev, int flags, void* stream);
 
 // The dispatcher's decision for a problem with M, N, K > 0 (what launch_gemm acts on).
-enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3, GEMM_MFMA_ANY = 4 };
-struct GemmPlan { int kernel; bool elementwise_stores; bool persistent; };
+enum { GEMM_GENERIC = 1, GEMM_TILED_256 = 2, GEMM_TILED_128 = 3, GEMM_MFMA_ANY = 4, GEMM_TILED_MIXED = 5 };
+struct GemmPlan { int kernel; bool elementwise_stores; bool persistent; int wide_cols; };
 GemmPlan plan_gemm(const GemmArgs& g);
 
 // ---- small device helpers used by the kernels -------------------------------------------------

@@ -8,6 +8,8 @@
 // (arXiv 2209.05433, Section 2: FP8 operands, fp32 accumulation, scales taken out once per output).
 #include "gemm_common.hpp"
 
+#include <algorithm>
+
 namespace fp8mm {
 namespace {
 
@@ -119,7 +121,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 GemmPlan plan_gemm(const GemmArgs& g)
 {
     const int64_t M = g.M, N = g.N, K = g.K;
-    GemmPlan plan{!force_generic() && mfma_any_takes(g) ? GEMM_MFMA_ANY : GEMM_GENERIC, false, false};
+    GemmPlan plan{!force_generic() && mfma_any_takes(g) ? GEMM_MFMA_ANY : GEMM_GENERIC, false, false, 0};
     const uint64_t ldmax = (uint64_t)(M > N ? (M > K ? M : K) : (N > K ? N : K));
     const bool fits32 = 256 * ldmax < (1ull << 32) && M < (1ll << 31) - TILE_M && N < (1ll << 31) - TILE_N &&
                         K < (1ll << 31) &&
@@ -150,6 +152,52 @@ GemmPlan plan_gemm(const GemmArgs& g)
     const bool narrow = tn ? tn == 128 : 0.88 * fill(128) > fill(256);
     plan.kernel = narrow ? GEMM_TILED_128 : GEMM_TILED_256;
     plan.elementwise_stores = !c_lines;
+    // Both widths in one launch (gemm_mixed_kernel): the first c tile columns of 256, the rest of N in
+    // tiles of 128.  Chosen where a model of the run time says it beats the better single width by 3 %:
+    // workgroups are handed to the 256 compute units in order, the wide ones first; a tile takes
+    // a S + b microseconds, S = stages of 64 along K (fitted to one-round and three-round problems,
+    // 4096 x 4096 and 4096 x 6144 over K = 512 .. 8192: fp16 mode 1.30 S + 9.4 wide, 0.70 S + 5.8
+    // narrow; FP8 mode 0.65 S + 8.6 and 0.37 S + 4.7), and the change of width costs 3 + 32 / S
+    // microseconds (measured: the mixed launch is that much slower than its two parts).  With these
+    // figures it pays for long K (4096 x 6144 x 8192: 4 % in the fp16 mode, 7 % in the FP8 mode) and
+    // not for short K, where the narrow tile is nearly as efficient as the wide one.  Problems of
+    // more than 64 rounds are left alone (the last round is then under 2 %).
+    // Knob FP8_KNOB_MIXED: 0 = by the model, 1 = never, 2 = wherever it is possible.
+    const int mk = knob(FP8_KNOB_MIXED);
+    const int64_t tiles_m = (M + TILE_M - 1) / TILE_M, wide_cols_all = (N + TILE_N - 1) / TILE_N;
+    if (!tn && mk != 1 && g.splits <= 1 && N > TILE_N && tiles_m * wide_cols_all <= 64 * 256) {
+        const double S = 2.0 * (double)((K + 2 * TILE_K - 1) / (2 * TILE_K));
+        const double tw = g.acc == ACC_FP8 ? 0.65 * S + 8.6 : 1.30 * S + 9.4;
+        const double tnar = g.acc == ACC_FP8 ? 0.37 * S + 4.7 : 0.70 * S + 5.8;
+        const double change = 3.0 + 32.0 / S;
+        // time until the last of Tw wide and then Tn narrow tiles ends on 256 units
+        auto makespan = [&](int64_t Tw, int64_t Tn) {
+            const int64_t q = Tw / 256, k = Tw % 256;          // k units get q + 1 wide tiles, the others q
+            if (Tn == 0) return (double)(q + (k > 0)) * tw;
+            double best = 1e300;
+            for (int64_t r = 0; r <= Tn; ++r) {                // r narrow tiles on the units that are free first
+                const int64_t late = r * tnar >= tw ? (int64_t)((r * tnar - tw) / tnar) : 0;     // and as many as fit on the others
+                if ((256 - k) * r + k * late >= Tn) { best = (double)q * tw + (double)r * tnar; break; }
+            }
+            for (int64_t r = 1; r <= Tn; ++r) {                // or the last one ends on a unit that had q + 1 wide tiles
+                const int64_t early = (int64_t)((tw + r * tnar) / tnar);
+                if (k * r + (256 - k) * early >= Tn) { best = std::min(best, (double)(q + 1) * tw + (double)r * tnar); break; }
+                if ((double)(q + 1) * tw + (double)r * tnar >= best) break;
+            }
+            return best;
+        };
+        const double uniform = std::min(makespan(tiles_m * wide_cols_all, 0), makespan(0, tiles_m * ((N + 127) / 128)));
+        double best = 1e300;
+        int64_t best_c = 0;
+        for (int64_t c = 1; c * TILE_N < N; ++c) {
+            const double t = makespan(tiles_m * c, tiles_m * ((N - c * TILE_N + 127) / 128)) + change;
+            if (t < best) { best = t; best_c = c; }
+        }
+        if (best_c > 0 && (mk == 2 || best < 0.97 * uniform)) {
+            plan.kernel = GEMM_TILED_MIXED;
+            plan.wide_cols = (int)best_c;
+        }
+    }
     // The persistent form of the narrow tile (one workgroup per compute unit walks its tiles as one K
     // loop, see gemm_tiled.hip): for problems of more than one round of tiles without edge tiles, with
     // per-tensor factors and an fp32 / bf16 output.  It hides every tile's first loads and sends the
@@ -160,8 +208,8 @@ GemmPlan plan_gemm(const GemmArgs& g)
     // 1 - 2 % slower at K = 8192 throughout.  Knob FP8_KNOB_PERSIST: 0 = where it pays (below),
     // 1 = never, 2 = wherever it is possible.
     const int pk = knob(FP8_KNOB_PERSIST);
-    const int64_t tiles = ((M + TILE_M - 1) / TILE_M) * ((N + 127) / 128);
-    const bool possible = narrow && c_lines && M % TILE_M == 0 && N % 128 == 0 && K % (2 * TILE_K) == 0 && K >= 8 * TILE_K &&
+    const int64_t tiles = tiles_m * ((N + 127) / 128);
+    const bool possible = plan.kernel == GEMM_TILED_128 && c_lines && M % TILE_M == 0 && N % 128 == 0 && K % (2 * TILE_K) == 0 && K >= 8 * TILE_K &&
                           !g.ep.a_per_row && !g.ep.b_per_col && g.ep.out_kind <= OUT_BF16 && !g.ep.amax_out && g.splits <= 1;
     const bool pays = tiles > 256 && (g.ep.out_kind == OUT_F32 ? K <= 64 * TILE_K
                                                                : g.acc == ACC_F16 && K >= 16 * TILE_K && K <= 32 * TILE_K);
@@ -197,6 +245,7 @@ int launch_gemm(const GemmArgs& g)
         GemmArgs gt = g;
         gt.ep.ragged_n = plan.elementwise_stores ? 1 : 0;
         gt.tile_n = plan.kernel == GEMM_TILED_128 ? 128 : 256;
+        gt.wide_cols = plan.kernel == GEMM_TILED_MIXED ? plan.wide_cols : 0;
         gt.persist = plan.persistent;
         gt.splits = 1;
         return launch_tiled(gt);

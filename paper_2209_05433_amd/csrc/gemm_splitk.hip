@@ -74,7 +74,7 @@ SplitPlan plan_splitk(const GemmArgs& g, int requested)
     SplitPlan sp{1, 0, 256};
     GemmArgs probe = g;
     const int kernel = plan_gemm(probe).kernel;
-    if (kernel != GEMM_TILED_256 && kernel != GEMM_TILED_128) return sp;
+    if (kernel != GEMM_TILED_256 && kernel != GEMM_TILED_128 && kernel != GEMM_TILED_MIXED) return sp;
     const int forced_tile = knob(FP8_KNOB_TILE_N);
     sp.tile_n = forced_tile ? forced_tile : 256;             // the slices fill the chip: the wide tile is the faster one
     const int64_t tiles = ((g.M + TILE_M - 1) / TILE_M) * ((g.N + sp.tile_n - 1) / sp.tile_n);

@@ -349,7 +349,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
                 o = *LDS_PTR(u32x4, blk + row * ROWB + st_col);
             }
             if (!ep.ragged_n) {
-                *(u32x4*)out = o;
+                *(u32x4*)out = o;                        // (non-temporal stores measured the same, 8 shapes)
             } else {                                    // rows of C start anywhere: element by element
                 const int left = N - (wave_n0 + st_col / ESZ);          // columns from the lane's first one to the edge
 #pragma unroll
@@ -382,10 +382,14 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
 // them: the waits of the three steps after a tile end leave room for them.  Conditions (checked by
 // the dispatcher): no edge tiles, K a multiple of 128 and at least 512, per-tensor factors, fp32 or
 // bf16 output with rows on 16-byte boundaries, no output maximum, no K slices.
+//
+// The body works on tile number `bid_in` of a region of the output that starts at column n_begin and
+// is tiles_n tiles wide (the whole output for the plain kernel; see gemm_mixed_kernel).
 template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB, bool PERSIST>
-__global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
+__device__ __forceinline__ void gemm_tile_body(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
-    int M, int N, int K, EpilogueArgs ep, int group_m, int splits, int pairs_per_split)
+    int M, int N, int K, const EpilogueArgs& ep, int group_m, int splits, int pairs_per_split,
+    int bid_in, int n_begin, int tiles_n)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     constexpr int BN = 64 * NB;                             // tile width
@@ -406,11 +410,11 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     // with zeros.  With splits > 1 the workgroup computes one slice of K (pairs_per_split pairs,
     // the last slice what is left) of its tile and writes the fp32 sums, without the scales, into
     // slice `split` of C, which is then a workspace of `splits` M x N matrices.
-    int bid = blockIdx.x, split = 0;
+    int bid = bid_in, split = 0;
     if (!PERSIST && splits > 1) { split = bid % splits; bid /= splits; }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int tiles_m = (M + BM - 1) / BM;
     const TileMap tile = map_tile(bid, tiles_m, tiles_n, group_m);
-    int m0 = tile.tm * BM, n0 = tile.tn * BN;               // the tile whose products are being accumulated
+    int m0 = tile.tm * BM, n0 = n_begin + tile.tn * BN;     // the tile whose products are being accumulated
     const int pair0 = split * pairs_per_split;
     const int KT_TILE = 2 * min(pairs_per_split, (K + 2 * BK - 1) / (2 * BK) - pair0);     // stages of one tile
     // PERSIST: `units` tiles in a row; every stage and pair index below is then a global one
@@ -875,6 +879,34 @@ __global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
     }
 }
 
+template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC, int NB, bool PERSIST>
+__global__ __launch_bounds__(FAST_THREADS, 1) void gemm_fast_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int M, int N, int K, EpilogueArgs ep, int group_m, int splits, int pairs_per_split)
+{
+    gemm_tile_body<FMT_A, FMT_B, ACC, A_KC, B_KC, NB, PERSIST>(A, B, C, M, N, K, ep, group_m, splits, pairs_per_split,
+                                                              (int)blockIdx.x, 0, (N + 64 * NB - 1) / (64 * NB));
+}
+
+// Both tile widths in one launch: the first wide_cols * 256 columns of the output in 256 x 256 tiles
+// (workgroups 0 .. tiles_m * wide_cols - 1, dispatched first), the remaining columns in 256 x 128
+// tiles.  For problems whose tiles of one width leave much of the last round of workgroups empty
+// (4096 x 6144: 384 wide tiles = 1.5 rounds, 768 narrow ones = 3 rounds at 0.6 of the wide tile's
+// time each; 256 wide + 256 narrow = one round of each); the narrow tiles also fill the compute
+// units that the last wide tiles leave idle.  The choice of wide_cols is the dispatcher's.
+template <int FMT_A, int FMT_B, int ACC, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(FAST_THREADS, 1) void gemm_mixed_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int M, int N, int K, EpilogueArgs ep, int group_m, int pairs, int wide_cols)
+{
+    const int wide_tiles = ((M + BM - 1) / BM) * wide_cols;
+    if ((int)blockIdx.x < wide_tiles)
+        gemm_tile_body<FMT_A, FMT_B, ACC, A_KC, B_KC, 4, false>(A, B, C, M, N, K, ep, group_m, 1, pairs, (int)blockIdx.x, 0, wide_cols);
+    else
+        gemm_tile_body<FMT_A, FMT_B, ACC, A_KC, B_KC, 2, false>(A, B, C, M, N, K, ep, group_m, 1, pairs, (int)blockIdx.x - wide_tiles,
+                                                                wide_cols * 256, (N - wide_cols * 256 + 127) / 128);
+}
+
 // ---- launch ------------------------------------------------------------------------------
 // The knob FP8_KNOB_GROUP_M sets the number of tile rows per band of the tile order (0: GROUP_M).
 int group_m_setting()
@@ -921,6 +953,28 @@ int launch_fast(const GemmArgs& g)
     return check_launch(PERSIST ? "gemm (tiled kernel, persistent form)" : "gemm (tiled kernel)");
 }
 
+template <int FA, int FB, int ACC, bool A_KC, bool B_KC>
+int launch_mixed(const GemmArgs& g)
+{
+    static std::atomic<unsigned long long> attr_set{0ull};
+    auto kern = gemm_mixed_kernel<FA, FB, ACC, A_KC, B_KC>;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FP8_ERR_DEVICE, "hipGetDevice failed");
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev >= 64 || !(attr_set.load(std::memory_order_relaxed) & bit)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FAST_LDS);
+        if (e != hipSuccess)
+            return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", FAST_LDS, hipGetErrorString(e));
+        if (dev < 64) attr_set.fetch_or(bit, std::memory_order_relaxed);
+    }
+    const int64_t tiles_m = (g.M + BM - 1) / BM;
+    const int64_t grid = tiles_m * g.wide_cols + tiles_m * ((g.N - (int64_t)g.wide_cols * 256 + 127) / 128);
+    const int pairs = (int)((g.K + 2 * BK - 1) / (2 * BK));
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FAST_THREADS), FAST_LDS, g.stream, g.A, g.B, g.C,
+                       (int)g.M, (int)g.N, (int)g.K, g.ep, group_m_setting(), pairs, g.wide_cols);
+    return check_launch("gemm (tiled kernel, both tile widths)");
+}
+
 }  // namespace
 
 #if !defined(FP8MM_LAYOUT) || !defined(FP8MM_ACC)
@@ -947,8 +1001,18 @@ static int launch_formats(const GemmArgs& g)
                               : launch_fast<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC, NB>(g);
 }
 
+static int launch_mixed_formats(const GemmArgs& g)
+{
+    constexpr bool A_KC = (FP8MM_LAYOUT & 2) == 0, B_KC = (FP8MM_LAYOUT & 1) != 0;
+    constexpr int ACC = FP8MM_ACC;
+    if (g.fmtA == FP8_E4M3)
+        return g.fmtB == FP8_E4M3 ? launch_mixed<FP8_E4M3, FP8_E4M3, ACC, A_KC, B_KC>(g) : launch_mixed<FP8_E4M3, FP8_E5M2, ACC, A_KC, B_KC>(g);
+    return g.fmtB == FP8_E4M3 ? launch_mixed<FP8_E5M2, FP8_E4M3, ACC, A_KC, B_KC>(g) : launch_mixed<FP8_E5M2, FP8_E5M2, ACC, A_KC, B_KC>(g);
+}
+
 int FP8MM_TILED_NAME(FP8MM_LAYOUT, FP8MM_ACC)(const GemmArgs& g)
 {
+    if (g.wide_cols > 0) return launch_mixed_formats(g);
     return g.tile_n == 128 ? launch_formats<2>(g) : launch_formats<4>(g);
 }
 

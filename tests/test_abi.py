@@ -79,6 +79,7 @@ def test_gemm_plan_names_the_kernel_for_the_workload_shapes():
                                                                             # 768 narrow ones = 3 per compute unit, walked as one K loop
     assert not plan(0, 0, 4096, 6144 + 16, 2048) & fp8.FP8_PLAN_PERSISTENT   # an edge tile: one workgroup per tile
     assert plan(0, 0, 4096, 6144, 2048 + 64) == T128             # K not in whole stage pairs
+    assert plan(0, 0, 4096, 6144, 8192) == fp8.FP8_PLAN_TILED_MIXED   # long K: 256 wide tiles, then 256 narrow ones, one launch
     assert plan(0, 0, 256, 256, 256) in (T256, T128)             # config 1
     for ta in (0, 1):
         for tb in (0, 1):
@@ -112,6 +113,11 @@ def test_knobs_round_trip_and_reject_bad_values():
     assert fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 2) == 1
     assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_MFMA_ANY
     fp8.fp8_set_knob(fp8.FP8_KNOB_GEMM_KERNEL, 0)
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_MIXED, 1) == 0
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 4096, 6144, 2048, None) == fp8.FP8_PLAN_TILED_256x128 | fp8.FP8_PLAN_PERSISTENT
+    assert fp8.fp8_set_knob(fp8.FP8_KNOB_MIXED, 2) == 1
+    assert L.fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, None) == fp8.FP8_PLAN_TILED_MIXED
+    fp8.fp8_set_knob(fp8.FP8_KNOB_MIXED, 0)
     assert L.fp8_gemm_plan(A, 0, B, 0, C, (1 << 31) * 128, 128 * 3, 77, None) == fp8.FP8_PLAN_FMA_KERNEL   # more 128 x 128 tiles than a grid holds
     for knob, bad in ((fp8.FP8_KNOB_TILE_N, 64), (fp8.FP8_KNOB_CAST_PATH, 2), (fp8.FP8_KNOB_SPLIT_K, 65), (fp8.FP8_KNOB_GEMM_KERNEL, 3), (99, 0)):
         with pytest.raises(fp8.Fp8Error):

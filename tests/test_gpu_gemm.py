@@ -27,6 +27,7 @@ MODES = ["f16", "mfma8"]
 GEMM = {("f16", False): fp8.fp8_gemm, ("f16", True): fp8.fp8_gemm_dscale,
         ("mfma8", False): fp8.fp8_gemm_mfma8, ("mfma8", True): fp8.fp8_gemm_mfma8_dscale}
 REL = {"f16": 2.0 ** -20, "mfma8": 2.0 ** -10}
+TILED = (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_TILED_MIXED)
 
 
 def run_gemm(Aq, fmtA, sA, Bq, fmtB, sB, out_dtype, dscale=False, fill=None, mode="f16"):
@@ -248,7 +249,7 @@ def run_config(A_bits, B_bits, fmtA, fmtB, out_dtype, npts, nrows, label, full=F
         fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
     fp8.fp8_gemm_dscale(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C)
     torch.cuda.synchronize()
-    assert fp8.fp8_gemm_plan(qA, 0, qB, 0, C) & ~fp8.FP8_PLAN_PERSISTENT in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), label
+    assert fp8.fp8_gemm_plan(qA, 0, qB, 0, C) & ~fp8.FP8_PLAN_PERSISTENT in TILED, label
     del dA, dB
     Aq, sA, Bq, sB = quantize_pair(A_bits, B_bits, fmtA, fmtB)
     assert np.float32(scale[0].item()) == sA and np.float32(scale[1].item()) == sB, label
@@ -458,7 +459,7 @@ def test_every_stage_count_through_the_loop_regions(transA, transB, mode, tile_n
         dA = guarded(np.ascontiguousarray(Aq.T) if transA else Aq)
         dB = guarded(np.ascontiguousarray(Bq.T) if transB else Bq)
         C = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
-        assert fp8.fp8_gemm_plan(dA, transA, dB, transB, C) in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), K
+        assert fp8.fp8_gemm_plan(dA, transA, dB, transB, C) in TILED, K
         fp8.fp8_gemm_ex(dA, E4M3, transA, dB, E4M3, transB, C, 1.0, 1.0, fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0)
         torch.cuda.synchronize()
         got = out_to_f64(C)
@@ -497,6 +498,64 @@ def test_repeated_launches_give_identical_bits_while_memory_is_busy(transA, tran
         fp8.fp8_gemm_ex(dA, E5M2, transA, dB, E4M3, transB, C, 1.0, 1.0, flags)
         torch.cuda.synchronize()
         assert torch.equal(C, C0), "launch %d differs from the first in %d outputs" % (rep, int((C != C0).sum()))
+
+
+# ---- both tile widths in one launch --------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_mixed_tile_widths_exact_integers(transA, transB, mode):
+    """256-wide tiles for the first columns and 128-wide ones for the rest, one launch (forced by the
+    knob, and chosen by the dispatcher's model where it predicts a gain).  Shapes with a single wide
+    column and many, with edge tiles in M and in N, with N that is no multiple of 16 (element-wise
+    stores) and a K tail; integer operands, so the result must equal the oracle's exactly; nothing
+    may be written outside C."""
+    rng = np.random.default_rng(500 + 2 * transA + transB)
+    shapes = [(512, 384, 256), (304, 1300 if transB else 1296, 448), (1024, 2048 + 128, 128), (256, 520 if transB else 528, 64), (720, 1000 if transB else 1008, 192)]
+    for (M, N, K) in shapes:
+        ai = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        bi = rng.integers(-4, 5, (K, N)).astype(np.float32)
+        Aq, Bq = oracle.quantize(ai, E4M3, 1.0), oracle.quantize(bi, E5M2, 1.0)
+        want = (ai.astype(np.float64) @ bi.astype(np.float64)) * 4.0
+        dA = to_dev(np.ascontiguousarray(Aq.T) if transA else Aq)
+        dB = to_dev(np.ascontiguousarray(Bq.T) if transB else Bq)
+        for out_dtype in (fp8.FP8_F32, fp8.FP8_BF16):
+            guard = 64
+            flat = torch.full((M * N + 2 * guard,), 9.0, dtype=OUT[out_dtype], device="cuda")
+            C = flat[guard:guard + M * N].view(M, N)
+            with knob(fp8.FP8_KNOB_MIXED, 2):
+                assert fp8.fp8_gemm_plan(dA, transA, dB, transB, C) & 15 == fp8.FP8_PLAN_TILED_MIXED, (M, N, K)
+                fp8.fp8_gemm_ex(dA, E4M3, transA, dB, E5M2, transB, C, 0.5, 0.5, fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0)
+            torch.cuda.synchronize()
+            ref = want if out_dtype == fp8.FP8_F32 else torch.from_numpy(want).to(torch.bfloat16).double().numpy()
+            assert np.array_equal(out_to_f64(C), ref), "%s layout %d%d %s: %d outputs differ" % (
+                (M, N, K), transA, transB, mode, np.count_nonzero(out_to_f64(C) != ref))
+            assert torch.all(flat[:guard] == 9.0) and torch.all(flat[guard + M * N:] == 9.0), "wrote outside C"
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_mixed_tile_widths_chosen_by_the_dispatcher_and_within_the_bound(mode):
+    """The dispatcher picks the mixed launch by itself for 4096 x 6144 with a long K (384 wide tiles =
+    1.5 rounds of the chip); random codes against the oracle on sampled rows, and the same bits as
+    the single-width launches give (every output accumulates its K in the same order whatever the tile)."""
+    rng = np.random.default_rng(77)
+    M, N, K = 4096, 6144, 8192
+    A, B = random_codes(rng, (M, K), E4M3), random_codes(rng, (K, N), E4M3)
+    rows = np.sort(rng.choice(M, 24, replace=False))
+    S, T = oracle.gemm_rows(A, E4M3, B, E4M3, rows)
+    dA, dB = to_dev(A), to_dev(B)
+    flags = fp8.FP8_GEMM_MFMA8 if mode == "mfma8" else 0
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    assert fp8.fp8_gemm_plan(dA, 0, dB, 0, C) == fp8.FP8_PLAN_TILED_MIXED
+    fp8.fp8_gemm_ex(dA, E4M3, 0, dB, E4M3, 0, C, 2.0, 3.0, flags)
+    torch.cuda.synchronize()
+    check(out_to_f64(C[torch.from_numpy(rows).cuda()]), S, T, 2.0, 3.0, fp8.FP8_F32, "mixed widths", mode=mode)
+    for tile in (128, 256):
+        C1 = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        with knob(fp8.FP8_KNOB_TILE_N, tile), knob(fp8.FP8_KNOB_PERSIST, 1):
+            fp8.fp8_gemm_ex(dA, E4M3, 0, dB, E4M3, 0, C1, 2.0, 3.0, flags)
+        torch.cuda.synchronize()
+        assert torch.equal(C, C1), "mixed and %d-wide launches differ" % tile
 
 
 # ---- the persistent form of the narrow tile ---------------------------------------------------------

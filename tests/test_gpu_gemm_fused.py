@@ -389,7 +389,7 @@ def test_any_n_with_b_stored_n_by_k_and_unaligned_outputs(mode, tile_n):
             what = "any N %s transA %d offset %d out %d %s" % ((M, N, K), transA, off, out_kind, mode)
             plan = fp8.fp8_gemm_plan(dA, transA, dB, 1, D, sBbuf[off:off + N])
             if N % 16 or off:                                   # the matrix-core kernel with element-wise stores
-                assert plan & fp8.FP8_PLAN_ELEMENTWISE_STORES and plan & 3 in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128), what
+                assert plan & fp8.FP8_PLAN_ELEMENTWISE_STORES and plan & 15 in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_TILED_MIXED), what
             assert bool((buf[:pad + off] == 7).all()) and bool((buf[pad + off + M * N:] == 7).all()), what + ": wrote outside D"
             if out_kind == fp8.FP8_OUT_E4M3:
                 check_fp8_bytes(D.cpu().numpy(), c_ref, b, np.float32(sD.item()), E4M3, what,
