@@ -144,7 +144,7 @@ int main(void)
             const int ta = (int)(s >> 63), tb = (int)((s >> 62) & 1), off = (int)((s >> 40) & 15) * (int)((s >> 61) & 1);
             const int plan = fp8_gemm_plan(A + off, ta, B, tb, C, dim[0], dim[1], dim[2], (s >> 33) & 1 ? F : NULL);
             const int kernel = plan & 15;
-            if (plan < 0 || kernel < FP8_PLAN_FMA_KERNEL || kernel > FP8_PLAN_MFMA_ANY ||
+            if (plan < 0 || kernel < FP8_PLAN_FMA_KERNEL || kernel > FP8_PLAN_TILED_MIXED ||
                 (plan & ~(15 | FP8_PLAN_ELEMENTWISE_STORES | FP8_PLAN_PERSISTENT))) {
                 printf("plan(%lld, %lld, %lld, %d, %d, +%d) = %d\n", (long long)dim[0], (long long)dim[1], (long long)dim[2], ta, tb, off, plan);
                 ++failures;
@@ -167,6 +167,10 @@ int main(void)
     EXPECT(fp8_set_knob(FP8_KNOB_COUNT, 0), -BAD);
     EXPECT(fp8_get_knob(FP8_KNOB_COUNT), -BAD);
     EXPECT(fp8_set_knob(FP8_KNOB_PERSIST, 3), -BAD);
+    EXPECT(fp8_set_knob(FP8_KNOB_MIXED, 2), 0);
+    EXPECT(fp8_gemm_plan(A, 0, B, 0, C, 8192, 49152, 12288, NULL), FP8_PLAN_TILED_MIXED);
+    EXPECT(fp8_set_knob(FP8_KNOB_MIXED, 0), 2);
+    EXPECT(fp8_gemm_plan(A, 0, B, 0, C, 4096, 6144, 8192, NULL), FP8_PLAN_TILED_MIXED);
 
     if (failures) { printf("%d failure(s)\n", failures); return 1; }
     printf("ok\n");
