@@ -111,7 +111,7 @@ def run_workload(name, args, fp8, synth, torch, np, probes, steps, warmup, extra
 
     amax = torch.zeros(2, device="cuda")
     scale = torch.zeros(2, device="cuda")
-    ws = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
     qA = torch.empty((M, K), dtype=torch.uint8, device="cuda")
     qB = torch.empty((K, N), dtype=torch.uint8, device="cuda")
     C = torch.empty((M, N), dtype=out_dtype, device="cuda")
@@ -120,9 +120,10 @@ def run_workload(name, args, fp8, synth, torch, np, probes, steps, warmup, extra
     def step(gemm=fp8.fp8_gemm_dscale, record=None):
         if record is not None:
             record[0].record(stream)
-        for t, q, i, f in ((dA, qA, 0, fmtA), (dB, qB, 1, fmtB)):
-            fp8.fp8_amax_scale(t, f, amax[i:i + 1], scale[i:i + 1], ws)
-            fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
+        # amax + scale of both operands in one launch, then both casts (one launch where the outputs are
+        # small enough for ordinary stores, else one per tensor inside the call)
+        fp8.fp8_amax_scale_multi((dA, dB), (fmtA, fmtB), amax, scale, ws)
+        fp8.fp8_quantize_multi((dA, dB), (fmtA, fmtB), scale, (qA, qB))
         if record is not None:
             record[1].record(stream)
         gemm(qA, fmtA, scale[0:1], qB, fmtB, scale[1:2], C)
@@ -190,7 +191,7 @@ def run_workload(name, args, fp8, synth, torch, np, probes, steps, warmup, extra
             "flops_per_launch": flops, "avg_launch_ms": round(gemm_ms, 4), "traffic": traffic,
         },
         "roofline_cast": {
-            "kernels": "amax_vec_kernel (with the scale, one launch) + quantize_vec_kernel over A and B",
+            "kernels": "amax_multi_kernel (A and B, with the scales, one launch) + quantize_multi_kernel (one launch) or quantize_vec_kernel per tensor (outputs of 384 MiB and more)",
             "bound": "hbm", "achieved": round(cast_bytes / cast_ms * 1e-6, 1), "peak": PEAK_HBM_GBS,
             "unit": "GB/s", "frac": round(cast_bytes / cast_ms * 1e-6 / PEAK_HBM_GBS, 4),
             "bytes_per_step": cast_bytes,
@@ -200,12 +201,11 @@ def run_workload(name, args, fp8, synth, torch, np, probes, steps, warmup, extra
 
     if extras:
         # The same launches recorded once into a HIP graph and replayed: what the step costs when the
-        # host does not have to issue five launches per step (on the small workload the eager step is
+        # host does not have to issue three to four launches per step (on the small workload the eager step is
         # bound by that, not by the GPU).  Three graphs: the whole step, the amax + cast chain, the GEMM.
         def cast_chain():
-            for t, q, i, f in ((dA, qA, 0, fmtA), (dB, qB, 1, fmtB)):
-                fp8.fp8_amax_scale(t, f, amax[i:i + 1], scale[i:i + 1], ws)
-                fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q)
+            fp8.fp8_amax_scale_multi((dA, dB), (fmtA, fmtB), amax, scale, ws)
+            fp8.fp8_quantize_multi((dA, dB), (fmtA, fmtB), scale, (qA, qB))
         def replay_ms(fn, n):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):

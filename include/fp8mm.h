@@ -87,6 +87,28 @@ int fp8_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_o
                    void* workspace, void* stream);
 
 /*
+ * fp8_amax_scale_multi, fp8_quantize_multi -- the two steps above for up to FP8_MULTI_MAX tensors of
+ * one element type in ONE launch each (both operands of a GEMM, say: Section 2's per-tensor
+ * amax -> factor -> cast applies to each of them).  For small tensors a launch costs as much as the
+ * kernel's work; results are those of the single-tensor calls, bit for bit.
+ *   count      number of tensors, 0 .. FP8_MULTI_MAX
+ *   x, n, fmt  HOST arrays of count entries: device pointer, element count and FP8 format of each
+ *              tensor (read during the call; alignment of x[i] as for fp8_amax)
+ *   amax_out, scale_out  DEVICE arrays of count floats (scale_out may be NULL for fp8_amax_scale_multi)
+ *   workspace  device, count * FP8_AMAX_WORKSPACE_BYTES bytes, rules as for fp8_amax_scale
+ *   scale_dev  device array of count factors (fp8_quantize_multi: as fp8_quantize_dscale per tensor)
+ *   q_out      HOST array of count device pointers to the output bytes
+ * Tensors that do not meet the conditions of the vector kernels (empty, not 16-byte aligned,
+ * outputs of 384 MiB and more) are served by single-tensor launches inside the call.
+ * Errors: FP8_ERR_INVALID_ARG for a bad count, NULL arrays, bad enums or misaligned pointers.
+ */
+#define FP8_MULTI_MAX 4
+int fp8_amax_scale_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                         float* amax_out, float* scale_out, void* workspace, void* stream);
+int fp8_quantize_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                       const float* scale_dev, uint8_t* const* q_out, void* stream);
+
+/*
  * fp8_scale_from_amax_host / fp8_scale_from_amax -- scale = fmt_max / amax in IEEE
  * single precision, fmt_max = 448 (E4M3) or 57344 (E5M2) (Section 2: the maximum
  * magnitude is moved close to the largest representable one; Table 1, Max normal;

@@ -18,13 +18,14 @@ FP8_GEMM_MFMA8 = 1
 FP8_OUT_F32, FP8_OUT_BF16, FP8_OUT_E4M3, FP8_OUT_E5M2 = 0, 1, 2, 3
 FP8_PLAN_NO_GEMM, FP8_PLAN_FMA_KERNEL, FP8_PLAN_TILED_256x256, FP8_PLAN_TILED_256x128, FP8_PLAN_MFMA_ANY, FP8_PLAN_TILED_MIXED = 0, 1, 2, 3, 4, 5
 FP8_PLAN_ELEMENTWISE_STORES = 16
+FP8_MULTI_MAX = 4
 FP8_PLAN_PERSISTENT = 32
 FP8_KNOB_CAST_PATH, FP8_KNOB_TILE_N, FP8_KNOB_GROUP_M, FP8_KNOB_GEMM_KERNEL, FP8_KNOB_SPLIT_K, FP8_KNOB_CAST_RUN, FP8_KNOB_PERSIST, FP8_KNOB_MIXED = 0, 1, 2, 3, 4, 5, 6, 7
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfp8mm.so")
 
 EXPORTS = (
-    "fp8_amax", "fp8_amax_scale", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
+    "fp8_amax", "fp8_amax_scale", "fp8_amax_scale_multi", "fp8_quantize_multi", "fp8_scale_from_amax_host", "fp8_scale_from_amax", "fp8_quantize",
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
@@ -55,6 +56,8 @@ def lib() -> ctypes.CDLL:
     vp, sz, i, i64, f = c.c_void_p, c.c_size_t, c.c_int, c.c_int64, c.c_float
     L.fp8_amax.argtypes, L.fp8_amax.restype = [vp, sz, i, vp, vp], i
     L.fp8_amax_scale.argtypes, L.fp8_amax_scale.restype = [vp, sz, i, i, vp, vp, vp, vp], i
+    L.fp8_amax_scale_multi.argtypes, L.fp8_amax_scale_multi.restype = [i, vp, vp, i, vp, vp, vp, vp, vp], i
+    L.fp8_quantize_multi.argtypes, L.fp8_quantize_multi.restype = [i, vp, vp, i, vp, vp, vp, vp], i
     L.fp8_scale_from_amax_host.argtypes, L.fp8_scale_from_amax_host.restype = [f, i], f
     L.fp8_scale_from_amax.argtypes, L.fp8_scale_from_amax.restype = [vp, i, vp, vp], i
     L.fp8_quantize.argtypes, L.fp8_quantize.restype = [vp, sz, i, i, f, vp, vp], i
@@ -161,6 +164,41 @@ def fp8_amax_scale(x: torch.Tensor, fmt: int, amax_out: torch.Tensor, scale_out,
     _check(lib().fp8_amax_scale(_dev(x, "x") if x.numel() else None, x.numel(), dtype_code(x), fmt,
                                 _dev(amax_out, "amax_out"), _dev(scale_out, "scale_out") if scale_out is not None else None,
                                 _dev(workspace, "workspace"), _stream(stream)))
+
+
+def _host_arrays(tensors, fmts, what):
+    """The host-side argument arrays of the multi-tensor entry points: device pointers, element counts, formats."""
+    count = len(tensors)
+    if count > FP8_MULTI_MAX or len(fmts) != count:
+        raise ValueError("%s: at most %d tensors, one format each" % (what, FP8_MULTI_MAX))
+    codes = {dtype_code(t) for t in tensors}
+    if len(codes) > 1:
+        raise TypeError("%s: all tensors must have one element type" % what)
+    ptrs = (ctypes.c_void_p * count)(*[(_dev(t, "x") if t.numel() else None) for t in tensors])
+    ns = (ctypes.c_size_t * count)(*[t.numel() for t in tensors])
+    fm = (ctypes.c_int * count)(*[int(f) for f in fmts])
+    return count, ptrs, ns, (codes.pop() if codes else FP8_BF16), fm
+
+
+def fp8_amax_scale_multi(xs, fmts, amax_out: torch.Tensor, scale_out, workspace: torch.Tensor, stream=None) -> None:
+    """fp8_amax_scale for up to FP8_MULTI_MAX tensors of one element type in one launch: amax_out and
+    scale_out are fp32 device tensors of len(xs) values, workspace holds len(xs) * FP8_AMAX_WORKSPACE_BYTES bytes."""
+    count, ptrs, ns, code, fm = _host_arrays(xs, fmts, "fp8_amax_scale_multi")
+    if workspace.numel() * workspace.element_size() < count * FP8_AMAX_WORKSPACE_BYTES:
+        raise ValueError("workspace must hold FP8_AMAX_WORKSPACE_BYTES bytes per tensor")
+    _check(lib().fp8_amax_scale_multi(count, ptrs, ns, code, fm, _f32_cells(amax_out, "amax_out", count),
+                                      _f32_cells(scale_out, "scale_out", count) if scale_out is not None else None,
+                                      _dev(workspace, "workspace"), _stream(stream)))
+
+
+def fp8_quantize_multi(xs, fmts, scale: torch.Tensor, q_outs, stream=None) -> None:
+    """fp8_quantize_dscale for up to FP8_MULTI_MAX tensors of one element type in one launch; scale is an
+    fp32 device tensor of len(xs) factors, q_outs the uint8 outputs."""
+    count, ptrs, ns, code, fm = _host_arrays(xs, fmts, "fp8_quantize_multi")
+    if len(q_outs) != count or any(q.dtype != torch.uint8 or q.numel() != x.numel() for q, x in zip(q_outs, xs)):
+        raise ValueError("q_outs must be uint8 tensors with as many elements as their inputs")
+    qs = (ctypes.c_void_p * count)(*[(_dev(q, "q_out") if q.numel() else None) for q in q_outs])
+    _check(lib().fp8_quantize_multi(count, ptrs, ns, code, fm, _f32_cells(scale, "scale", count), qs, _stream(stream)))
 
 
 def fp8_scale_from_amax_host(amax: float, fmt: int) -> float:

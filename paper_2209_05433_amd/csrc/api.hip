@@ -151,6 +151,44 @@ int fp8_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_o
     return launch_amax_scale(x, n, in_dtype, fmt, amax_out, scale_out, workspace, (hipStream_t)stream);
 }
 
+int fp8_amax_scale_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                         float* amax_out, float* scale_out, void* workspace, void* stream)
+{
+    const char* who = "fp8_amax_scale_multi";
+    clear_error();
+    if (count < 0 || count > FP8_MULTI_MAX) return fail(FP8_ERR_INVALID_ARG, "%s: count %d is not in 0..%d", who, count, FP8_MULTI_MAX);
+    if (count == 0) return FP8_OK;
+    if (!x || !n || !fmt) return fail(FP8_ERR_INVALID_ARG, "%s: x, n or fmt is NULL", who);
+    if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
+    if (!amax_out || !workspace) return fail(FP8_ERR_INVALID_ARG, "%s: amax_out or workspace is NULL", who);
+    if (((uintptr_t)amax_out | (uintptr_t)scale_out | (uintptr_t)workspace) % 4)
+        return fail(FP8_ERR_INVALID_ARG, "%s: amax_out, scale_out and workspace must be 4-byte aligned", who);
+    for (int i = 0; i < count; ++i) {
+        if (!valid_format(fmt[i])) return fail(FP8_ERR_INVALID_ARG, "%s: fmt[%d] = %d is not an fp8_format_t", who, i, fmt[i]);
+        if (n[i] > 0 && !x[i]) return fail(FP8_ERR_INVALID_ARG, "%s: x[%d] is NULL with n = %zu", who, i, n[i]);
+        if ((uintptr_t)x[i] % (in_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "%s: x[%d] is not aligned to its element size", who, i);
+    }
+    return launch_amax_scale_multi(count, x, n, in_dtype, fmt, amax_out, scale_out, workspace, (hipStream_t)stream);
+}
+
+int fp8_quantize_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                       const float* scale_dev, uint8_t* const* q_out, void* stream)
+{
+    const char* who = "fp8_quantize_multi";
+    clear_error();
+    if (count < 0 || count > FP8_MULTI_MAX) return fail(FP8_ERR_INVALID_ARG, "%s: count %d is not in 0..%d", who, count, FP8_MULTI_MAX);
+    if (count == 0) return FP8_OK;
+    if (!x || !n || !fmt || !q_out) return fail(FP8_ERR_INVALID_ARG, "%s: x, n, fmt or q_out is NULL", who);
+    if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
+    if (!scale_dev || (uintptr_t)scale_dev % 4) return fail(FP8_ERR_INVALID_ARG, "%s: scale_dev is NULL or misaligned", who);
+    for (int i = 0; i < count; ++i) {
+        if (!valid_format(fmt[i])) return fail(FP8_ERR_INVALID_ARG, "%s: fmt[%d] = %d is not an fp8_format_t", who, i, fmt[i]);
+        if (n[i] > 0 && (!x[i] || !q_out[i])) return fail(FP8_ERR_INVALID_ARG, "%s: NULL tensor pointer %d with n = %zu", who, i, n[i]);
+        if ((uintptr_t)x[i] % (in_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "%s: x[%d] is not aligned to its element size", who, i);
+    }
+    return launch_quantize_multi(count, x, n, in_dtype, fmt, scale_dev, q_out, (hipStream_t)stream);
+}
+
 float fp8_scale_from_amax_host(float amax, int fmt)
 {
     clear_error();

@@ -14,6 +14,7 @@ constexpr int kAmaxBlocks = 256 * 4;      // read-only stream: 32 KB chunks deal
 // size (6.04 10^8 bf16 elements: 290 us, against 320 us when the grid stopped growing at 16 384
 // workgroups); the limit only keeps the grid dimension in range
 constexpr int kCastBlocks = 1 << 20;
+constexpr int kMultiMax = FP8_MULTI_MAX;  // tensors per launch of the multi-tensor forms
 constexpr size_t kStreamingStoreBytes = (size_t)384 << 20;   // outputs from this size on are stored non-temporally
 
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));

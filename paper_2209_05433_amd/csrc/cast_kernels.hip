@@ -41,17 +41,19 @@ __device__ __forceinline__ unsigned draw_ticket(unsigned* counter)
     return __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// bid, grid: the workgroup's number and the number of workgroups that work on this tensor.
 __device__ __forceinline__ void amax_finish_ticket(unsigned r, unsigned* __restrict__ ws, int fmt,
-                                                   float* __restrict__ amax_out, float* __restrict__ scale_out)
+                                                   float* __restrict__ amax_out, float* __restrict__ scale_out,
+                                                   unsigned bid, unsigned grid)
 {
     __shared__ bool last;
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&ws[kTicketPartials + blockIdx.x], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws[kTicketPartials + bid], r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);            // (the compiler keeps the three steps in this order)
         __builtin_amdgcn_s_waitcnt(0x0070);                 // vmcnt(0) (and lgkmcnt(0)): the store has been acknowledged
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        const unsigned g = blockIdx.x / kTicketGroup, groups = (gridDim.x + kTicketGroup - 1) / kTicketGroup;
-        const unsigned members = min(kTicketGroup, gridDim.x - g * kTicketGroup);
+        const unsigned g = bid / kTicketGroup, groups = (grid + kTicketGroup - 1) / kTicketGroup;
+        const unsigned members = min(kTicketGroup, grid - g * kTicketGroup);
         bool l = false;
         if (draw_ticket(&ws[32 * (1 + g)]) == members - 1) {
             __hip_atomic_store(&ws[32 * (1 + g)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -62,7 +64,7 @@ __device__ __forceinline__ void amax_finish_ticket(unsigned r, unsigned* __restr
     __syncthreads();
     if (!last) return;
     unsigned m = 0;
-    for (unsigned i = threadIdx.x; i < gridDim.x; i += kThreads) {
+    for (unsigned i = threadIdx.x; i < grid; i += kThreads) {
         const unsigned p = __hip_atomic_load(&ws[kTicketPartials + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         m = m > p ? m : p;
     }
@@ -75,17 +77,18 @@ __device__ __forceinline__ void amax_finish_ticket(unsigned r, unsigned* __restr
     }
 }
 
+// The work of workgroup `bid` of `grid` on one tensor.
 template <int DT, bool TICKET>
-__global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restrict__ x, size_t n,
-                                                           unsigned* __restrict__ out_bits, unsigned* __restrict__ ws,
-                                                           int fmt, float* __restrict__ scale_out)
+__device__ __forceinline__ void amax_vec_body(const void* __restrict__ x, size_t n, unsigned* __restrict__ out_bits,
+                                              unsigned* __restrict__ ws, int fmt, float* __restrict__ scale_out,
+                                              unsigned bid, unsigned grid)
 {
     constexpr int PV = Elem<DT>::per_vec;
     const u32x4* xv = (const u32x4*)x;
     const size_t nvec = n / PV;
     const size_t nchunk = nvec / kAmaxChunkVecs;
     unsigned run[4] = {0u, 0u, 0u, 0u};
-    for (size_t c = blockIdx.x; c < nchunk; c += gridDim.x) {
+    for (size_t c = bid; c < nchunk; c += grid) {
         const u32x4* p = xv + c * kAmaxChunkVecs + threadIdx.x;
         u32x4 v[8];
 #pragma unroll
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
         for (int j = 0; j < 8; ++j) run[j & 3] = vec_mag_max<DT>(v[j], run[j & 3]);
     }
     // vectors after the last whole chunk, then the tail elements: workgroup 0
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
         for (size_t i = nchunk * kAmaxChunkVecs + threadIdx.x; i < nvec; i += kThreads)
             run[0] = vec_mag_max<DT>(__builtin_nontemporal_load(&xv[i]), run[0]);
     }
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
         unsigned short m = p.x > p.y ? p.x : p.y;
         r = (unsigned)m << 16;
     }
-    if (blockIdx.x == 0) {
+    if (bid == 0) {
         size_t t = nvec * PV + threadIdx.x;
         if (t < n) {
             unsigned m = scalar_mag<DT>(x, t);
@@ -119,11 +122,49 @@ __global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restri
     r = block_max_u32(r);
     if (TICKET) {
         __syncthreads();                                    // block_max_u32's LDS cells are used again below
-        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out);
+        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out, bid, grid);
         return;
     }
     // most workgroups find the cell already large enough and skip the atomic
     if (threadIdx.x == 0 && r > __hip_atomic_load(out_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(out_bits, r);
+}
+
+template <int DT, bool TICKET>
+__global__ __launch_bounds__(kThreads) void amax_vec_kernel(const void* __restrict__ x, size_t n,
+                                                           unsigned* __restrict__ out_bits, unsigned* __restrict__ ws,
+                                                           int fmt, float* __restrict__ scale_out)
+{
+    amax_vec_body<DT, TICKET>(x, n, out_bits, ws, fmt, scale_out, blockIdx.x, gridDim.x);
+}
+
+// Up to kMultiMax tensors in one launch (fp8_amax_scale_multi): the grid is the concatenation of the
+// grids the single-tensor launches would use; tensor t has the workgroups first[t] .. first[t + 1] - 1,
+// its own 4096 words of workspace, and cells t of amax_out / scale_out.
+struct MultiTensors {
+    const void* x[kMultiMax];
+    uint8_t* q[kMultiMax];
+    size_t n[kMultiMax];
+    int fmt[kMultiMax];
+    unsigned first[kMultiMax + 1];
+    int count;
+};
+
+__device__ __forceinline__ int multi_find(const MultiTensors& m, unsigned b)
+{
+    int t = 0;
+#pragma unroll
+    for (int i = 1; i < kMultiMax; ++i)
+        if (i < m.count && b >= m.first[i]) t = i;
+    return t;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kThreads) void amax_multi_kernel(MultiTensors m, float* __restrict__ amax_out,
+                                                             float* __restrict__ scale_out, unsigned* __restrict__ ws)
+{
+    const int t = multi_find(m, blockIdx.x);
+    amax_vec_body<DT, true>(m.x[t], m.n[t], (unsigned*)(amax_out + t), ws + (size_t)t * (FP8_AMAX_WORKSPACE_BYTES / 4), m.fmt[t],
+                            scale_out ? scale_out + t : nullptr, blockIdx.x - m.first[t], m.first[t + 1] - m.first[t]);
 }
 
 // Any alignment the element type allows: one element per lane per step.
@@ -141,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void amax_scalar_kernel(const void* __res
     r = block_max_u32(r);
     if (TICKET) {
         __syncthreads();
-        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out);
+        amax_finish_ticket(r, ws, fmt, (float*)out_bits, scale_out, blockIdx.x, gridDim.x);
         return;
     }
     if (threadIdx.x == 0) atomicMax(out_bits, r);
@@ -170,24 +211,41 @@ __global__ void scale_kernel(const float* __restrict__ amax, int fmt, float* __r
 // kStreamingStoreBytes of output, where they win 5 % because part of the output stays in the
 // 256 MB memory-side cache, and non-temporal beyond (5-8 % better there).
 template <int DT, int FMT, int PATH, bool NTS>
+__device__ __forceinline__ void quantize_vec_body(const void* __restrict__ x, size_t n, float s, uint8_t* __restrict__ q,
+                                                  unsigned bid, unsigned grid)
+{
+    constexpr int VPI = DT == FP8_BF16 ? 2 : 4;     // 16-byte vectors per 16 elements
+    const size_t nitem = n / 16;
+    const size_t per = (nitem + grid - 1) / grid;
+    const size_t lo = (size_t)bid * per;
+    const size_t hi = lo + per < nitem ? lo + per : nitem;
+    unsigned unused = 0;
+    if (lo < hi)
+        cast_run<DT, FMT, PATH, NTS, false>((const u32x4*)x, (typename Piece<DT>::type*)q, VPI * lo, VPI * hi, s, unused);
+    if (bid == 0) {                                 // fewer than 16 tail elements
+        const size_t t = nitem * 16 + threadIdx.x;
+        if (t < n) q[t] = (uint8_t)encode_bits<FMT, PATH != kCastBitsStrict>(load_scalar<DT>(x, t) * s);
+    }
+}
+
+template <int DT, int FMT, int PATH, bool NTS>
 __global__ __launch_bounds__(kThreads) void quantize_vec_kernel(const void* __restrict__ x, size_t n,
                                                                float scale,
                                                                const float* __restrict__ scale_dev,
                                                                uint8_t* __restrict__ q)
 {
-    constexpr int VPI = DT == FP8_BF16 ? 2 : 4;     // 16-byte vectors per 16 elements
-    const float s = scale_dev ? *scale_dev : scale;
-    const size_t nitem = n / 16;
-    const size_t per = (nitem + gridDim.x - 1) / gridDim.x;
-    const size_t lo = (size_t)blockIdx.x * per;
-    const size_t hi = lo + per < nitem ? lo + per : nitem;
-    unsigned unused = 0;
-    if (lo < hi)
-        cast_run<DT, FMT, PATH, NTS, false>((const u32x4*)x, (typename Piece<DT>::type*)q, VPI * lo, VPI * hi, s, unused);
-    if (blockIdx.x == 0) {                          // fewer than 16 tail elements
-        const size_t t = nitem * 16 + threadIdx.x;
-        if (t < n) q[t] = (uint8_t)encode_bits<FMT, PATH != kCastBitsStrict>(load_scalar<DT>(x, t) * s);
-    }
+    quantize_vec_body<DT, FMT, PATH, NTS>(x, n, scale_dev ? *scale_dev : scale, q, blockIdx.x, gridDim.x);
+}
+
+// Up to kMultiMax tensors in one launch (fp8_quantize_multi), grid as for amax_multi_kernel; tensor t is
+// cast with scale_dev[t] to format fmt[t].
+template <int DT, int PATH>
+__global__ __launch_bounds__(kThreads) void quantize_multi_kernel(MultiTensors m, const float* __restrict__ scale_dev)
+{
+    const int t = multi_find(m, blockIdx.x);
+    const unsigned bid = blockIdx.x - m.first[t], grid = m.first[t + 1] - m.first[t];
+    if (m.fmt[t] == FP8_E4M3) quantize_vec_body<DT, FP8_E4M3, PATH, false>(m.x[t], m.n[t], scale_dev[t], m.q[t], bid, grid);
+    else quantize_vec_body<DT, FP8_E5M2, PATH, false>(m.x[t], m.n[t], scale_dev[t], m.q[t], bid, grid);
 }
 
 // Any alignment: one element per lane per step, always the integer rounding.
@@ -246,6 +304,37 @@ int launch_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* ama
     if (n == 0) hipLaunchKernelGGL(amax_empty_kernel, dim3(1), dim3(1), 0, stream, fmt, amax_out, scale_out);
     else launch_amax_kernels<true>(x, n, in_dtype, (unsigned*)amax_out, (unsigned*)workspace, fmt, scale_out, stream);
     return check_launch("amax_scale");
+}
+
+// One launch where every tensor takes the vector path (non-empty, 16-byte aligned); tensor by tensor
+// otherwise.  Results are those of the single-tensor launches either way.
+int launch_amax_scale_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt, float* amax_out,
+                            float* scale_out, void* workspace, hipStream_t stream)
+{
+    bool one = count > 1;
+    for (int i = 0; i < count; ++i) one = one && n[i] > 0 && aligned16(x[i]);
+    if (!one) {
+        for (int i = 0; i < count; ++i)
+            if (int e = launch_amax_scale(x[i], n[i], in_dtype, fmt[i], amax_out + i, scale_out ? scale_out + i : nullptr,
+                                          (char*)workspace + (size_t)i * FP8_AMAX_WORKSPACE_BYTES, stream))
+                return e;
+        return FP8_OK;
+    }
+    MultiTensors m{};
+    m.count = count;
+    unsigned total = 0;
+    const size_t per_vec = in_dtype == FP8_F32 ? 4 : 8;
+    for (int i = 0; i < count; ++i) {
+        const size_t nchunk = n[i] / per_vec / kAmaxChunkVecs;
+        m.x[i] = x[i]; m.n[i] = n[i]; m.fmt[i] = fmt[i]; m.first[i] = total;
+        total += (unsigned)(nchunk < 1 ? 1 : nchunk > (size_t)kAmaxBlocks ? (size_t)kAmaxBlocks : nchunk);
+    }
+    for (int i = count; i <= kMultiMax; ++i) m.first[i] = total;
+    if (in_dtype == FP8_F32)
+        hipLaunchKernelGGL(amax_multi_kernel<FP8_F32>, dim3(total), dim3(kThreads), 0, stream, m, amax_out, scale_out, (unsigned*)workspace);
+    else
+        hipLaunchKernelGGL(amax_multi_kernel<FP8_BF16>, dim3(total), dim3(kThreads), 0, stream, m, amax_out, scale_out, (unsigned*)workspace);
+    return check_launch("amax_scale_multi");
 }
 
 float scale_from_amax_host(float amax, int fmt) { return scale_rule(amax, fmt); }
@@ -384,6 +473,37 @@ int launch_dequantize(const uint8_t* q, size_t n, int fmt, float scale, const fl
         else hipLaunchKernelGGL((dequantize_kernel<FP8_E5M2, FP8_BF16>), dim3(grid), dim3(kThreads), 0, stream, q, n, scale, scale_dev, out, vec);
     }
     return check_launch("dequantize");
+}
+
+int launch_quantize_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                          const float* scale_dev, uint8_t* const* q_out, hipStream_t stream)
+{
+    // one launch where every tensor takes the vector path with ordinary stores; else tensor by tensor
+    bool one = count > 1;
+    for (int i = 0; i < count; ++i) one = one && n[i] > 0 && n[i] < kStreamingStoreBytes && aligned16(x[i]) && aligned16(q_out[i]);
+    if (!one) {
+        for (int i = 0; i < count; ++i)
+            if (int e = launch_quantize(x[i], n[i], in_dtype, fmt[i], 0.0f, scale_dev + i, true, q_out[i], stream)) return e;
+        return FP8_OK;
+    }
+    MultiTensors m{};
+    m.count = count;
+    unsigned total = 0;
+    const size_t per_lane = knob(FP8_KNOB_CAST_RUN) ? (size_t)knob(FP8_KNOB_CAST_RUN) : 4;
+    for (int i = 0; i < count; ++i) {
+        m.x[i] = x[i]; m.q[i] = q_out[i]; m.n[i] = n[i]; m.fmt[i] = fmt[i]; m.first[i] = total;
+        total += (unsigned)grid_for((n[i] / 16 + per_lane - 1) / per_lane, kCastBlocks);
+    }
+    for (int i = count; i <= kMultiMax; ++i) m.first[i] = total;
+    const bool cvt = cast_path() == kCastCvt;
+    if (in_dtype == FP8_F32) {
+        if (cvt) hipLaunchKernelGGL((quantize_multi_kernel<FP8_F32, kCastCvt>), dim3(total), dim3(kThreads), 0, stream, m, scale_dev);
+        else hipLaunchKernelGGL((quantize_multi_kernel<FP8_F32, kCastBits>), dim3(total), dim3(kThreads), 0, stream, m, scale_dev);
+    } else {
+        if (cvt) hipLaunchKernelGGL((quantize_multi_kernel<FP8_BF16, kCastCvt>), dim3(total), dim3(kThreads), 0, stream, m, scale_dev);
+        else hipLaunchKernelGGL((quantize_multi_kernel<FP8_BF16, kCastBits>), dim3(total), dim3(kThreads), 0, stream, m, scale_dev);
+    }
+    return check_launch("quantize_multi");
 }
 
 }  // namespace fp8mm

@@ -37,6 +37,10 @@ int knob(int which);
 int launch_amax(const void* x, size_t n, int in_dtype, float* amax_out, hipStream_t stream);
 int launch_amax_scale(const void* x, size_t n, int in_dtype, int fmt, float* amax_out, float* scale_out, void* workspace,
                       hipStream_t stream);
+int launch_amax_scale_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt, float* amax_out,
+                            float* scale_out, void* workspace, hipStream_t stream);
+int launch_quantize_multi(int count, const void* const* x, const size_t* n, int in_dtype, const int* fmt,
+                          const float* scale_dev, uint8_t* const* q_out, hipStream_t stream);
 float scale_from_amax_host(float amax, int fmt);
 int launch_scale_from_amax(const float* amax, int fmt, float* scale_out, hipStream_t stream);
 int launch_quantize(const void* x, size_t n, int in_dtype, int fmt, float scale,

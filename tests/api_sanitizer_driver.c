@@ -59,6 +59,29 @@ int main(void)
     EXPECT(fp8_scale_from_amax_n(F, 4, -1, F, NULL), BAD);
     EXPECT(fp8_scale_from_amax_n(NULL, 4, FP8_E4M3, F, NULL), BAD);
 
+    {
+        const void* xs[5] = {X, X, X, X, X};
+        const size_t ns[5] = {16, 0, 16, 16, 16};
+        const int fm[5] = {FP8_E4M3, FP8_E5M2, FP8_E4M3, FP8_E4M3, FP8_E4M3};
+        const int badfm[2] = {FP8_E4M3, 4};
+        uint8_t* qs[5] = {A, A, A, A, A};
+        const void* withnull[2] = {X, NULL};
+        EXPECT(fp8_amax_scale_multi(5, xs, ns, FP8_BF16, fm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(-1, xs, ns, FP8_BF16, fm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(0, NULL, NULL, FP8_BF16, NULL, NULL, NULL, NULL, NULL), FP8_OK);
+        EXPECT(fp8_amax_scale_multi(2, NULL, ns, FP8_BF16, fm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(2, xs, ns, FP8_BF16, badfm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(2, xs, ns, FP8_BF16, fm, NULL, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(2, xs, ns, 9, fm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_amax_scale_multi(2, withnull, ns + 2, FP8_BF16, fm, F, F + 8, F + 64, NULL), BAD);
+        EXPECT(fp8_quantize_multi(5, xs, ns, FP8_BF16, fm, F, qs, NULL), BAD);
+        EXPECT(fp8_quantize_multi(2, xs, ns, FP8_BF16, fm, NULL, qs, NULL), BAD);
+        EXPECT(fp8_quantize_multi(2, xs, ns, FP8_BF16, fm, Fodd, qs, NULL), BAD);
+        EXPECT(fp8_quantize_multi(2, xs, ns, FP8_BF16, fm, F, NULL, NULL), BAD);
+        EXPECT(fp8_quantize_multi(2, xs, ns, FP8_BF16, badfm, F, qs, NULL), BAD);
+        EXPECT(fp8_quantize_multi(0, NULL, NULL, FP8_BF16, NULL, NULL, NULL, NULL), FP8_OK);
+    }
+
     /* casts */
     EXPECT(fp8_quantize(X, 0, FP8_BF16, FP8_E4M3, 1.0f, A, NULL), FP8_OK);          /* empty: nothing to launch */
     EXPECT(fp8_quantize(NULL, 0, FP8_F32, FP8_E5M2, 1.0f, NULL, NULL), FP8_OK);

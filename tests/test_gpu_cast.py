@@ -324,3 +324,61 @@ def test_cast_and_back_is_the_simulated_fp8_of_the_paper(fmt):
     assert bool(same.all())
     exact = oracle.dequantize(q.cpu().numpy(), fmt, np.float32(scale.item()))
     assert np.array_equal(back.cpu().numpy(), exact.astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_multi_tensor_amax_scale_and_cast_equal_the_oracle_and_the_single_tensor_calls(dtype):
+    """fp8_amax_scale_multi / fp8_quantize_multi: up to four tensors of one element type per launch,
+    each with its own format; amax, scale and bytes against the oracle (and thereby the single-tensor
+    entry points), twice in a row on one workspace (the tickets must come back to zero), with sizes
+    from one workgroup's share to many, ragged tails, specials; then the cases that are served
+    tensor by tensor inside the call (an empty tensor, one that is not 16-byte aligned)."""
+    rng = np.random.default_rng(23)
+    fmts = [fp8.FP8_E4M3, fp8.FP8_E5M2, fp8.FP8_E5M2, fp8.FP8_E4M3]
+    ws = torch.zeros(4 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    for sizes in ([1 << 21, 300_007], [70_001, 1 << 22, 17, 1_000_000], [5, 9]):
+        count = len(sizes)
+        hs = []
+        for k, n in enumerate(sizes):
+            x = (rng.standard_normal(n) * np.float32(10.0 ** (k - 1))).astype(np.float32)
+            if n > 1000:
+                x[rng.integers(0, n, 4)] = [0.0, -0.0, 1e-30, -3e4 * 10.0 ** k]
+            hs.append(x if dtype == "f32" else synth.to_bf16_bits(x))
+        ds = [to_dev(h) for h in hs]
+        amax = torch.full((count,), -1.0, device="cuda")
+        scale = torch.full((count,), -1.0, device="cuda")
+        qs = [torch.full((n,), 0xAA, dtype=torch.uint8, device="cuda") for n in sizes]
+        for rep in range(2):
+            fp8.fp8_amax_scale_multi(ds, fmts[:count], amax, scale, ws)
+            fp8.fp8_quantize_multi(ds, fmts[:count], scale, qs)
+            torch.cuda.synchronize()
+            for k in range(count):
+                a = oracle.amax(hs[k])
+                sc = oracle.scale_from_amax(a, fmts[k])
+                assert amax[k].item() == a and np.float32(scale[k].item()) == sc, (sizes, k, rep)
+                want = oracle.quantize(hs[k], fmts[k], sc)
+                got = qs[k].cpu().numpy()
+                assert np.array_equal(got, want), (sizes, k, rep, int(np.count_nonzero(got != want)))
+    # tensor-by-tensor service inside the call: an empty tensor and an unaligned one among aligned ones
+    base = to_dev((rng.standard_normal(200_001)).astype(np.float32) if dtype == "f32" else synth.to_bf16_bits(rng.standard_normal(200_001).astype(np.float32)))
+    odd = base[1:]                                                    # 4 or 2 bytes off a 16-byte boundary
+    empty = torch.empty(0, dtype=base.dtype, device="cuda")
+    big = to_dev(np.full(40_000, 3.0, dtype=np.float32) if dtype == "f32" else synth.to_bf16_bits(np.full(40_000, 3.0, dtype=np.float32)))
+    xs = [big, empty, odd]
+    amax = torch.full((3,), -1.0, device="cuda")
+    scale = torch.full((3,), -1.0, device="cuda")
+    qs = [torch.full((t.numel(),), 0xAA, dtype=torch.uint8, device="cuda") for t in xs]
+    fp8.fp8_amax_scale_multi(xs, [fp8.FP8_E4M3] * 3, amax, scale, ws)
+    fp8.fp8_quantize_multi(xs, [fp8.FP8_E4M3] * 3, scale, qs)
+    torch.cuda.synchronize()
+    assert amax[0].item() == 3.0 and amax[1].item() == 0.0 and scale[1].item() == 1.0
+    ho = odd.cpu().view(torch.int16).numpy().view(np.uint16) if dtype == "bf16" else odd.cpu().numpy()
+    a = oracle.amax(ho)
+    assert amax[2].item() == a
+    assert np.array_equal(qs[2].cpu().numpy(), oracle.quantize(ho, fp8.FP8_E4M3, oracle.scale_from_amax(a, fp8.FP8_E4M3)))
+    assert np.array_equal(qs[0].cpu().numpy(), np.full(40_000, oracle.encode(fp8.FP8_E4M3, 448.0), dtype=np.uint8))
+    for t in range(4):                                                # the counters' part of every tensor's workspace
+        lo = t * fp8.FP8_AMAX_WORKSPACE_BYTES // 4
+        assert int(ws[lo:lo + 32 * 33].abs().sum().item()) == 0, "a counter was left non-zero"
+    rc = fp8.lib().fp8_amax_scale_multi(fp8.FP8_MULTI_MAX + 1, None, None, 0, None, amax.data_ptr(), None, ws.data_ptr(), None)
+    assert rc == fp8.FP8_ERR_INVALID_ARG and "count" in fp8.binding.fp8_last_error()

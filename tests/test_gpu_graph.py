@@ -32,6 +32,9 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
     W2, W3 = torch.empty_like(W), torch.empty_like(W)
     ws_amax = torch.zeros(fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
     ws_k = torch.empty(fp8.fp8_gemm_splitk_workspace_size(K, N, M, 0, 0, 2), dtype=torch.uint8, device="cuda")
+    ws_multi = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    amax2, scale2 = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
+    q2A, q2B = torch.empty_like(qA), torch.empty_like(qB)
 
     def step():
         fp8.fp8_amax(dA, amax[0:1])
@@ -46,6 +49,8 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         fp8.fp8_amax_scale(dB, E5M2, amax[1:2], scale[2:3], ws_amax)     # one-launch amax + scale (tickets in a workspace)
         fp8.fp8_gemm_splitk(qAt, E4M3, 0, D, E5M2, 0, W2, 1.0, 1.0, ws_k, 0, 2)     # the same product in two K slices
         fp8.fp8_gemm_splitk_static(qAt, E4M3, 0, D, E5M2, 0, W3, 1.0, 1.0, 0, 2)     # ... with the library's own scratch array
+        fp8.fp8_amax_scale_multi((dA, dB), (E4M3, E5M2), amax2, scale2, ws_multi)     # both operands per launch
+        fp8.fp8_quantize_multi((dA, dB), (E4M3, E5M2), scale2, (q2A, q2B))
 
     def load(seed):
         a, b = synth.config3(M, N, K)
@@ -58,7 +63,7 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W, W2, W3)]
+        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W, W2, W3, amax2, scale2, q2A, q2B)]
 
     load(0)
     hist.zero_()
@@ -78,12 +83,13 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         hist.fill_(0.25 * (trial + 1))
         for t in (qA, qAt, qB, C, D):
             t.zero_()
-        for t in (W, W2, W3):
+        for t in (W, W2, W3, q2A, q2B, scale2):
             t.zero_()
         amax.fill_(-1.0)
+        amax2.fill_(-1.0)
         graph.replay()
         replayed = snapshot()
-        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W W2 W3".split()):
+        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W W2 W3 amax2 scale2 q2A q2B".split()):
             assert torch.equal(e.view(torch.uint8), r.view(torch.uint8)), "replay %d differs from eager in %s" % (trial, name)
         if trial == 0:                       # and eager is what the oracle says
             sA = oracle.scale_from_amax(oracle.amax(a_bits), oracle.E4M3)
@@ -97,3 +103,5 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
             assert np.all(np.abs(out_to_f64(eager[6]) - c_ref) <= bound)
             assert torch.equal(eager[9], eager[10]) and np.float32(eager[0][1].item()) == oracle.amax(b_bits)
             assert np.float32(eager[1][2].item()) == oracle.scale_from_amax(oracle.amax(b_bits), oracle.E5M2)
+            assert np.array_equal(eager[13].cpu().numpy(), Aq)              # the multi-tensor calls: A as above, B to E5M2
+            assert np.array_equal(eager[14].cpu().numpy(), oracle.quantize(b_bits, oracle.E5M2, np.float32(eager[1][2].item())))
