@@ -13,7 +13,6 @@
  *
  * Conventions of this repository that the paper does not fix ("parity
  * unpinned", they occur in none of the benchmark workloads):
- *   - the E5M2 NaN payload emitted by encode (Table 1 allows three),
  *   - the scale returned for a zero / non-finite amax (also from a history of maxima),
  *   - the stochastic-rounding rule fp8o_encode_sr (Section 2 names the mode without defining
  *     it; the rule's properties and its generator's published vectors are pinned, the choice
@@ -93,7 +92,8 @@ static int fmt_nfinite(int fmt) { return fmt == FMT_E4M3 ? 127 : 124; }
  *    (E5M2).
  *  - The sign bit of the input is kept, also when the magnitude rounds to
  *    zero (IEEE reading of the signed zeros of Section 3.1).
- *  - NaN payload for E5M2: mantissa 11 (repository convention).
+ *  - NaN payload for E5M2: mantissa 11 (Table 1 allows three; the code a widely used library cast
+ *    emits, which a test compares with).
  *
  * All comparisons are exact: a float and every FP8 value are exact doubles,
  * and so are 2*m and lo+hi.

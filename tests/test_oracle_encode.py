@@ -185,6 +185,22 @@ def test_torch_cast_agrees(fmt):
     assert np.array_equal(lib[inside], sat[inside])
 
 
+def test_nan_codes_are_those_of_the_library_cast():
+    """Table 1 gives E5M2 three NaN mantissas and does not say which one a conversion emits; the
+    oracle emits S.11111.11 for every NaN input, whatever its payload and sign: the code torch's CPU
+    cast (an independent library routine) emits.  E4M3 has a single NaN code per sign."""
+    nan_bits = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF800001, 0x7FFFFFFF, 0xFFFFFFFF, 0x7FA55AA5], dtype=np.uint32)
+    y = nan_bits.view(np.float32)
+    for fmt in FMTS:
+        lib = torch.from_numpy(y).to(TORCH[fmt]).view(torch.uint8).numpy()
+        for sat in (True, False):
+            got = oracle.quantize(y, fmt, 1.0, saturating=sat)
+            assert np.array_equal(got & 0x7F, np.full(y.size, 0x7F, dtype=np.uint8)), fmt
+            assert np.array_equal(got & 0x7F, lib & 0x7F), fmt
+    # the sign of a NaN is kept by the oracle (it copies the sign bit like for every other value)
+    assert oracle.encode(E5M2, np.float32(np.nan)) in (0x7F, 0xFF)
+
+
 def test_strict_mode_overflow_points():
     # E4M3: the virtual next grid point is 480; halfway (464) ties to the even code 0x7E
     assert oracle.encode(E4M3, 464.0, saturating=False) == 0x7E
