@@ -477,3 +477,69 @@ def test_wgrad_of_the_ffn_up_layer_full_size():
         bound2 = REL[mode] * alpha * np.abs(T) + 0.5 * oracle.ulp(c_ref2, oracle.F32)
         err = np.abs(dW[ti, tj].cpu().numpy().astype(np.float64) - c_ref2)
         assert np.all(err <= bound2), "wgrad per-row factors %s: worst err/bound %.3g" % (mode, np.max(err / bound2))
+
+
+def test_seeded_sweep_over_plans_and_epilogues_exact_on_integers():
+    """Shapes, storage orders, format pairs, both modes, every output kind, per-tensor / per-row /
+    per-column power-of-two factors and the output maximum, with the dispatcher left alone or pushed
+    by the knobs onto each of its kernels (either tile width, both widths in one launch, the
+    any-shape kernel).  Operands are small integers: every sum and every quotient is exact, so the
+    outputs (FP8 bytes included) and the maximum must equal the oracle's, and nothing may be written
+    outside D."""
+    rng = np.random.default_rng(20261)
+    seen = {}
+    for case in range(96):
+        kind = case % 4
+        if kind == 3:
+            M, N, K = int(rng.integers(1, 700)), int(rng.integers(1, 900)), int(rng.integers(1, 500))
+        else:
+            M = int(rng.integers(1, 7)) * 128 + 16 * int(rng.integers(0, 8)) * (kind == 0)
+            N = int(rng.integers(2, 12)) * 128 + 16 * int(rng.integers(0, 8)) * (kind != 1)
+            K = int(rng.integers(1, 10)) * 64 + 16 * int(rng.integers(0, 4)) * (kind == 2)
+        transA, transB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        if kind != 3 and transA:
+            M = (M + 15) // 16 * 16
+        fmtA, fmtB = (E4M3, E5M2)[int(rng.integers(0, 2))], (E4M3, E5M2)[int(rng.integers(0, 2))]
+        mode = MODES[int(rng.integers(0, len(MODES)))]
+        out_kind = int(rng.integers(0, 4))
+        per_row, per_col = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        knobs = {fp8.FP8_KNOB_MIXED: int(rng.integers(0, 3)), fp8.FP8_KNOB_TILE_N: (0, 0, 128, 256)[int(rng.integers(0, 4))],
+                 fp8.FP8_KNOB_GEMM_KERNEL: (0, 0, 0, 2)[int(rng.integers(0, 4))]}
+        ai = rng.integers(-3, 4, (M, K)).astype(np.float32)
+        bi = rng.integers(-3, 4, (K, N)).astype(np.float32)
+        A, B = oracle.quantize(ai, fmtA, 1.0), oracle.quantize(bi, fmtB, 1.0)
+        S = ai.astype(np.float64) @ bi.astype(np.float64)
+        sA = (2.0 ** rng.integers(-2, 3, M if per_row else 1)).astype(np.float32)
+        sB = (2.0 ** rng.integers(-2, 3, N if per_col else 1)).astype(np.float32)
+        c = S / (sA.astype(np.float64)[:, None] if per_row else float(sA[0])) / (sB.astype(np.float64)[None, :] if per_col else float(sB[0]))
+        sD = np.float32(2.0 ** int(rng.integers(-3, 2)))
+        if out_kind >= fp8.FP8_OUT_E4M3:
+            want = oracle.quantize(c.astype(np.float32), E4M3 if out_kind == fp8.FP8_OUT_E4M3 else E5M2, sD)
+        elif out_kind == fp8.FP8_OUT_BF16:
+            want = torch.from_numpy(c).to(torch.bfloat16).double().numpy()
+        else:
+            want = c
+        dA = to_dev(np.ascontiguousarray(A.T) if transA else A)
+        dB = to_dev(np.ascontiguousarray(B.T) if transB else B)
+        guard = 64
+        flat = torch.full((M * N + 2 * guard,), 5, dtype=OUT_T[out_kind], device="cuda")
+        D = flat[guard:guard + M * N].view(M, N)
+        amax = torch.full((1,), -1.0, device="cuda")
+        what = "case %d: %s layout %d%d formats %d%d %s out %d per-row %d per-col %d knobs %s" % (
+            case, (M, N, K), transA, transB, fmtA, fmtB, mode, out_kind, per_row, per_col, list(knobs.values()))
+        old = {k: fp8.fp8_set_knob(k, v) for k, v in knobs.items()}
+        try:
+            plan = fp8.fp8_gemm_plan(dA, transA, dB, transB, D, dev_f32(sB) if per_col else None) & 15
+            seen[plan] = seen.get(plan, 0) + 1
+            fp8.fp8_gemm_fused(dA, fmtA, transA, dB, fmtB, transB, D, out_kind, dev_f32(sA), dev_f32(sB),
+                               dev_f32(sD) if out_kind >= fp8.FP8_OUT_E4M3 else None, amax, flags_of(mode))
+            torch.cuda.synchronize()
+        finally:
+            for k, v in old.items():
+                fp8.fp8_set_knob(k, v)
+        got = D.cpu().numpy() if out_kind >= fp8.FP8_OUT_E4M3 else out_to_f64(D)
+        assert np.array_equal(got, want), what + ": %d outputs differ" % np.count_nonzero(got != want)
+        assert float(amax.item()) == float(np.max(np.abs(c))), what
+        assert bool((flat[:guard] == 5).all()) and bool((flat[guard + M * N:] == 5).all()), what + ": wrote outside D"
+    for plan in (fp8.FP8_PLAN_TILED_256x256, fp8.FP8_PLAN_TILED_256x128, fp8.FP8_PLAN_TILED_MIXED, fp8.FP8_PLAN_MFMA_ANY):
+        assert seen.get(plan, 0) >= 3, "the sweep did not reach plan %d often enough: %s" % (plan, seen)
