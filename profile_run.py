@@ -6,6 +6,7 @@ to FP8 by the library itself) or on uniformly random FP8 codes (--data random).
     python3 profile_run.py --workload ffn_up_175b --mode f16 --iters 3
     python3 profile_run.py --workload quantize_only --iters 3
     python3 profile_run.py --workload cast_variants --iters 3
+    python3 profile_run.py --workload splitk --iters 6
 """
 from __future__ import annotations
 
@@ -54,7 +55,7 @@ def random_codes(shape, top=0x5F):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="ffn_up_175b", choices=sorted(SHAPES) + ["quantize_only", "cast_variants"])
+    ap.add_argument("--workload", default="ffn_up_175b", choices=sorted(SHAPES) + ["quantize_only", "cast_variants", "splitk"])
     ap.add_argument("--mode", default="f16", choices=["f16", "mfma8"])
     ap.add_argument("--iters", type=int, default=3)
     ap.add_argument("--ramp", type=int, default=12, help="untimed GEMM launches first (clock ramp after idle), as in bench.py")
@@ -84,6 +85,18 @@ def main():
             for fmt in (fp8.FP8_E4M3, fp8.FP8_E5M2):
                 fp8.fp8_amax_scale(x, fmt, amax, scale, ws)
                 fp8.fp8_quantize_dscale(x, fmt, scale, q)
+    elif args.workload == "splitk":
+        # the weight-gradient regime of bench.py: 1024 x 1024 x 65536, A stored K x M; one workgroup per tile, then K slices
+        M = N = 1024
+        K = 65536
+        A, B = random_codes((K, M), 0x4F), random_codes((K, N), 0x6F)
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        ws = torch.empty(max(fp8.fp8_gemm_splitk_workspace_size(M, N, K, 1, 0, 0), 16), dtype=torch.uint8, device="cuda")
+        flags = 0 if args.mode == "f16" else fp8.FP8_GEMM_MFMA8
+        for _ in range(args.iters):
+            fp8.fp8_gemm_ex(A, fp8.FP8_E5M2, 1, B, fp8.FP8_E4M3, 0, C, 1.0, 1.0, flags)
+        for _ in range(args.iters):
+            fp8.fp8_gemm_splitk(A, fp8.FP8_E5M2, 1, B, fp8.FP8_E4M3, 0, C, 1.0, 1.0, ws, flags, 0)
     elif args.workload == "cast_variants":
         rows = cols = 1 << 14
         x = torch.randn(rows * cols, device="cuda").to(torch.bfloat16).view(rows, cols)
