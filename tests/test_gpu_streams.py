@@ -14,21 +14,29 @@ pytestmark = pytest.mark.gpu
 E4M3, E5M2 = fp8.FP8_E4M3, fp8.FP8_E5M2
 
 
-def whole_path(x, w, fmt_x, out, stream):
-    """amax -> scale -> cast of both operands -> GEMM, all on `stream`; returns the intermediates."""
+def whole_path(x, w, fmt_x, out, stream, form, ws):
+    """amax -> scale -> cast of both operands -> GEMM, all on `stream`; returns the intermediates.
+    form "plain": one launch per step and tensor (atomic maximum in the caller's cell); "multi": amax +
+    scale of both tensors in one launch and both casts in one launch, tickets in the workspace `ws`,
+    which belongs to this stream alone."""
     amax = torch.zeros(2, device="cuda")
     scale = torch.zeros(2, device="cuda")
     qx = torch.empty(x.shape, dtype=torch.uint8, device="cuda")
     qw = torch.empty(w.shape, dtype=torch.uint8, device="cuda")
-    for t, q, i, f in ((x, qx, 0, fmt_x), (w, qw, 1, E4M3)):
-        fp8.fp8_amax(t, amax[i:i + 1], stream=stream)
-        fp8.fp8_scale_from_amax(amax[i:i + 1], f, scale[i:i + 1], stream=stream)
-        fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q, stream=stream)
+    if form == "multi":
+        fp8.fp8_amax_scale_multi((x, w), (fmt_x, E4M3), amax, scale, ws, stream=stream)
+        fp8.fp8_quantize_multi((x, w), (fmt_x, E4M3), scale, (qx, qw), stream=stream)
+    else:
+        for t, q, i, f in ((x, qx, 0, fmt_x), (w, qw, 1, E4M3)):
+            fp8.fp8_amax(t, amax[i:i + 1], stream=stream)
+            fp8.fp8_scale_from_amax(amax[i:i + 1], f, scale[i:i + 1], stream=stream)
+            fp8.fp8_quantize_dscale(t, f, scale[i:i + 1], q, stream=stream)
     fp8.fp8_gemm_dscale(qx, fmt_x, scale[0:1], qw, E4M3, scale[1:2], out, stream=stream)
     return amax, scale, qx, qw
 
 
-def test_two_streams_and_two_threads_give_the_single_stream_results():
+@pytest.mark.parametrize("form", ["plain", "multi"])
+def test_two_streams_and_two_threads_give_the_single_stream_results(form):
     g = torch.Generator(device="cuda")
     g.manual_seed(5)
     jobs = []
@@ -41,7 +49,7 @@ def test_two_streams_and_two_threads_give_the_single_stream_results():
     alone = []
     for x, w, fmt, dt, shape in jobs:
         out = torch.empty(shape, dtype=dt, device="cuda")
-        mids = whole_path(x, w, fmt, out, None)
+        mids = whole_path(x, w, fmt, out, None, form, torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda"))
         torch.cuda.synchronize()
         alone.append((out.clone(), [m.clone() for m in mids]))
     # together: one host thread and one stream per job, several rounds each
@@ -53,9 +61,10 @@ def test_two_streams_and_two_threads_give_the_single_stream_results():
         try:
             x, w, fmt, dt, shape = jobs[j]
             with torch.cuda.stream(streams[j]):
+                ws = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")    # this stream's own
                 for _ in range(6):
                     out = torch.full(shape, 3.0, dtype=dt, device="cuda")
-                    mids = whole_path(x, w, fmt, out, streams[j])
+                    mids = whole_path(x, w, fmt, out, streams[j], form, ws)
                 streams[j].synchronize()
                 results[j] = (out, mids)
         except Exception as e:                                  # pragma: no cover
