@@ -173,15 +173,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 
 template <int DT> struct TransposeTile { static constexpr int cols = DT == FP8_BF16 ? 256 : 128; };
 
-// Four scaled values -> 4 FP8 bytes, converter path with the special values routed to the integer path.
-template <int FMT>
-__device__ __forceinline__ unsigned encode4(float y0, float y1, float y2, float y3)
-{
-    if (is_special(y0) | is_special(y1) | is_special(y2) | is_special(y3)) return encode4_bits<FMT>(y0, y1, y2, y3);
-    const unsigned w = cvt_pair<FMT, false>(y0, y1, 0u);
-    return cvt_pair<FMT, true>(y2, y3, w);
-}
-
 template <int DT, int FMT>
 __global__ __launch_bounds__(kThreads) void quantize_transpose_kernel(const void* __restrict__ x, int64_t rows, int64_t cols,
                                                                      const float* __restrict__ scale_dev,

@@ -76,6 +76,16 @@ __device__ __forceinline__ unsigned encode4_bits(float y0, float y1, float y2, f
            (encode_bits<FMT, SAT>(y3) << 24);
 }
 
+// Four scaled values -> 4 FP8 bytes (saturating): the converter instructions, with NaN / inf quadruples
+// routed to the integer path.
+template <int FMT>
+__device__ __forceinline__ unsigned encode4(float y0, float y1, float y2, float y3)
+{
+    if (is_special(y0) | is_special(y1) | is_special(y2) | is_special(y3)) return encode4_bits<FMT>(y0, y1, y2, y3);
+    const unsigned w = cvt_pair<FMT, false>(y0, y1, 0u);
+    return cvt_pair<FMT, true>(y2, y3, w);
+}
+
 // Sixteen scaled values -> four dwords.  Converter path: one test for NaN/inf over all sixteen
 // (a single, almost never taken branch per item), then eight packed conversions.
 template <int FMT, int PATH>

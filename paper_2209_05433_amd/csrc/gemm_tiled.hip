@@ -245,16 +245,16 @@ __device__ __forceinline__ void read_part(const uint8_t* smem, const Operand& op
 // A lane holds 4 consecutive N of one C row per accumulator quad; written straight out that would
 // be small pieces scattered over 32 rows per instruction.  Instead the wave turns each 32 x 32 NB
 // block around through its own piece of the (now idle) LDS and stores it with 16 bytes per lane
-// along N: whole 128-byte lines (64-byte halves for FP8 outputs of the narrow tile).  fp32 and bf16 outputs are converted before the turn; FP8 outputs
-// pass through LDS as fp32 (already multiplied by the output scale) and are rounded after it,
-// 16 consecutive columns per lane, by the same routine as in the cast kernel.
+// along N: whole 128-byte lines (64-byte halves for FP8 outputs of the narrow tile).  Every output kind is
+// converted before the turn (FP8: multiplied by the output scale and rounded four at a time by the
+// routine of the cast kernels), so the turn moves 4, 2 or 1 bytes per output.
 template <int OUT, bool BVEC, int NB>
 __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, const EpilogueArgs& ep, void* C, int M, int N,
                                          int wave_m0, int wave_n0, int w, int l)
 {
     constexpr bool FP8OUT = OUT == OUT_E4M3 || OUT == OUT_E5M2;
     constexpr int ESZ = OUT == OUT_F32 ? 4 : OUT == OUT_BF16 ? 2 : 1;     // bytes per output in memory
-    constexpr int LSZ = FP8OUT ? 4 : ESZ;                                 // bytes per output in LDS
+    constexpr int LSZ = ESZ;                                              // bytes per output in LDS
     constexpr int WN = 32 * NB;                                           // columns of the wave's sub-tile
     constexpr int ROWB = WN * LSZ + 16;                                   // padded LDS row of the wave's block
     constexpr int ROWS_PER_ST = 1024 / (WN * ESZ);                        // C rows covered by one store instruction
@@ -328,7 +328,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
                     o.y = (int)__builtin_bit_cast(unsigned, __builtin_convertvector((v2f){c2, c3}, v2bf));
                     *LDS_PTR(v2i, dst) = o;
                 } else {
-                    *LDS_PTR(v4f, dst) = (v4f){c0 * sD, c1 * sD, c2 * sD, c3 * sD};
+                    *LDS_PTR(unsigned, dst) = encode4<OUT == OUT_E4M3 ? FP8_E4M3 : FP8_E5M2>(c0 * sD, c1 * sD, c2 * sD, c3 * sD);
                 }
             }
 #pragma unroll
@@ -336,18 +336,7 @@ __device__ __forceinline__ void epilogue(v16f (&acc)[NB][4], uint8_t* smem, cons
             const int row = i * ROWS_PER_ST + st_row;
             uint8_t* out = c_wave + (size_t)(mb * 32 + row) * N * ESZ + st_col;
             if (wave_m0 + mb * 32 + row >= M || wave_n0 + st_col / ESZ >= N) continue;   // beyond the edges of C
-            u32x4 o;
-            if (FP8OUT) {
-                float y[16];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const v4f v = *LDS_PTR(v4f, blk + row * ROWB + st_col * 4 + j * 16);
-                    y[4 * j] = v.x; y[4 * j + 1] = v.y; y[4 * j + 2] = v.z; y[4 * j + 3] = v.w;
-                }
-                o = encode16<OUT == OUT_E4M3 ? FP8_E4M3 : FP8_E5M2, kCastCvt>(y);
-            } else {
-                o = *LDS_PTR(u32x4, blk + row * ROWB + st_col);
-            }
+            const u32x4 o = *LDS_PTR(u32x4, blk + row * ROWB + st_col);
             if (!ep.ragged_n) {
                 *(u32x4*)out = o;                        // (non-temporal stores measured the same, 8 shapes)
             } else {                                    // rows of C start anywhere: element by element
