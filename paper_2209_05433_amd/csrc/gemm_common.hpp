@@ -73,9 +73,11 @@ constexpr int TILE_M = 256, TILE_N = 256, TILE_K = 64;
 
 int launch_gemm(const GemmArgs& g);
 
-// The matrix-core kernel for any shape and alignment (gemm_mfma_any.hip): 128 x 128 tiles, operands
-// staged through registers.  Takes every problem with M, N, K > 0 whose tile count fits the grid.
+// The matrix-core kernel for any shape and alignment (gemm_mfma_any.hip): operands staged through
+// registers; 128 x 128 tiles, or 256 x 256 tiles where those fill the chip (mfma_any_wide).  Takes
+// every problem with M, N, K > 0 whose tile count fits the grid.
 bool mfma_any_takes(const GemmArgs& g);
+bool mfma_any_wide(const GemmArgs& g);
 int launch_mfma_any(const GemmArgs& g);
 
 // The tiled kernel instance for g's storage orders and accumulation mode, with g.tile_n, g.splits,

@@ -20,10 +20,12 @@
 //     holds (arXiv 2209.05433, Section 2: FP8 operands, single-precision accumulation, factors
 //     taken out once per output);
 //   - the epilogue is that of the generic kernel, element by element (any N, any output alignment).
-// 32 KB of LDS and about 150 registers per lane: several workgroups share a compute unit and hide
-// each other's barriers and load latencies; nothing here is pipelined by hand.
+// 32 KB of LDS and about 100 registers per lane: several workgroups share a compute unit and hide
+// each other's barriers and load latencies; nothing in this form is pipelined by hand.  Problems of
+// many tiles take the wide form further down (256 x 256 tiles, one workgroup per compute unit).
 #include "gemm_common.hpp"
 
+#include <atomic>
 #include <type_traits>
 
 namespace fp8mm {
@@ -31,6 +33,7 @@ namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 
@@ -126,6 +129,75 @@ __device__ __forceinline__ void tile_of(int64_t bid, int64_t tiles_m, int64_t ti
     tn = q / rows;
 }
 
+// Epilogue of both kernels: c = acc / (sA sB) element by element, as in the generic kernel (any N,
+// any output alignment).  acc[nb][mb] is the wave's block of 32 columns nb x 32 rows mb; wave_m /
+// wave_n = first row / column of the wave's part of C; lane (r, h) holds, per accumulator quad, 4
+// consecutive columns of row r of a block.
+// Block row MB and, by recursion, those after it: the index into acc is a constant whatever the
+// optimizer makes of the loops (an accumulator array indexed by a loop that was not unrolled would
+// go to scratch memory).  A lane's columns are col0 + (a constant per element): one row pointer per
+// block row and constant offsets, so that no element needs address registers of its own.
+template <int OUT, int NBLK, int MB>
+__device__ __forceinline__ void store_block_rows(const v16f (&acc)[NBLK][NBLK], void* __restrict__ C, int64_t M, int64_t N,
+                                                 int64_t wave_m, int64_t col0, int r, const EpilogueArgs& ep,
+                                                 float sA_host, float sB_host, float r_uniform, float sD, bool uniform,
+                                                 unsigned& amax_bits)
+{
+    typedef std::conditional_t<OUT == OUT_F32, float, std::conditional_t<OUT == OUT_BF16, unsigned short, uint8_t>> out_t;
+    const int64_t gm = wave_m + MB * 32 + r, cols_left = N - col0;
+    if (gm < M) {
+        const double a = ep.a_per_row ? (double)ep.sA_dev[gm] : (double)scale_value(ep.sA_dev, sA_host);
+        out_t* __restrict__ rowp = (out_t*)C + gm * N + col0;
+#pragma unroll
+        for (int nb = 0; nb < NBLK; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int off = nb * 32 + 8 * (e >> 2) + (e & 3);          // column col0 + off
+                if (off >= cols_left) continue;
+                float rcp = r_uniform;
+                if (!uniform) {
+                    const double b = ep.b_per_col ? (double)ep.sB_dev[col0 + off] : (double)scale_value(ep.sB_dev, sB_host);
+                    rcp = (float)(1.0 / (a * b));
+                }
+                const float c = acc[nb][MB][e] * rcp;
+                amax_bits = max(amax_bits, as_u32(c) & 0x7fffffffu);
+                if (OUT == OUT_F32) rowp[off] = (out_t)c;
+                else if (OUT == OUT_BF16) rowp[off] = (out_t)bf16_bits_any(c);
+                else if (OUT == OUT_E4M3) rowp[off] = (out_t)encode_bits<FP8_E4M3>(c * sD);
+                else rowp[off] = (out_t)encode_bits<FP8_E5M2>(c * sD);
+            }
+    }
+    if constexpr (MB + 1 < NBLK)
+        store_block_rows<OUT, NBLK, MB + 1>(acc, C, M, N, wave_m, col0, r, ep, sA_host, sB_host, r_uniform, sD, uniform, amax_bits);
+}
+
+template <int OUT, int NBLK>
+__device__ __forceinline__ void store_outputs_as(const v16f (&acc)[NBLK][NBLK], void* __restrict__ C, int64_t M, int64_t N,
+                                                 int64_t wave_m, int64_t wave_n, int r, int h, const EpilogueArgs& ep)
+{
+    const float sA_host = ep.sA, sB_host = ep.sB;     // by value: a choice between two memory locations would cost scratch
+    const bool uniform = !ep.a_per_row && !ep.b_per_col;
+    const float r_uniform = uniform ? (float)(1.0 / ((double)scale_value(ep.sA_dev, sA_host) * (double)scale_value(ep.sB_dev, sB_host))) : 0.0f;
+    const float sD = (OUT >= OUT_E4M3) ? scale_value(ep.sD_dev, 1.0f) : 1.0f;
+    unsigned amax_bits = 0;
+    store_block_rows<OUT, NBLK, 0>(acc, C, M, N, wave_m, wave_n + 4 * h, r, ep, sA_host, sB_host, r_uniform, sD, uniform, amax_bits);
+    if (ep.amax_out) wave_amax_commit(amax_bits, ep.amax_out);
+}
+
+template <int NBLK>
+__device__ __forceinline__ void store_outputs(const v16f (&acc)[NBLK][NBLK], void* __restrict__ C, int64_t M, int64_t N,
+                                              int64_t wave_m, int64_t wave_n, int r, int h, const EpilogueArgs& ep)
+{
+    switch (ep.out_kind) {
+        case OUT_F32: store_outputs_as<OUT_F32>(acc, C, M, N, wave_m, wave_n, r, h, ep); break;
+        case OUT_BF16: store_outputs_as<OUT_BF16>(acc, C, M, N, wave_m, wave_n, r, h, ep); break;
+        case OUT_E4M3: store_outputs_as<OUT_E4M3>(acc, C, M, N, wave_m, wave_n, r, h, ep); break;
+        default: store_outputs_as<OUT_E5M2>(acc, C, M, N, wave_m, wave_n, r, h, ep); break;
+    }
+}
+
+int64_t tile_count(const GemmArgs& g, int64_t edge) { return ((g.M + edge - 1) / edge) * ((g.N + edge - 1) / edge); }
+
 template <int FMT_A, int FMT_B, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
@@ -191,73 +263,276 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
         __syncthreads();
     }
 
-    // ---- epilogue: c = acc / (sA sB) element by element, as in the generic kernel -----------------
-    const float sA_host = ep.sA, sB_host = ep.sB;     // by value: a choice between two memory locations would cost scratch
-    const bool uniform = !ep.a_per_row && !ep.b_per_col;
-    const float r_uniform = uniform ? (float)(1.0 / ((double)scale_value(ep.sA_dev, sA_host) * (double)scale_value(ep.sB_dev, sB_host))) : 0.0f;
-    const float sD = (ep.out_kind >= OUT_E4M3) ? scale_value(ep.sD_dev, 1.0f) : 1.0f;
-    unsigned amax_bits = 0;
+    store_outputs<2>(acc, C, M, N, m0 + wm * 64, n0 + wn * 64, r, h, ep);
+}
+
+// ---- the wide form ------------------------------------------------------------------------------
+// For problems of many tiles: a 256 x 256 tile per workgroup (128 x 128 per wave as 4 x 4 blocks,
+// half the LDS reads per product of the 2 x 2 form), one workgroup per compute unit, so nobody
+// hides a workgroup's waits but itself:
+//   - the LDS holds two stages of both images (128 KB); stage s is multiplied out of one half
+//     while stage s + 1 is written into the other, one barrier per stage;
+//   - two register sets: the bytes of stage s + 2 are requested before stage s is multiplied and
+//     are widened and written to LDS a stage later, between the two halves of stage s + 1's products;
+//   - an operand that is contiguous along M / N is fetched as 4 consecutive K rows x 16 tile rows per
+//     thread and turned round in registers (byte permutes), so that the image gets 8-byte writes
+//     (4 halves along K) instead of 2-byte ones.
+constexpr int WT = 256;                         // tile edge
+constexpr int WNV = WT * FK / 16 / 256;         // 16-byte vectors per thread, operand and stage: 4
+constexpr int W_IMG = WT * FPITCH;              // one operand, one stage: 32 KB
+constexpr int W_LDS = 4 * W_IMG;
+
+// Sixteen zero bytes in device memory, never written: what a lane of the wide form loads in place of
+// a piece that is not wholly inside its row.
+__device__ __attribute__((aligned(16))) uint8_t g_any_zero_chunk[16];
+
+// Where vector v (of WNV) of the thread's bytes for the stage that starts at k0 lies, and how many
+// of its 16 bytes exist (16 = all; <= 0 = none: the piece lies beyond the edge of the operand):
+//   KC: as in fetch_stage (row 64 v + tid / 4, K bytes 16 (tid % 4) ..);
+//   MC: K-row 4 (tid / 16) + v, tile rows 16 (tid % 16) .. : 16 lanes cover the 256 bytes of a K-row.
+template <bool KC>
+__device__ __forceinline__ const uint8_t* piece_wide(const uint8_t* base, int64_t ext, int64_t K, int64_t t0, int64_t k0, int tid, int v,
+                                                     int64_t& count)
+{
+    if (KC) {
+        const int64_t r = t0 + 64 * v + (tid >> 2), k = k0 + (tid & 3) * 16;
+        count = r < ext ? K - k : 0;
+        return base + r * K + k;
+    }
+    const int64_t k = k0 + 4 * (tid >> 4) + v, r = t0 + (tid & 15) * 16;
+    count = k < K ? ext - r : 0;
+    return base + k * ext + r;
+}
+
+// The thread's WNV vectors of one operand for the stage that starts at k0.  First one 16-byte load per
+// vector, unconditionally (whole pieces from the operand, the others from the zero chunk); only then
+// the pieces that straddle an edge, byte by byte.  In that order the number of loads issued after
+// any earlier load has a known minimum, and the waits for the stage fetched before this one leave
+// this stage's loads in flight.  (With each piece's choice between one load and its bytes made in
+// place, every wait for older bytes also waited for the loads just issued.)
+template <bool KC>
+__device__ __forceinline__ void fetch_wide(u32x4 (&x)[WNV], const uint8_t* base, int64_t ext, int64_t K, int64_t t0, int64_t k0, int tid)
+{
+    const uint8_t* p[WNV];
+    int64_t count[WNV];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-        const int64_t gm = m0 + wm * 64 + mb * 32 + r;
-        if (gm >= M) continue;
-        const double a = ep.a_per_row ? (double)ep.sA_dev[gm] : (double)scale_value(ep.sA_dev, sA_host);
+    for (int v = 0; v < WNV; ++v) {
+        p[v] = piece_wide<KC>(base, ext, K, t0, k0, tid, v, count[v]);
+        __builtin_memcpy(&x[v], count[v] >= 16 ? p[v] : g_any_zero_chunk, 16);
+    }
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+    for (int v = 0; v < WNV; ++v)
+        if (count[v] > 0 && count[v] < 16) {
+            u32x4 e = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t gn = n0 + wn * 64 + nb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                if (gn >= N) continue;
-                float rcp = r_uniform;
-                if (!uniform) {
-                    const double b = ep.b_per_col ? (double)ep.sB_dev[gn] : (double)scale_value(ep.sB_dev, sB_host);
-                    rcp = (float)(1.0 / (a * b));
-                }
-                const float c = acc[nb][mb][e] * rcp;
-                amax_bits = max(amax_bits, as_u32(c) & 0x7fffffffu);
-                const int64_t o = gm * N + gn;
-                switch (ep.out_kind) {
-                    case OUT_F32: ((float*)C)[o] = c; break;
-                    case OUT_BF16: ((unsigned short*)C)[o] = (unsigned short)bf16_bits_any(c); break;
-                    case OUT_E4M3: ((uint8_t*)C)[o] = (uint8_t)encode_bits<FP8_E4M3>(c * sD); break;
-                    default: ((uint8_t*)C)[o] = (uint8_t)encode_bits<FP8_E5M2>(c * sD); break;
+            for (int j = 0; j < 16; ++j)
+                if (j < count[v]) e[j >> 2] |= (unsigned)p[v][j] << (8 * (j & 3));
+            x[v] = e;
+        }
+}
+
+// Part d (of WNV) of the thread's share of writing an operand's stage into its image.
+//   KC: vector d as in store_stage.
+//   MC: byte j of x[v] is the element of tile row 16 (tid % 16) + j at K index 4 (tid / 16) + v; part d
+//       takes the tile rows 4 d .. 4 d + 3: 4 x 4 bytes (K index x tile row) are turned into 4 words,
+//       one per tile row with K ascending, widened, and written as 4 halves (8 bytes) per row.
+template <int FMT, bool KC>
+__device__ __forceinline__ void store_wide_part(uint8_t* img, const u32x4 (&x)[WNV], int tid, int d)
+{
+    if (KC) {
+        store_stage<FMT, true>(img, x[d], tid, d);
+        return;
+    }
+    const int kg = tid >> 4, row = (tid & 15) * 16 + 4 * d;
+    const int chunk = kg >> 1, inner = (kg & 1) * 8;          // 8 halves per 16-byte chunk: K indices 4 kg .. 4 kg + 3
+    const unsigned t0 = __builtin_amdgcn_perm(x[1][d], x[0][d], 0x05010400u), t1 = __builtin_amdgcn_perm(x[1][d], x[0][d], 0x07030602u);
+    const unsigned u0 = __builtin_amdgcn_perm(x[3][d], x[2][d], 0x05010400u), u1 = __builtin_amdgcn_perm(x[3][d], x[2][d], 0x07030602u);
+    const unsigned w0 = __builtin_amdgcn_perm(u0, t0, 0x05040100u), w1 = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
+    const unsigned w2 = __builtin_amdgcn_perm(u1, t1, 0x05040100u), w3 = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
+    const v8h h01 = widen8<FMT>((int)w0, (int)w1), h23 = widen8<FMT>((int)w2, (int)w3);
+    *LDS_PTR(v4h, img + (row + 0) * FPITCH + ((chunk ^ swz(row + 0)) * 16) + inner) = (v4h){h01[0], h01[1], h01[2], h01[3]};
+    *LDS_PTR(v4h, img + (row + 1) * FPITCH + ((chunk ^ swz(row + 1)) * 16) + inner) = (v4h){h01[4], h01[5], h01[6], h01[7]};
+    *LDS_PTR(v4h, img + (row + 2) * FPITCH + ((chunk ^ swz(row + 2)) * 16) + inner) = (v4h){h23[0], h23[1], h23[2], h23[3]};
+    *LDS_PTR(v4h, img + (row + 3) * FPITCH + ((chunk ^ swz(row + 3)) * 16) + inner) = (v4h){h23[4], h23[5], h23[6], h23[7]};
+}
+
+template <int FMT_A, int FMT_B, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(256) void gemm_mfma_any_wide_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, void* __restrict__ C,
+    int64_t M, int64_t N, int64_t K, EpilogueArgs ep)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // [stage parity][A image, B image]
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63;
+    const int wm = w >> 1, wn = w & 1, r = l & 31, h = l >> 5;
+    const int64_t tiles_m = (M + WT - 1) / WT, tiles_n = (N + WT - 1) / WT;
+    int64_t tm, tn;
+    tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = tm * WT, n0 = tn * WT;
+    const int64_t stages = (K + FK - 1) / FK;
+
+    v16f acc[4][4];                                   // [block of 32 columns][block of 32 rows]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    auto fetch = [&](u32x4 (&xa)[WNV], u32x4 (&xb)[WNV], int64_t stage) __attribute__((always_inline)) {
+        fetch_wide<A_KC>(xa, A, M, K, m0, stage * FK, tid);
+        fetch_wide<B_KC>(xb, B, N, K, n0, stage * FK, tid);
+    };
+    // the same for a stage that lies wholly inside K, of a tile that lies wholly inside C: no tests
+    auto fetch_inside = [&](u32x4 (&xa)[WNV], u32x4 (&xb)[WNV], int64_t stage) __attribute__((always_inline)) {
+        int64_t count;
+#pragma unroll
+        for (int v = 0; v < WNV; ++v) {
+            __builtin_memcpy(&xa[v], piece_wide<A_KC>(A, M, K, m0, stage * FK, tid, v, count), 16);
+            __builtin_memcpy(&xb[v], piece_wide<B_KC>(B, N, K, n0, stage * FK, tid, v, count), 16);
+        }
+    };
+    // lane (r, h): fragments of the K indices 16 s .. 16 s + 15 of the stage in half `parity`
+    auto read_frags = [&](int parity, int s, v8h (&af)[4], v8h (&bf)[4]) __attribute__((always_inline)) {
+        const uint8_t* As = lds + parity * 2 * W_IMG;
+        const uint8_t* Bs = As + W_IMG;
+        const int c = 2 * h + (s & 1) + 4 * (s >> 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ra_ = wm * 128 + i * 32 + r, rb_ = wn * 128 + i * 32 + r;
+            af[i] = *LDS_PTR(v8h, As + ra_ * FPITCH + ((c ^ swz(ra_)) * 16));
+            bf[i] = *LDS_PTR(v8h, Bs + rb_ * FPITCH + ((c ^ swz(rb_)) * 16));
+        }
+    };
+    // One stage: the products of the stage in half `parity`, in four K sub-steps; the fragments of a
+    // sub-step are read during the one before it.  STORE: meanwhile (xa, xb), the bytes of the next
+    // stage, go into the other half, a quarter per sub-step, so that the widening and the LDS writes
+    // are issued between the matrix instructions and not after them.
+    auto stage = [&](auto store_tag, int parity, const u32x4 (&xa)[WNV], const u32x4 (&xb)[WNV]) __attribute__((always_inline)) {
+        constexpr bool STORE = decltype(store_tag)::value;
+        uint8_t* other = lds + (parity ^ 1) * 2 * W_IMG;
+        v8h af[2][4], bf[2][4];
+        read_frags(parity, 0, af[0], bf[0]);
+#pragma unroll
+        for (int s = 0; s < FK / 16; ++s) {
+            if (s + 1 < FK / 16) read_frags(parity, s + 1, af[(s + 1) & 1], bf[(s + 1) & 1]);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[s & 1][nb], af[s & 1][mb], acc[nb][mb], 0, 0, 0);
+            if (STORE) {
+                store_wide_part<FMT_A, A_KC>(other, xa, tid, s);
+                store_wide_part<FMT_B, B_KC>(other + W_IMG, xb, tid, s);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one matrix instruction,
+                if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // one fragment read of the next sub-step,
+                if (STORE) {
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                // two vector instructions of the store
+                    if (i >= 4 && (i & 1)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // and its LDS writes behind them
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);        // nothing drifts into another sub-step (register pressure)
+        }
+    };
+
+    u32x4 a0[WNV], b0[WNV], a1[WNV], b1[WNV];         // register set 0: even stages, set 1: odd stages
+    fetch(a0, b0, 0);
+    if (stages > 1) fetch(a1, b1, 1);
+#pragma unroll
+    for (int d = 0; d < WNV; ++d) {
+        store_wide_part<FMT_A, A_KC>(lds, a0, tid, d);
+        store_wide_part<FMT_B, B_KC>(lds + W_IMG, b0, tid, d);
     }
-    if (ep.amax_out) wave_amax_commit(amax_bits, ep.amax_out);
+    __syncthreads();
+    // Two stages per trip; an odd last stage follows the loop.  (With the loop left from the middle
+    // of a trip, or with a choice between two forms of a stage inside it, the compiler spilled a
+    // thousand registers per lane.)  Every condition is the same for the whole workgroup.
+    int64_t st = 0;
+    // trips whose two fetches need no tests: straight-line code (with branches in the loop the
+    // accumulators changed register class, 256 moves, in every stage)
+    const int64_t inside = (m0 + WT <= M && n0 + WT <= N) ? K / FK : 0;
+    for (; st + 3 < inside; st += 2) {
+        fetch_inside(a0, b0, st + 2);
+        stage(std::true_type{}, 0, a1, b1);
+        __syncthreads();
+        fetch_inside(a1, b1, st + 3);
+        stage(std::true_type{}, 1, a0, b0);
+        __syncthreads();
+    }
+    // the other trips: edge tiles, and the end of K
+    for (; st + 2 <= stages; st += 2) {
+        if (st + 2 < stages) fetch(a0, b0, st + 2);
+        stage(std::true_type{}, 0, a1, b1);
+        __syncthreads();
+        if (st + 3 < stages) fetch(a1, b1, st + 3);
+        stage(std::true_type{}, 1, a0, b0);           // after the last stage: old bytes into a half nobody reads again
+        __syncthreads();
+    }
+    if (st < stages) stage(std::false_type{}, 0, a0, b0);
+
+    store_outputs<4>(acc, C, M, N, m0 + wm * 128, n0 + wn * 128, r, h, ep);
 }
 
 template <int FA, int FB, bool A_KC, bool B_KC>
-int launch_one(const GemmArgs& g, unsigned tiles)
+int launch_one(const GemmArgs& g, bool wide)
 {
-    hipLaunchKernelGGL((gemm_mfma_any_kernel<FA, FB, A_KC, B_KC>), dim3(tiles), dim3(256), 0, g.stream, g.A, g.B, g.C,
-                       g.M, g.N, g.K, g.ep);
-    return check_launch("gemm (matrix-core kernel for any shape)");
+    if (!wide) {
+        hipLaunchKernelGGL((gemm_mfma_any_kernel<FA, FB, A_KC, B_KC>), dim3((unsigned)tile_count(g, FT)), dim3(256), 0, g.stream,
+                           g.A, g.B, g.C, g.M, g.N, g.K, g.ep);
+        return check_launch("gemm (matrix-core kernel for any shape)");
+    }
+    // the wide form needs more dynamic LDS than the default limit: raised once per device
+    static std::atomic<unsigned long long> attr_set{0ull};
+    auto kern = gemm_mfma_any_wide_kernel<FA, FB, A_KC, B_KC>;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(FP8_ERR_DEVICE, "hipGetDevice failed");
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev >= 64 || !(attr_set.load(std::memory_order_relaxed) & bit)) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS);
+        if (e != hipSuccess)
+            return fail(FP8_ERR_DEVICE, "hipFuncSetAttribute(LDS=%d): %s", W_LDS, hipGetErrorString(e));
+        if (dev < 64) attr_set.fetch_or(bit, std::memory_order_relaxed);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)tile_count(g, WT)), dim3(256), W_LDS, g.stream, g.A, g.B, g.C, g.M, g.N, g.K, g.ep);
+    return check_launch("gemm (matrix-core kernel for any shape, wide form)");
 }
 
 template <int FA, int FB>
-int launch_layout(const GemmArgs& g, unsigned tiles)
+int launch_layout(const GemmArgs& g, bool wide)
 {
     // A stored M x K is K-contiguous; B stored N x K (transB) is K-contiguous
-    if (!g.transA) return g.transB ? launch_one<FA, FB, true, true>(g, tiles) : launch_one<FA, FB, true, false>(g, tiles);
-    return g.transB ? launch_one<FA, FB, false, true>(g, tiles) : launch_one<FA, FB, false, false>(g, tiles);
+    if (!g.transA) return g.transB ? launch_one<FA, FB, true, true>(g, wide) : launch_one<FA, FB, true, false>(g, wide);
+    return g.transB ? launch_one<FA, FB, false, true>(g, wide) : launch_one<FA, FB, false, false>(g, wide);
 }
-
-int64_t tile_count(const GemmArgs& g) { return ((g.M + FT - 1) / FT) * ((g.N + FT - 1) / FT); }
 
 }  // namespace
 
 bool mfma_any_takes(const GemmArgs& g)
 {
-    return g.M > 0 && g.N > 0 && g.K > 0 && tile_count(g) <= 0x7fffffffll;
+    return g.M > 0 && g.N > 0 && g.K > 0 && tile_count(g, FT) <= 0x7fffffffll;
+}
+
+// The wide form where its 256 x 256 tiles fill the rounds of one workgroup per compute unit to
+// 80 % at least and K is long enough for the two-stage pipeline to pay; FP8_KNOB_TILE_N forces
+// either form (128 / 256).
+bool mfma_any_wide(const GemmArgs& g)
+{
+    const int forced = knob(FP8_KNOB_TILE_N);
+    if (forced) return forced == 256;
+    const int64_t tiles = tile_count(g, WT), units = 256;
+    const int64_t rounds = (tiles + units - 1) / units;
+    return g.K >= 8 * FK && 5 * tiles >= 4 * rounds * units;
 }
 
 int launch_mfma_any(const GemmArgs& g)
 {
-    const unsigned tiles = (unsigned)tile_count(g);
+    const bool wide = mfma_any_wide(g);
     if (g.fmtA == FP8_E4M3)
-        return g.fmtB == FP8_E4M3 ? launch_layout<FP8_E4M3, FP8_E4M3>(g, tiles) : launch_layout<FP8_E4M3, FP8_E5M2>(g, tiles);
-    return g.fmtB == FP8_E4M3 ? launch_layout<FP8_E5M2, FP8_E4M3>(g, tiles) : launch_layout<FP8_E5M2, FP8_E5M2>(g, tiles);
+        return g.fmtB == FP8_E4M3 ? launch_layout<FP8_E4M3, FP8_E4M3>(g, wide) : launch_layout<FP8_E4M3, FP8_E5M2>(g, wide);
+    return g.fmtB == FP8_E4M3 ? launch_layout<FP8_E5M2, FP8_E4M3>(g, wide) : launch_layout<FP8_E5M2, FP8_E5M2>(g, wide);
 }
 
 }  // namespace fp8mm

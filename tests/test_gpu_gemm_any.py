@@ -4,7 +4,10 @@ boundaries, unaligned pointers) against the CPU oracle, through fp8_gemm_ex / fp
 
 Acceptance as for fp8_gemm: |C - C_ref| <= 2^-20 * sum_k |a b| / (sA sB) + ulp_out(C_ref) / 2, and
 equality where the sums are exact.  FP8_KNOB_GEMM_KERNEL = 2 forces the kernel onto problems the
-tiled kernel would take, = 1 forces the plain FMA kernel (an independent second implementation)."""
+tiled kernel would take, = 1 forces the plain FMA kernel (an independent second implementation).
+The kernel has two forms (128 x 128 tiles, several workgroups per compute unit; 256 x 256 tiles,
+pipelined by hand, for problems of many tiles); FP8_KNOB_TILE_N = 128 / 256 forces one, and the
+tests run under both."""
 
 import numpy as np
 import pytest
@@ -19,6 +22,12 @@ pytestmark = pytest.mark.gpu
 E4M3, E5M2 = fp8.FP8_E4M3, fp8.FP8_E5M2
 OUT = {fp8.FP8_F32: torch.float32, fp8.FP8_BF16: torch.bfloat16}
 ANY = fp8.FP8_PLAN_MFMA_ANY
+
+
+@pytest.fixture(params=[128, 256], ids=["tile128", "tile256"])
+def form(request):
+    with knob(fp8.FP8_KNOB_TILE_N, request.param):
+        yield request.param
 
 
 def random_codes(rng, shape, fmt, top=None):
@@ -37,12 +46,13 @@ def bound_check(C, S, T, sA, sB, out_dtype, what):
 
 
 @pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-def test_odd_shapes_every_storage_order_exact_on_integers(transA, transB):
+def test_odd_shapes_every_storage_order_exact_on_integers(transA, transB, form):
     """Shapes with nothing aligned (odd M, N, K; one to several tiles; K shorter than a stage, K with
     a ragged last 16-byte piece), small integer operands: every sum is exact, the result must equal
     the oracle's, and nothing may be written outside C."""
     rng = np.random.default_rng(40 + 2 * transA + transB)
-    for (M, N, K) in [(1, 1, 1), (5, 3, 7), (129, 127, 33), (131, 257, 95), (300, 401, 777), (64, 1001, 50), (515, 130, 1)]:
+    for (M, N, K) in [(1, 1, 1), (5, 3, 7), (129, 127, 33), (131, 257, 95), (300, 401, 777), (64, 1001, 50), (515, 130, 1),
+                      (257, 513, 64), (260, 250, 129), (77, 300, 193), (258, 31, 256), (33, 290, 321)]:
         fmtA, fmtB = ((E4M3, E5M2), (E5M2, E4M3))[(M + N) % 2]
         A = oracle.quantize(rng.integers(-4, 5, (M, K)).astype(np.float32), fmtA, 1.0)
         B = oracle.quantize(rng.integers(-4, 5, (K, N)).astype(np.float32), fmtB, 1.0)
@@ -65,7 +75,7 @@ def test_odd_shapes_every_storage_order_exact_on_integers(transA, transB):
 
 
 @pytest.mark.parametrize("offA,offB", [(1, 0), (0, 3), (5, 9), (15, 15)])
-def test_operands_at_any_address(offA, offB):
+def test_operands_at_any_address(offA, offB, form):
     """Operand pointers that are not 16-byte aligned (views into larger byte buffers), aligned shapes:
     the dispatcher must choose this kernel by itself, and the result must meet the bound."""
     rng = np.random.default_rng(7 + offA + 16 * offB)
@@ -85,7 +95,7 @@ def test_operands_at_any_address(offA, offB):
 
 
 @pytest.mark.parametrize("transA,transB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-def test_random_codes_forced_on_a_tiled_problem_and_against_the_other_kernels(transA, transB):
+def test_random_codes_forced_on_a_tiled_problem_and_against_the_other_kernels(transA, transB, form):
     """A problem the tiled kernel takes (512 x 384 x 640), forced through this kernel: within the
     bound of the oracle, like the tiled kernel and the plain FMA kernel on the same bytes."""
     rng = np.random.default_rng(90 + 2 * transA + transB)
@@ -101,7 +111,7 @@ def test_random_codes_forced_on_a_tiled_problem_and_against_the_other_kernels(tr
         bound_check(C, S, T, 1.5, 0.75, fp8.FP8_F32, label)
 
 
-def test_vocabulary_sized_weight_stored_in_by_out():
+def test_vocabulary_sized_weight_stored_in_by_out(form):
     """The shape class this kernel exists for: B stored K x N with an odd N (a vocabulary projection
     with the weight kept [in, out]), several hundred tiles, K a multiple of nothing in particular;
     sampled rows against the oracle."""
@@ -119,7 +129,7 @@ def test_vocabulary_sized_weight_stored_in_by_out():
         bound_check(C[torch.from_numpy(rows).cuda()], S, T, 4.0, 2.0, out_dtype, "N = 5027, out %d" % out_dtype)
 
 
-def test_special_values_and_zero_padding():
+def test_special_values_and_zero_padding(form):
     """NaN and infinity in the operands propagate as IEEE arithmetic says, also next to the zero
     padding of a ragged K and ragged tile edges: the padding must not turn an infinity into NaN."""
     M, N, K = 70, 45, 50
@@ -139,7 +149,7 @@ def test_special_values_and_zero_padding():
     assert np.all(np.isinf(got[3, np.arange(N) != 7])) and np.all(np.isnan(got[9])) and np.all(np.isnan(got[:, 7]))
 
 
-def test_fused_epilogue_on_a_ragged_problem():
+def test_fused_epilogue_on_a_ragged_problem(form):
     """Per-row and per-column factors, FP8 output with output scale and output amax, on a shape only
     this kernel takes; integers, so the FP8 bytes must be the oracle's."""
     rng = np.random.default_rng(77)
