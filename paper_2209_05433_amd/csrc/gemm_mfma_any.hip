@@ -331,29 +331,30 @@ __device__ __forceinline__ void fetch_wide(u32x4 (&x)[WNV], const uint8_t* base,
         }
 }
 
-// Part d (of WNV) of the thread's share of writing an operand's stage into its image.
-//   KC: vector d as in store_stage.
-//   MC: byte j of x[v] is the element of tile row 16 (tid % 16) + j at K index 4 (tid / 16) + v; part d
-//       takes the tile rows 4 d .. 4 d + 3: 4 x 4 bytes (K index x tile row) are turned into 4 words,
-//       one per tile row with K ascending, widened, and written as 4 halves (8 bytes) per row.
+// Piece q (of 2 WNV) of the thread's share of writing an operand's stage into its image; d = q / 2.
+//   KC: 8 of the 16 bytes of vector d, placed as in store_stage.
+//   MC: byte j of x[v] is the element of tile row 16 (tid % 16) + j at K index 4 (tid / 16) + v; the
+//       piece takes the tile rows 4 d + 2 (q % 2) and the one after it: 4 x 2 bytes (K index x tile
+//       row) are turned into 2 words, one per tile row with K ascending, widened, and written as
+//       4 halves (8 bytes) per row.
 template <int FMT, bool KC>
-__device__ __forceinline__ void store_wide_part(uint8_t* img, const u32x4 (&x)[WNV], int tid, int d)
+__device__ __forceinline__ void store_wide_piece(uint8_t* img, const u32x4 (&x)[WNV], int tid, int q)
 {
+    const int d = q >> 1, second = q & 1;
     if (KC) {
-        store_stage<FMT, true>(img, x[d], tid, d);
+        const int row = 64 * d + (tid >> 2), c = 2 * (tid & 3) + second;
+        const v8h hv = second ? widen8<FMT>((int)x[d].z, (int)x[d].w) : widen8<FMT>((int)x[d].x, (int)x[d].y);
+        *LDS_PTR(v8h, img + row * FPITCH + ((c ^ swz(row)) * 16)) = hv;
         return;
     }
-    const int kg = tid >> 4, row = (tid & 15) * 16 + 4 * d;
+    const int kg = tid >> 4, row = (tid & 15) * 16 + 4 * d + 2 * second;
     const int chunk = kg >> 1, inner = (kg & 1) * 8;          // 8 halves per 16-byte chunk: K indices 4 kg .. 4 kg + 3
-    const unsigned t0 = __builtin_amdgcn_perm(x[1][d], x[0][d], 0x05010400u), t1 = __builtin_amdgcn_perm(x[1][d], x[0][d], 0x07030602u);
-    const unsigned u0 = __builtin_amdgcn_perm(x[3][d], x[2][d], 0x05010400u), u1 = __builtin_amdgcn_perm(x[3][d], x[2][d], 0x07030602u);
-    const unsigned w0 = __builtin_amdgcn_perm(u0, t0, 0x05040100u), w1 = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
-    const unsigned w2 = __builtin_amdgcn_perm(u1, t1, 0x05040100u), w3 = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
-    const v8h h01 = widen8<FMT>((int)w0, (int)w1), h23 = widen8<FMT>((int)w2, (int)w3);
-    *LDS_PTR(v4h, img + (row + 0) * FPITCH + ((chunk ^ swz(row + 0)) * 16) + inner) = (v4h){h01[0], h01[1], h01[2], h01[3]};
-    *LDS_PTR(v4h, img + (row + 1) * FPITCH + ((chunk ^ swz(row + 1)) * 16) + inner) = (v4h){h01[4], h01[5], h01[6], h01[7]};
-    *LDS_PTR(v4h, img + (row + 2) * FPITCH + ((chunk ^ swz(row + 2)) * 16) + inner) = (v4h){h23[0], h23[1], h23[2], h23[3]};
-    *LDS_PTR(v4h, img + (row + 3) * FPITCH + ((chunk ^ swz(row + 3)) * 16) + inner) = (v4h){h23[4], h23[5], h23[6], h23[7]};
+    const unsigned sel = second ? 0x07030602u : 0x05010400u;  // bytes 2, 3 / 0, 1 of both words, interleaved
+    const unsigned t = __builtin_amdgcn_perm(x[1][d], x[0][d], sel), u = __builtin_amdgcn_perm(x[3][d], x[2][d], sel);
+    const unsigned w0 = __builtin_amdgcn_perm(u, t, 0x05040100u), w1 = __builtin_amdgcn_perm(u, t, 0x07060302u);
+    const v8h hv = widen8<FMT>((int)w0, (int)w1);
+    *LDS_PTR(v4h, img + (row + 0) * FPITCH + ((chunk ^ swz(row + 0)) * 16) + inner) = (v4h){hv[0], hv[1], hv[2], hv[3]};
+    *LDS_PTR(v4h, img + (row + 1) * FPITCH + ((chunk ^ swz(row + 1)) * 16) + inner) = (v4h){hv[4], hv[5], hv[6], hv[7]};
 }
 
 template <int FMT_A, int FMT_B, bool A_KC, bool B_KC>
@@ -383,70 +384,106 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_wide_kernel(
         fetch_wide<A_KC>(xa, A, M, K, m0, stage * FK, tid);
         fetch_wide<B_KC>(xb, B, N, K, n0, stage * FK, tid);
     };
-    // the same for a stage that lies wholly inside K, of a tile that lies wholly inside C: no tests
+    // the same for a stage that lies wholly inside K, of a tile that lies wholly inside C: no tests,
+    // and addresses as a base per stage (the same for the whole workgroup) plus the thread's offset
+    // of each vector within the tile's stage (fits 32 bits: see mfma_any_wide)
+    unsigned offa[WNV], offb[WNV];
+#pragma unroll
+    for (int v = 0; v < WNV; ++v) {
+        offa[v] = A_KC ? (unsigned)(64 * v + (tid >> 2)) * (unsigned)K + (tid & 3) * 16 : (unsigned)(4 * (tid >> 4) + v) * (unsigned)M + (tid & 15) * 16;
+        offb[v] = B_KC ? (unsigned)(64 * v + (tid >> 2)) * (unsigned)K + (tid & 3) * 16 : (unsigned)(4 * (tid >> 4) + v) * (unsigned)N + (tid & 15) * 16;
+    }
+    const uint8_t* tile_a = A + (A_KC ? m0 * K : m0);
+    const uint8_t* tile_b = B + (B_KC ? n0 * K : n0);
     auto fetch_inside = [&](u32x4 (&xa)[WNV], u32x4 (&xb)[WNV], int64_t stage) __attribute__((always_inline)) {
-        int64_t count;
+        const uint8_t* sa = tile_a + stage * FK * (A_KC ? 1 : M);
+        const uint8_t* sb = tile_b + stage * FK * (B_KC ? 1 : N);
 #pragma unroll
         for (int v = 0; v < WNV; ++v) {
-            __builtin_memcpy(&xa[v], piece_wide<A_KC>(A, M, K, m0, stage * FK, tid, v, count), 16);
-            __builtin_memcpy(&xb[v], piece_wide<B_KC>(B, N, K, n0, stage * FK, tid, v, count), 16);
+            __builtin_memcpy(&xa[v], sa + offa[v], 16);
+            __builtin_memcpy(&xb[v], sb + offb[v], 16);
         }
     };
-    // lane (r, h): fragments of the K indices 16 s .. 16 s + 15 of the stage in half `parity`
+    // lane (r, h): fragments of the K indices 16 s .. 16 s + 15 of the stage in half `parity`.  Block i
+    // of the wave is row r0 + 32 i of the image, chunk c = 2 h + (s & 1) + 4 (s >> 1) at position
+    // c ^ swz(row).  Adding 32 i to the row flips swz by 2 i, and c is 2 h with constant bits flipped, so
+    // an address is one value per lane with three bits flipped by a constant, plus a constant: two
+    // registers hold what would otherwise be an address per block and sub-step.
+    const unsigned lane_a = (unsigned)((wm * 128 + r) * FPITCH) + (unsigned)(((2 * h) ^ swz(wm * 128 + r)) << 4);
+    const unsigned lane_b = (unsigned)((wn * 128 + r) * FPITCH) + (unsigned)(((2 * h) ^ swz(wn * 128 + r)) << 4) + W_IMG;
     auto read_frags = [&](int parity, int s, v8h (&af)[4], v8h (&bf)[4]) __attribute__((always_inline)) {
-        const uint8_t* As = lds + parity * 2 * W_IMG;
-        const uint8_t* Bs = As + W_IMG;
-        const int c = 2 * h + (s & 1) + 4 * (s >> 1);
+        const int cs = (s & 1) + 4 * (s >> 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ra_ = wm * 128 + i * 32 + r, rb_ = wn * 128 + i * 32 + r;
-            af[i] = *LDS_PTR(v8h, As + ra_ * FPITCH + ((c ^ swz(ra_)) * 16));
-            bf[i] = *LDS_PTR(v8h, Bs + rb_ * FPITCH + ((c ^ swz(rb_)) * 16));
+            const unsigned flip = (unsigned)(((cs ^ (2 * i)) & 7) << 4), add = (unsigned)(i * 32 * FPITCH + parity * 2 * W_IMG);
+            af[i] = *LDS_PTR(v8h, lds + ((lane_a ^ flip) + add));
+            bf[i] = *LDS_PTR(v8h, lds + ((lane_b ^ flip) + add));
         }
     };
-    // One stage: the products of the stage in half `parity`, in four K sub-steps; the fragments of a
-    // sub-step are read during the one before it.  STORE: meanwhile (xa, xb), the bytes of the next
-    // stage, go into the other half, a quarter per sub-step, so that the widening and the LDS writes
-    // are issued between the matrix instructions and not after them.
+    // One stage: the products of the stage in half `parity`, in four K sub-steps.  On entry fa[0],
+    // fb[0] hold the fragments of sub-step 0; the fragments of a sub-step are read during the one
+    // before it.  STORE: meanwhile (xa, xb), the bytes of the next stage, go into the other half
+    // during the first three sub-steps, in eight pieces, so that the widening and the LDS writes are issued between
+    // the matrix instructions and not after them.  The stage's barrier stands before the last
+    // sub-step: by then this wave has read all its fragments of this half and written its share of
+    // the other half, and after it the fragments of the next stage's sub-step 0 are read from the
+    // other half during the last sub-step's products (behind the last stage they are read for nothing).
+    // Since every wave's reads of a half precede the barrier of that stage, the writes into it, which
+    // belong to the stage after, follow that barrier.
+    v8h fa[2][4], fb[2][4];
     auto stage = [&](auto store_tag, int parity, const u32x4 (&xa)[WNV], const u32x4 (&xb)[WNV]) __attribute__((always_inline)) {
         constexpr bool STORE = decltype(store_tag)::value;
+        constexpr int STEPS = FK / 16;
         uint8_t* other = lds + (parity ^ 1) * 2 * W_IMG;
-        v8h af[2][4], bf[2][4];
-        read_frags(parity, 0, af[0], bf[0]);
-#pragma unroll
-        for (int s = 0; s < FK / 16; ++s) {
-            if (s + 1 < FK / 16) read_frags(parity, s + 1, af[(s + 1) & 1], bf[(s + 1) & 1]);
+        // sub-step S with the pieces FIRST .. LAST - 1 of the store
+        auto substep = [&](auto s_c, auto first_c, auto last_c) __attribute__((always_inline)) {
+            constexpr int S = decltype(s_c)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+            constexpr int PIECES = STORE ? LAST - FIRST : 0;
+            if (S == STEPS - 1) __syncthreads();
+            if (S + 1 < STEPS) read_frags(parity, S + 1, fa[(S + 1) & 1], fb[(S + 1) & 1]);
+            else read_frags(parity ^ 1, 0, fa[0], fb[0]);
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bf[s & 1][nb], af[s & 1][mb], acc[nb][mb], 0, 0, 0);
+                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[S & 1][nb], fa[S & 1][mb], acc[nb][mb], 0, 0, 0);
             if (STORE) {
-                store_wide_part<FMT_A, A_KC>(other, xa, tid, s);
-                store_wide_part<FMT_B, B_KC>(other + W_IMG, xb, tid, s);
-            }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one matrix instruction,
-                if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // one fragment read of the next sub-step,
-                if (STORE) {
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                // two vector instructions of the store
-                    if (i >= 4 && (i & 1)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // and its LDS writes behind them
+                for (int q = FIRST; q < LAST; ++q) {
+                    store_wide_piece<FMT_A, A_KC>(other, xa, tid, q);
+                    store_wide_piece<FMT_B, B_KC>(other + W_IMG, xb, tid, q);
                 }
             }
+            // Order asked of the scheduler: after every matrix instruction a few of the sub-step's other
+            // instructions (fragment reads, widening, LDS writes, loads), of whatever kind is ready.
+            // (Asked for kind by kind, the order fell apart wherever an instruction of the kind asked
+            // for was not ready, and most of a sub-step's vector work ended up behind one matrix
+            // instruction.)
+            constexpr int OTHERS = PIECES == 3 ? 4 : PIECES == 2 ? 3 : 2;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002 | 0x020 | 0x100 | 0x200, OTHERS, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);        // nothing drifts into another sub-step (register pressure)
-        }
+        };
+        using std::integral_constant;
+        substep(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 3>{});
+        substep(integral_constant<int, 1>{}, integral_constant<int, 3>{}, integral_constant<int, 6>{});
+        substep(integral_constant<int, 2>{}, integral_constant<int, 6>{}, integral_constant<int, 8>{});
+        substep(integral_constant<int, 3>{}, integral_constant<int, 8>{}, integral_constant<int, 8>{});
     };
 
     u32x4 a0[WNV], b0[WNV], a1[WNV], b1[WNV];         // register set 0: even stages, set 1: odd stages
     fetch(a0, b0, 0);
     if (stages > 1) fetch(a1, b1, 1);
 #pragma unroll
-    for (int d = 0; d < WNV; ++d) {
-        store_wide_part<FMT_A, A_KC>(lds, a0, tid, d);
-        store_wide_part<FMT_B, B_KC>(lds + W_IMG, b0, tid, d);
+    for (int q = 0; q < 2 * WNV; ++q) {
+        store_wide_piece<FMT_A, A_KC>(lds, a0, tid, q);
+        store_wide_piece<FMT_B, B_KC>(lds + W_IMG, b0, tid, q);
     }
     __syncthreads();
+    read_frags(0, 0, fa[0], fb[0]);
     // Two stages per trip; an odd last stage follows the loop.  (With the loop left from the middle
     // of a trip, or with a choice between two forms of a stage inside it, the compiler spilled a
     // thousand registers per lane.)  Every condition is the same for the whole workgroup.
@@ -457,19 +494,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_wide_kernel(
     for (; st + 3 < inside; st += 2) {
         fetch_inside(a0, b0, st + 2);
         stage(std::true_type{}, 0, a1, b1);
-        __syncthreads();
         fetch_inside(a1, b1, st + 3);
         stage(std::true_type{}, 1, a0, b0);
-        __syncthreads();
     }
     // the other trips: edge tiles, and the end of K
     for (; st + 2 <= stages; st += 2) {
         if (st + 2 < stages) fetch(a0, b0, st + 2);
         stage(std::true_type{}, 0, a1, b1);
-        __syncthreads();
         if (st + 3 < stages) fetch(a1, b1, st + 3);
         stage(std::true_type{}, 1, a0, b0);           // after the last stage: old bytes into a half nobody reads again
-        __syncthreads();
     }
     if (st < stages) stage(std::false_type{}, 0, a0, b0);
 
@@ -521,9 +554,11 @@ bool mfma_any_takes(const GemmArgs& g)
 bool mfma_any_wide(const GemmArgs& g)
 {
     const int forced = knob(FP8_KNOB_TILE_N);
-    if (forced) return forced == 256;
     const int64_t tiles = tile_count(g, WT), units = 256;
     const int64_t rounds = (tiles + units - 1) / units;
+    // 32-bit offsets within a tile's stage: 255 rows of K bytes, or 63 K-rows of M / N bytes
+    if (g.K >= (1 << 24) || g.M >= (1 << 26) || g.N >= (1 << 26)) return false;
+    if (forced) return forced == 256;
     return g.K >= 8 * FK && 5 * tiles >= 4 * rounds * units;
 }
 
