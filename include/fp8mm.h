@@ -244,7 +244,7 @@ int fp8_quantize_transpose(const void* x, int64_t rows, int64_t cols, int in_dty
  * given as K x M (see fp8_gemm_ex); with B given as N x K any N goes.  A C that is not
  * 16-byte aligned, or whose rows are not (N not a multiple of 16), is stored element by
  * element.  The other shapes and alignments take a second matrix-core kernel (register-staged
- * loads, 128 x 128 tiles, the same arithmetic and bound, about half the rate; see
+ * loads, 256 x 256 or 128 x 128 tiles, the same arithmetic and bound, 0.5 - 0.8 of the rate; see
  * fp8_gemm_plan).  fp8_gemm_dscale reads the two scales from device memory instead.
  */
 int fp8_gemm(const uint8_t* A, int fmtA, float sA,
@@ -380,8 +380,8 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * first columns of the output, 128-wide ones for the rest, where that fills the rounds of workgroups
  * better than either width alone),
  * FP8_PLAN_MFMA_ANY (the matrix-core kernel for every other shape and alignment: an odd K, operand
- * rows that do not start on 16-byte boundaries, unaligned pointers; about half of the tiled
- * kernel's rate, fifteen times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
+ * rows that do not start on 16-byte boundaries, unaligned pointers; 0.5 - 0.8 of the tiled
+ * kernel's rate, fifteen to twenty-five times that of plain FMAs; it computes in the default accumulation mode also under FP8_GEMM_MFMA8, which
  * meets that flag's bound a fortiori) or FP8_PLAN_FMA_KERNEL (plain FMAs: only when forced by
  * FP8_KNOB_GEMM_KERNEL or for outputs of more than 2^31 - 1 tiles of 128 x 128), ORed with
  * FP8_PLAN_ELEMENTWISE_STORES where the rows of the output do not start on 16-byte boundaries, and
@@ -407,7 +407,8 @@ int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, co
  *   FP8_KNOB_CAST_PATH    0 the FP8 conversion instructions of gfx950 (default), 1 the integer
  *                         rounding written from Table 1 (FP8MM_CAST_PATH=bits); both are bit-equal
  *   FP8_KNOB_TILE_N       0 the dispatcher chooses, 128 or 256 forces the tile width of the
- *                         matrix-core kernel (FP8MM_TILE_N)
+ *                         tiled kernel and the form of the any-shape matrix-core kernel
+ *                         (128 x 128 / 256 x 256 tiles) (FP8MM_TILE_N)
  *   FP8_KNOB_GROUP_M      tile rows per band of the tile order, 0 = default 8 (FP8MM_GROUP_M)
  *   FP8_KNOB_GEMM_KERNEL  0 the dispatcher chooses, 1 always the plain FMA kernel (FP8MM_GEMM=generic),
  *                         2 always the any-shape matrix-core kernel (FP8MM_GEMM=any)
