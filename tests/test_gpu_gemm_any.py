@@ -129,6 +129,29 @@ def test_vocabulary_sized_weight_stored_in_by_out(form):
         bound_check(C[torch.from_numpy(rows).cuda()], S, T, 4.0, 2.0, out_dtype, "N = 5027, out %d" % out_dtype)
 
 
+def test_many_tiles_dispatchers_own_choice_of_form():
+    """256 tiles of 256 x 256 with an odd N and K = 520 (eight whole stages and a ragged ninth): the
+    dispatcher takes the wide form by itself (no knob set); sampled rows against the oracle, and
+    the other form must give the same bits (same products, same order of accumulation)."""
+    rng = np.random.default_rng(2024)
+    M, N, K = 4096, 4081, 520
+    A, B = random_codes(rng, (M, K), E5M2, 0x5F), random_codes(rng, (K, N), E4M3, 0x5F)
+    rows = np.sort(rng.choice(M, 16, replace=False))
+    S, T = oracle.gemm_rows(A, E5M2, B, E4M3, rows)
+    dA, dB = to_dev(A), to_dev(B)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    assert fp8.fp8_get_knob(fp8.FP8_KNOB_TILE_N) == 0
+    assert fp8.fp8_gemm_plan(dA, 0, dB, 0, C) == ANY
+    fp8.fp8_gemm_ex(dA, E5M2, 0, dB, E4M3, 0, C, 8.0, 0.5)
+    torch.cuda.synchronize()
+    bound_check(C[torch.from_numpy(rows).cuda()], S, T, 8.0, 0.5, fp8.FP8_F32, "4096 x 4081 x 520")
+    C2 = torch.empty_like(C)
+    with knob(fp8.FP8_KNOB_TILE_N, 128):
+        fp8.fp8_gemm_ex(dA, E5M2, 0, dB, E4M3, 0, C2, 8.0, 0.5)
+    torch.cuda.synchronize()
+    assert torch.equal(C, C2)
+
+
 def test_special_values_and_zero_padding(form):
     """NaN and infinity in the operands propagate as IEEE arithmetic says, also next to the zero
     padding of a ragged K and ragged tile edges: the padding must not turn an infinity into NaN."""
