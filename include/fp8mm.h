@@ -371,6 +371,30 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
                    const float* sD_dev, float* amax_out, int flags, void* stream);
 
 /*
+ * fp8_scaled_gemm -- the whole of Section 2's scheme for one product in ONE call: per-tensor amax and
+ * factor of both operands (fmt_max / amax), their casts to FP8, the FP8 x FP8 product with
+ * single-precision accumulation, and the factors taken out once per output.  It issues exactly the
+ * launches of fp8_amax_scale_multi, fp8_quantize_multi and fp8_gemm_ex (factors read from scale_out)
+ * in that order on `stream`, so every result is theirs bit for bit; what it saves is the host time
+ * between three short dependent launches (4096 x 6144 x 2048: 0.147 -> 0.142 ms per step; replaying
+ * the three launches from a captured HIP graph, which a caller can do with either form, gives 0.118).
+ *   a, b        the operands in the wide type in_dtype, stored as fp8_gemm_ex stores A and B
+ *               (a: M x K, or K x M if transA; b: K x N, or N x K if transB); alignment as for fp8_amax
+ *   fmtA, fmtB  FP8 formats the operands are cast to
+ *   qa_out, qb_out  M K and K N bytes: the FP8 operands, in the storage order of a and b (kept for
+ *               the backward products)
+ *   amax_out, scale_out  2 floats each: [0] for a, [1] for b
+ *   workspace   2 * FP8_AMAX_WORKSPACE_BYTES bytes, rules as for fp8_amax_scale
+ *   C, out_dtype, flags  as for fp8_gemm_ex
+ * Errors: FP8_ERR_INVALID_ARG (bad enum or flag bits, negative dimension, NULL or misaligned
+ * pointer), decided before anything is launched.
+ */
+int fp8_scaled_gemm(const void* a, const void* b, int in_dtype, int transA, int transB,
+                    int64_t M, int64_t N, int64_t K, int fmtA, int fmtB,
+                    uint8_t* qa_out, uint8_t* qb_out, float* amax_out, float* scale_out, void* workspace,
+                    void* C, int out_dtype, int flags, void* stream);
+
+/*
  * Which kernel the GEMM entry points would run for a problem (diagnostics; nothing is launched and
  * no pointer is dereferenced: only shapes, storage orders and pointer alignment decide).  Pass the
  * pointers of the intended call; sB_per_column is the per-column factor vector of fp8_gemm_fused or

@@ -29,7 +29,7 @@ EXPORTS = (
     "fp8_quantize_dscale", "fp8_quantize_ex", "fp8_dequantize", "fp8_quantize_amax", "fp8_quantize_sr",
     "fp8_scale_from_amax_history", "fp8_scale_from_amax_n", "fp8_amax_rows", "fp8_quantize_rows",
     "fp8_quantize_transpose", "fp8_gemm", "fp8_gemm_dscale", "fp8_gemm_mfma8",
-    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_splitk", "fp8_gemm_splitk_workspace_size", "fp8_gemm_splitk_static", "fp8_gemm_fused", "fp8_gemm_plan", "fp8_set_knob", "fp8_get_knob",
+    "fp8_gemm_mfma8_dscale", "fp8_gemm_ex", "fp8_gemm_splitk", "fp8_gemm_splitk_workspace_size", "fp8_gemm_splitk_static", "fp8_gemm_fused", "fp8_scaled_gemm", "fp8_gemm_plan", "fp8_set_knob", "fp8_get_knob",
     "fp8_last_error", "fp8_version",
 )
 
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
     L.fp8_gemm_mfma8.argtypes, L.fp8_gemm_mfma8.restype = L.fp8_gemm.argtypes, i
     L.fp8_gemm_mfma8_dscale.argtypes, L.fp8_gemm_mfma8_dscale.restype = L.fp8_gemm_dscale.argtypes, i
     L.fp8_gemm_ex.argtypes, L.fp8_gemm_ex.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, vp], i
+    L.fp8_scaled_gemm.argtypes, L.fp8_scaled_gemm.restype = [vp, vp, i, i, i, i64, i64, i64, i, i, vp, vp, vp, vp, vp, vp, i, i, vp], i
     L.fp8_gemm_splitk.argtypes, L.fp8_gemm_splitk.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, i, vp, sz, vp], i
     L.fp8_gemm_splitk_static.argtypes, L.fp8_gemm_splitk_static.restype = [vp, i, i, vp, i, i, vp, i64, i64, i64, i, f, f, vp, vp, i, i, vp], i
     L.fp8_gemm_splitk_workspace_size.argtypes, L.fp8_gemm_splitk_workspace_size.restype = [i64, i64, i64, i, i, i], sz
@@ -301,6 +302,30 @@ def fp8_gemm_ex(A, fmtA: int, transA: bool, B, fmtB: int, transB: bool, C, sA, s
                              0.0 if dev else float(sA), 0.0 if dev else float(sB),
                              _dev(sA, "sA") if dev else None, _dev(sB, "sB") if dev else None,
                              int(flags), _stream(stream)))
+
+
+def fp8_scaled_gemm(a, fmtA: int, transA: bool, b, fmtB: int, transB: bool, qa_out, qb_out, amax_out, scale_out,
+                    workspace, C, flags: int = 0, stream=None) -> None:
+    """amax + scale + cast of both operands and their FP8 product in one call.  a is [M, K] (or
+    [K, M] if transA), b is [K, N] (or [N, K] if transB), both bf16 or both fp32; qa_out / qb_out are
+    uint8 tensors of the operands' shapes; amax_out and scale_out hold two floats ([0]: a, [1]: b);
+    workspace: 2 * FP8_AMAX_WORKSPACE_BYTES bytes, zero-filled once."""
+    if a.dim() != 2 or b.dim() != 2 or a.dtype != b.dtype:
+        raise ValueError("a and b must be 2-D tensors of one element type")
+    M, K = (a.shape[1], a.shape[0]) if transA else a.shape
+    N, K2 = (b.shape[0], b.shape[1]) if transB else (b.shape[1], b.shape[0])
+    if K != K2 or tuple(C.shape) != (M, N):
+        raise ValueError("shapes do not form C[M,N] = op(a)[M,K] op(b)[K,N]")
+    for q, x in ((qa_out, a), (qb_out, b)):
+        if q.dtype != torch.uint8 or tuple(q.shape) != tuple(x.shape):
+            raise ValueError("qa_out / qb_out must be uint8 tensors of the operands' shapes")
+    if workspace.numel() * workspace.element_size() < 2 * FP8_AMAX_WORKSPACE_BYTES:
+        raise ValueError("workspace must hold 2 * FP8_AMAX_WORKSPACE_BYTES bytes")
+    _check(lib().fp8_scaled_gemm(_dev(a, "a") if a.numel() else None, _dev(b, "b") if b.numel() else None, dtype_code(a),
+                                 int(bool(transA)), int(bool(transB)), M, N, K, fmtA, fmtB,
+                                 _dev(qa_out, "qa_out") if qa_out.numel() else None, _dev(qb_out, "qb_out") if qb_out.numel() else None,
+                                 _f32_cells(amax_out, "amax_out", 2), _f32_cells(scale_out, "scale_out", 2), _dev(workspace, "workspace"),
+                                 _dev(C, "C") if C.numel() else None, dtype_code(C), int(flags), _stream(stream)))
 
 
 def _gemm_ex_dims(A, transA, B, transB, C):

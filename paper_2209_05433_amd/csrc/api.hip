@@ -452,6 +452,34 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
     return launch_gemm(g);
 }
 
+int fp8_scaled_gemm(const void* a, const void* b, int in_dtype, int transA, int transB,
+                    int64_t M, int64_t N, int64_t K, int fmtA, int fmtB,
+                    uint8_t* qa_out, uint8_t* qb_out, float* amax_out, float* scale_out, void* workspace,
+                    void* C, int out_dtype, int flags, void* stream)
+{
+    const char* who = "fp8_scaled_gemm";
+    // every check of the three steps first: nothing is launched unless all of them can be
+    GemmArgs g{};
+    if (int e = fill_gemm_args(who, g, qa_out, fmtA, transA, qb_out, fmtB, transB, C, M, N, K, out_dtype, 1.0f, 1.0f,
+                               scale_out, scale_out ? scale_out + 1 : nullptr, flags, stream))
+        return e;
+    if (!valid_dtype(in_dtype)) return fail(FP8_ERR_INVALID_ARG, "%s: in_dtype %d is not an fp8_dtype_t", who, in_dtype);
+    if (!amax_out || !scale_out || !workspace) return fail(FP8_ERR_INVALID_ARG, "%s: amax_out, scale_out or workspace is NULL", who);
+    if (((uintptr_t)amax_out | (uintptr_t)scale_out | (uintptr_t)workspace) % 4)
+        return fail(FP8_ERR_INVALID_ARG, "%s: amax_out, scale_out and workspace must be 4-byte aligned", who);
+    const void* x[2] = {a, b};
+    const size_t n[2] = {(size_t)M * (size_t)K, (size_t)K * (size_t)N};
+    const int fmt[2] = {fmtA, fmtB};
+    uint8_t* q[2] = {qa_out, qb_out};
+    for (int i = 0; i < 2; ++i) {
+        if (n[i] > 0 && (!x[i] || !q[i])) return fail(FP8_ERR_INVALID_ARG, "%s: NULL operand or FP8 output %d with %zu elements", who, i, n[i]);
+        if ((uintptr_t)x[i] % (in_dtype == FP8_F32 ? 4 : 2)) return fail(FP8_ERR_INVALID_ARG, "%s: operand %d is not aligned to its element size", who, i);
+    }
+    if (int e = launch_amax_scale_multi(2, x, n, in_dtype, fmt, amax_out, scale_out, workspace, (hipStream_t)stream)) return e;
+    if (int e = launch_quantize_multi(2, x, n, in_dtype, fmt, scale_out, q, (hipStream_t)stream)) return e;
+    return launch_gemm(g);
+}
+
 int fp8_gemm_plan(const uint8_t* A, int transA, const uint8_t* B, int transB, const void* C,
                   int64_t M, int64_t N, int64_t K, const float* sB_per_column)
 {

@@ -82,6 +82,21 @@ int main(void)
         EXPECT(fp8_quantize_multi(0, NULL, NULL, FP8_BF16, NULL, NULL, NULL, NULL), FP8_OK);
     }
 
+    /* the whole scheme in one call: every check precedes the first launch */
+    EXPECT(fp8_scaled_gemm(X, X, 2, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 2, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, -4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, 5, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(NULL, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, Xodd, FP8_F32, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, NULL, B, F, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, NULL, F + 8, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, NULL, F + 64, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, NULL, C, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, NULL, FP8_F32, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, 3, 0, NULL), BAD);
+    EXPECT(fp8_scaled_gemm(X, X, FP8_BF16, 0, 0, 4, 4, 4, FP8_E4M3, FP8_E4M3, A, B, F, F + 8, F + 64, C, FP8_F32, 8, NULL), BAD);
+
     /* casts */
     EXPECT(fp8_quantize(X, 0, FP8_BF16, FP8_E4M3, 1.0f, A, NULL), FP8_OK);          /* empty: nothing to launch */
     EXPECT(fp8_quantize(NULL, 0, FP8_F32, FP8_E5M2, 1.0f, NULL, NULL), FP8_OK);

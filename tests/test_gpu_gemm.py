@@ -217,6 +217,46 @@ def test_config1_whole_path_full_check():
     check(out_to_f64(C), S, T, sA, sB, fp8.FP8_F32, "config 1")
 
 
+def test_config1_whole_path_in_one_call():
+    """fp8_scaled_gemm on config 1 (fp32 inputs) against the oracle's whole path, and on a bf16
+    problem with the operands in the other storage orders against the separate calls, bit for bit."""
+    A, B = synth.config1()
+    dA, dB = to_dev(A), to_dev(B)
+    amax, scale = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
+    ws = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    qA = torch.empty(A.shape, dtype=torch.uint8, device="cuda")
+    qB = torch.empty(B.shape, dtype=torch.uint8, device="cuda")
+    C = torch.empty((256, 256), dtype=torch.float32, device="cuda")
+    for _ in range(2):                               # the second call finds the workspace as the first left it
+        fp8.fp8_scaled_gemm(dA, E4M3, False, dB, E4M3, False, qA, qB, amax, scale, ws, C)
+    torch.cuda.synchronize()
+    Aq, sA, Bq, sB = quantize_pair(A, B, E4M3, E4M3)
+    assert np.array_equal(qA.cpu().numpy(), Aq) and np.array_equal(qB.cpu().numpy(), Bq)
+    assert np.float32(scale[0].item()) == sA and np.float32(scale[1].item()) == sB
+    assert float(amax[0].item()) == float(np.max(np.abs(A))) and float(amax[1].item()) == float(np.max(np.abs(B)))
+    S, T = oracle.gemm_rows(Aq, E4M3, Bq, E4M3)
+    check(out_to_f64(C), S, T, sA, sB, fp8.FP8_F32, "config 1, one call")
+
+    g = torch.Generator(device="cuda").manual_seed(9)
+    M, N, K = 384, 640, 512
+    a = torch.randn((K, M), device="cuda", generator=g).to(torch.bfloat16)          # stored K x M
+    b = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16)  # stored N x K
+    qa, qb = torch.empty((K, M), dtype=torch.uint8, device="cuda"), torch.empty((N, K), dtype=torch.uint8, device="cuda")
+    c1 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    fp8.fp8_scaled_gemm(a, E5M2, True, b, E4M3, True, qa, qb, amax, scale, ws, c1, fp8.FP8_GEMM_MFMA8)
+    amax2, scale2 = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
+    ws2 = torch.zeros_like(ws)
+    qa2, qb2, c2 = torch.empty_like(qa), torch.empty_like(qb), torch.empty_like(c1)
+    fp8.fp8_amax_scale_multi((a, b), (E5M2, E4M3), amax2, scale2, ws2)
+    fp8.fp8_quantize_multi((a, b), (E5M2, E4M3), scale2, (qa2, qb2))
+    fp8.fp8_gemm_ex(qa2, E5M2, True, qb2, E4M3, True, c2, scale2[0:1], scale2[1:2], fp8.FP8_GEMM_MFMA8)
+    torch.cuda.synchronize()
+    assert torch.equal(amax, amax2) and torch.equal(scale, scale2)
+    assert torch.equal(qa, qa2) and torch.equal(qb, qb2) and torch.equal(c1.view(torch.int16), c2.view(torch.int16))
+    with pytest.raises(fp8.Fp8Error):
+        fp8.fp8_scaled_gemm(a, E5M2, True, b, 7, True, qa, qb, amax, scale, ws, c1)
+
+
 def sample_points(rng, M, N, npts, tile=256):
     """Corners of the matrix, one point in every 256 x 256 tile (up to a cap), random extras."""
     pts = {(0, 0), (0, N - 1), (M - 1, 0), (M - 1, N - 1)}
