@@ -35,6 +35,9 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
     ws_multi = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
     amax2, scale2 = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
     q2A, q2B = torch.empty_like(qA), torch.empty_like(qB)
+    ws_one = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    amax3, scale3 = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
+    q3A, q3B, C3 = torch.empty_like(qA), torch.empty_like(qB), torch.empty_like(C)
 
     def step():
         fp8.fp8_amax(dA, amax[0:1])
@@ -51,6 +54,7 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         fp8.fp8_gemm_splitk_static(qAt, E4M3, 0, D, E5M2, 0, W3, 1.0, 1.0, 0, 2)     # ... with the library's own scratch array
         fp8.fp8_amax_scale_multi((dA, dB), (E4M3, E5M2), amax2, scale2, ws_multi)     # both operands per launch
         fp8.fp8_quantize_multi((dA, dB), (E4M3, E5M2), scale2, (q2A, q2B))
+        fp8.fp8_scaled_gemm(dA, E4M3, False, dB, E5M2, False, q3A, q3B, amax3, scale3, ws_one, C3)     # the whole path in one call
 
     def load(seed):
         a, b = synth.config3(M, N, K)
@@ -63,7 +67,7 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W, W2, W3, amax2, scale2, q2A, q2B)]
+        return [t.clone() for t in (amax, scale, hist, qA, qAt, qB, C, D, W, W2, W3, amax2, scale2, q2A, q2B, amax3, scale3, q3A, q3B, C3)]
 
     load(0)
     hist.zero_()
@@ -83,13 +87,14 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
         hist.fill_(0.25 * (trial + 1))
         for t in (qA, qAt, qB, C, D):
             t.zero_()
-        for t in (W, W2, W3, q2A, q2B, scale2):
+        for t in (W, W2, W3, q2A, q2B, scale2, q3A, q3B, C3, scale3):
             t.zero_()
+        amax3.fill_(-1.0)
         amax.fill_(-1.0)
         amax2.fill_(-1.0)
         graph.replay()
         replayed = snapshot()
-        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W W2 W3 amax2 scale2 q2A q2B".split()):
+        for e, r, name in zip(eager, replayed, "amax scale hist qA qAt qB C D W W2 W3 amax2 scale2 q2A q2B amax3 scale3 q3A q3B C3".split()):
             assert torch.equal(e.view(torch.uint8), r.view(torch.uint8)), "replay %d differs from eager in %s" % (trial, name)
         if trial == 0:                       # and eager is what the oracle says
             sA = oracle.scale_from_amax(oracle.amax(a_bits), oracle.E4M3)
@@ -105,3 +110,8 @@ def test_path_replayed_from_a_graph_matches_eager_and_oracle():
             assert np.float32(eager[1][2].item()) == oracle.scale_from_amax(oracle.amax(b_bits), oracle.E5M2)
             assert np.array_equal(eager[13].cpu().numpy(), Aq)              # the multi-tensor calls: A as above, B to E5M2
             assert np.array_equal(eager[14].cpu().numpy(), oracle.quantize(b_bits, oracle.E5M2, np.float32(eager[1][2].item())))
+            assert torch.equal(eager[15], eager[11]) and torch.equal(eager[16], eager[12])      # one call = the multi calls
+            assert torch.equal(eager[17], eager[13]) and torch.equal(eager[18], eager[14])
+            S3, T3 = oracle.gemm_rows(Aq, oracle.E4M3, eager[14].cpu().numpy(), oracle.E5M2)
+            c3_ref, bound3 = oracle.gemm_bound(S3, T3, np.float32(eager[12][0].item()), np.float32(eager[12][1].item()), oracle.BF16)
+            assert np.all(np.abs(out_to_f64(eager[19]) - c3_ref) <= bound3)
