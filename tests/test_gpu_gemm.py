@@ -167,6 +167,21 @@ def test_empty_and_zero_k():
     assert torch.count_nonzero(C).item() == 0
     C = run_gemm(np.zeros((0, 8), dtype=np.uint8), E4M3, 1.0, np.zeros((8, 4), dtype=np.uint8), E4M3, 1.0, fp8.FP8_F32)
     assert C.numel() == 0
+    # the one-call form on the same degenerate shapes: K = 0 gives amax 0, scale 1 and a zero product
+    amax, scale = torch.full((2,), -1.0, device="cuda"), torch.zeros(2, device="cuda")
+    ws = torch.zeros(2 * fp8.FP8_AMAX_WORKSPACE_BYTES // 4, dtype=torch.int32, device="cuda")
+    a, b = torch.empty((16, 0), dtype=torch.bfloat16, device="cuda"), torch.empty((0, 32), dtype=torch.bfloat16, device="cuda")
+    C = torch.full((16, 32), 5.0, dtype=torch.float32, device="cuda")
+    fp8.fp8_scaled_gemm(a, E4M3, False, b, E5M2, False, torch.empty((16, 0), dtype=torch.uint8, device="cuda"),
+                        torch.empty((0, 32), dtype=torch.uint8, device="cuda"), amax, scale, ws, C)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(C).item() == 0 and amax.tolist() == [0.0, 0.0] and scale.tolist() == [1.0, 1.0]
+    a = torch.ones((0, 8), dtype=torch.float32, device="cuda"); b = torch.full((8, 4), -3.0, dtype=torch.float32, device="cuda")
+    qb = torch.empty((8, 4), dtype=torch.uint8, device="cuda")
+    fp8.fp8_scaled_gemm(a, E4M3, False, b, E4M3, False, torch.empty((0, 8), dtype=torch.uint8, device="cuda"), qb, amax, scale, ws,
+                        torch.empty((0, 4), dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    assert amax.tolist() == [0.0, 3.0] and bool((qb == 0xFE).all())          # -3 * (448 / 3) = -448
 
 
 @pytest.mark.parametrize("mode", MODES)
