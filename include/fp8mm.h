@@ -376,8 +376,9 @@ int fp8_gemm_fused(const uint8_t* A, int fmtA, int transA, const uint8_t* B, int
  * single-precision accumulation, and the factors taken out once per output.  It issues exactly the
  * launches of fp8_amax_scale_multi, fp8_quantize_multi and fp8_gemm_ex (factors read from scale_out)
  * in that order on `stream`, so every result is theirs bit for bit; what it saves is the host time
- * between three short dependent launches (4096 x 6144 x 2048: 0.147 -> 0.142 ms per step; replaying
- * the three launches from a captured HIP graph, which a caller can do with either form, gives 0.118).
+ * between three short dependent launches (4096 x 6144 x 2048: 0.147 - 0.155 -> 0.128 - 0.142 ms per step
+ * over hosts; replaying the launches from a captured HIP graph, which a caller can do with either
+ * form, gives 0.118).
  *   a, b        the operands in the wide type in_dtype, stored as fp8_gemm_ex stores A and B
  *               (a: M x K, or K x M if transA; b: K x N, or N x K if transB); alignment as for fp8_amax
  *   fmtA, fmtB  FP8 formats the operands are cast to
