@@ -271,12 +271,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_kernel(
 // half the LDS reads per product of the 2 x 2 form), one workgroup per compute unit, so nobody
 // hides a workgroup's waits but itself:
 //   - the LDS holds two stages of both images (128 KB); stage s is multiplied out of one half
-//     while stage s + 1 is written into the other, one barrier per stage;
-//   - two register sets: the bytes of stage s + 2 are requested before stage s is multiplied and
-//     are widened and written to LDS a stage later, between the two halves of stage s + 1's products;
+//     while stage s + 1 is written into the other;
+//   - two register sets: the bytes of stage s + 2 are requested before stage s is multiplied; a
+//     stage later they are widened and written to LDS in eight pieces, issued between the matrix
+//     instructions of the first three of that stage's four K sub-steps;
+//   - one barrier per stage, before its last K sub-step, during which the first fragments of the
+//     next stage are already read (see the kernel);
 //   - an operand that is contiguous along M / N is fetched as 4 consecutive K rows x 16 tile rows per
 //     thread and turned round in registers (byte permutes), so that the image gets 8-byte writes
-//     (4 halves along K) instead of 2-byte ones.
+//     (4 halves along K) instead of 2-byte ones;
+//   - stages that lie inside K, of tiles that lie inside C, run a loop without a single test.
 constexpr int WT = 256;                         // tile edge
 constexpr int WNV = WT * FK / 16 / 256;         // 16-byte vectors per thread, operand and stage: 4
 constexpr int W_IMG = WT * FPITCH;              // one operand, one stage: 32 KB
@@ -423,8 +427,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_wide_kernel(
     // One stage: the products of the stage in half `parity`, in four K sub-steps.  On entry fa[0],
     // fb[0] hold the fragments of sub-step 0; the fragments of a sub-step are read during the one
     // before it.  STORE: meanwhile (xa, xb), the bytes of the next stage, go into the other half
-    // during the first three sub-steps, in eight pieces, so that the widening and the LDS writes are issued between
-    // the matrix instructions and not after them.  The stage's barrier stands before the last
+    // during the first three sub-steps, in eight pieces, so that the widening and the LDS writes
+    // are issued between the matrix instructions and not after them.  The stage's barrier stands
+    // before the last
     // sub-step: by then this wave has read all its fragments of this half and written its share of
     // the other half, and after it the fragments of the next stage's sub-step 0 are read from the
     // other half during the last sub-step's products (behind the last stage they are read for nothing).
