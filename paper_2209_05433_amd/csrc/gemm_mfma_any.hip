@@ -429,10 +429,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_any_wide_kernel(
     // before it.  STORE: meanwhile (xa, xb), the bytes of the next stage, go into the other half
     // during the first three sub-steps, in eight pieces, so that the widening and the LDS writes
     // are issued between the matrix instructions and not after them.  The stage's barrier stands
-    // before the last
-    // sub-step: by then this wave has read all its fragments of this half and written its share of
-    // the other half, and after it the fragments of the next stage's sub-step 0 are read from the
-    // other half during the last sub-step's products (behind the last stage they are read for nothing).
+    // before the last sub-step: by then this wave has read all its fragments of this half and
+    // written its share of the other half, and after it the fragments of the next stage's sub-step
+    // 0 are read from the other half during the last sub-step's products (behind the last stage
+    // they are read for nothing).
     // Since every wave's reads of a half precede the barrier of that stage, the writes into it, which
     // belong to the stage after, follow that barrier.
     v8h fa[2][4], fb[2][4];
